@@ -1,0 +1,159 @@
+/*
+ * nm_conv.h -- C ABI of libnmconv: 2-D convolution with column-wise,
+ * tile-level N:M pruned weights on one MI355X (gfx950).
+ *
+ * The operations follow the paper "Efficient Column-Wise N:M Pruning on
+ * RISC-V CPU": column-wise N:M pruning with L1-norm importance (section 3.1,
+ * Fig. 3c), the compressed weight + index array (section 2.1, inputs of
+ * Alg. 1), the tiled contraction over the kept columns (Alg. 1), the fused
+ * im2col + data packing that feeds it (section 3.2, Alg. 2) and the
+ * profile-every-candidate tuning of the kernel parameters (section 3.3).
+ * Bias, ReLU, stride/padding/dilation and bf16 follow their usual definitions.
+ *
+ * Notation: x[B][H][W][Cin] (NHWC); w[Cout][Kh][Kw][Cin] (OHWI) read as the
+ * matrix W[Cout][K], K = Kh*Kw*Cin, k = (kh*Kw + kw)*Cin + ci; T = tile size
+ * (output channels per column tile); G = K/M groups; K' = G*N kept columns
+ * per tile; n_tiles = ceil(Cout/T).
+ *
+ * All functions return NM_OK (0) or a negative nm_status_t; no exception
+ * crosses this boundary.  nm_last_error() returns a thread-local description
+ * of the last failure on the calling thread.  Every function that touches the
+ * GPU uses the calling thread's current HIP device.  Without a usable GPU the
+ * functions that compute return NM_ERR_HIP: there is no CPU fallback.
+ */
+#ifndef NM_CONV_H
+#define NM_CONV_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    NM_OK = 0,
+    NM_ERR_ARG = -1,         /* null pointer, n < 1, n > m, tile < 1, K % m != 0, non-finite weight, ... */
+    NM_ERR_SHAPE = -2,       /* output height or width would be < 1, or a tensor exceeds 2^31 - 1 elements */
+    NM_ERR_UNSUPPORTED = -3, /* no GPU kernel for this tile size / dtype pair / variant id */
+    NM_ERR_ALLOC = -4,       /* host or device allocation failed */
+    NM_ERR_HIP = -5,         /* a HIP call failed (no device, launch failure, ...) */
+    NM_ERR_IO = -6           /* cache file could not be read or written */
+} nm_status_t;
+
+typedef enum { NM_F32 = 0, NM_BF16 = 1 } nm_dtype_t;
+
+/* Packed, pruned weights of one layer.  Opaque, owned by the library, immutable
+ * after creation, bound to the device that was current in nm_prune. */
+typedef struct nm_packed nm_packed_t;
+
+const char* nm_last_error(void);
+
+/* Number of kernel variants the tuner chooses from (ids 0 .. count-1), and a
+ * short static description of one ("BP128 NJ2 CK32").  NULL for a bad id. */
+int nm_variant_count(void);
+const char* nm_variant_name(int variant);
+
+/*
+ * nm_prune -- column-wise N:M pruning (section 3.1) and packing (section 2.1).
+ *
+ * For every tile j of `tile` consecutive output channels (the last tile may be
+ * shorter) and every group g of m consecutive k, the L1 norm of each column
+ * over the tile's existing rows is accumulated in fp64 in ascending row order;
+ * the n columns with the largest norm are kept, the lower k winning among
+ * equal norms; exactly n are kept even if a kept column is all zero.  Kept
+ * values are compacted to vals[j][g*n + i][t] (zero for rows beyond Cout) and
+ * the kept absolute k stored ascending in idx[j][g][i].  n == m keeps
+ * everything (dense layer).  Selection, compaction and the repacking into the
+ * kernels' operand order all run on the GPU.
+ *
+ *   w_ohwi_host  host pointer, [cout][kh][kw][cin] fp32, caller-owned, only read
+ *   value_dtype  NM_F32: values kept as fp32.  NM_BF16: kept values are rounded
+ *                to bf16 (nearest even) after selection; selection itself
+ *                always uses the fp32 weights
+ *   out          receives the handle; free it with nm_packed_free
+ *
+ * Errors: NM_ERR_ARG (null, sizes < 1, n > m, (kh*kw*cin) % m != 0, m > 16384,
+ * a NaN or infinite weight), NM_ERR_ALLOC, NM_ERR_HIP.  Synchronous.
+ */
+int nm_prune(const float* w_ohwi_host, int cout, int kh, int kw, int cin,
+             int n, int m, int tile, nm_dtype_t value_dtype, nm_packed_t** out);
+
+int nm_packed_free(nm_packed_t* wp);
+
+/* Sizes of the canonical exports below.  Any out pointer may be NULL. */
+int nm_packed_dims(const nm_packed_t* wp, int* n_tiles, int* groups, int* n, int* kprime);
+
+/* Canonical exports into caller-allocated host buffers (for checking and for
+ * saving pruned weights):
+ *   idx  [n_tiles][groups][n] int32, absolute k, ascending
+ *   vals [n_tiles][kprime][tile] fp32 (bf16 handles: the rounded values, widened)
+ *   mask [cout][K] uint8, 1 = kept                                            */
+int nm_packed_indices(const nm_packed_t* wp, int32_t* idx_host);
+int nm_packed_values(const nm_packed_t* wp, float* vals_host);
+int nm_packed_mask(const nm_packed_t* wp, uint8_t* mask_host);
+
+/*
+ * nm_conv2d -- y = relu?( conv(x, W_pruned) + bias ), computed as the
+ * contraction of Alg. 1 over the kept columns only:
+ *   y[p][j*T + t] = sum_{kk < K'} A[idx[j][kk]][p] * vals[j][kk][t] + bias
+ * where A[k][p] is the im2col matrix of section 2.2 (zero outside the image),
+ * p = (b*Hout + ho)*Wout + wo.  A is never written to memory: its kept rows
+ * are gathered from x into on-chip storage inside the kernel (the fused
+ * im2col + packing of section 3.2).
+ *
+ *   x_dev     device pointer, NHWC [b][h][w][cin] of x_dtype, 16-byte aligned,
+ *             caller-owned, only read
+ *   wp        handle from nm_prune on the same device; its cin must equal cin
+ *   bias_dev  device pointer [cout] fp32, or NULL
+ *   relu      0 or 1
+ *   y_dev     device pointer, NHWC [b][hout][wout][cout] of y_dtype, 16-byte
+ *             aligned, caller-allocated, fully overwritten,
+ *             hout = (h + 2*pad_h - dil_h*(kh-1) - 1)/stride_h + 1 (same for w)
+ *   hip_stream  hipStream_t (NULL = default stream)
+ *
+ * fp32 inputs are multiplied in fp32 on the matrix cores with fp32
+ * accumulation; bf16 inputs are multiplied exactly and accumulated in fp32;
+ * bf16 outputs are rounded to nearest even once.  The call only enqueues work
+ * on the stream and never synchronises.  The kernel variant is the one
+ * nm_autotune cached for this shape, else nm_force_variant's, else a
+ * deterministic default.  Errors: NM_ERR_ARG, NM_ERR_SHAPE, NM_ERR_UNSUPPORTED,
+ * NM_ERR_HIP.
+ */
+int nm_conv2d(const void* x_dev, nm_dtype_t x_dtype, int b, int h, int w, int cin,
+              const nm_packed_t* wp, const float* bias_dev,
+              int stride_h, int stride_w, int pad_h, int pad_w, int dil_h, int dil_w,
+              int relu, void* y_dev, nm_dtype_t y_dtype, void* hip_stream);
+
+/*
+ * nm_autotune -- per-layer choice of the fastest kernel variant (section 3.3:
+ * every candidate is run on the target and the fastest kept).  Runs each legal
+ * variant for this shape on library-allocated scratch tensors (pseudo-random
+ * input), times it with HIP events on `hip_stream`, stores the winner in the
+ * process-wide cache keyed by (shape, N:M, T, dtypes) and returns it.
+ * Synchronous.  A cached shape returns immediately with the cached result.
+ *   chosen_variant, best_ms   may be NULL
+ */
+int nm_autotune(nm_dtype_t x_dtype, int b, int h, int w, int cin,
+                const nm_packed_t* wp, int has_bias,
+                int stride_h, int stride_w, int pad_h, int pad_w, int dil_h, int dil_w,
+                int relu, nm_dtype_t y_dtype, void* hip_stream,
+                int* chosen_variant, float* best_ms);
+
+/* Tuning cache: text file, one line per shape.  Loading merges into the cache. */
+int nm_cache_save(const char* path);
+int nm_cache_load(const char* path);
+int nm_cache_clear(void);
+int nm_cache_size(void);
+
+/* Test hook: variant >= 0 makes every nm_conv2d use that variant (an illegal
+ * one for a shape gives NM_ERR_UNSUPPORTED); -1 restores the normal choice. */
+int nm_force_variant(int variant_or_minus1);
+
+/* Whether `variant` can run this layer (1), cannot (0), or bad arguments (<0). */
+int nm_variant_legal(int variant, const nm_packed_t* wp, nm_dtype_t x_dtype, nm_dtype_t y_dtype);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* NM_CONV_H */

@@ -1,0 +1,94 @@
+"""Build libnmconv.so (HIP, gfx950 only) in-tree with hipcc.
+
+    python -m paper_2507_17301_amd.build [-j N] [--force]
+
+Objects go to ``_build/`` at the repository root (never committed); the shared
+library is written next to this file so that it travels with the tree.
+"""
+from __future__ import annotations
+
+import argparse
+import os
+import re
+import subprocess
+import sys
+from concurrent.futures import ThreadPoolExecutor
+
+PKG = os.path.dirname(os.path.abspath(__file__))
+ROOT = os.path.dirname(PKG)
+CSRC = os.path.join(PKG, "csrc")
+INCLUDE = os.path.join(ROOT, "include")
+OBJDIR = os.path.join(ROOT, "_build")
+LIB = os.path.join(PKG, "libnmconv.so")
+
+HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+FLAGS = [
+    "-O3", "--offload-arch=gfx950", "-fPIC", "-std=c++17", "-Wall", "-Wno-unused-function",
+    # the compiler must not form packed fp32 instructions on this target
+    "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+    "-I", INCLUDE, "-I", CSRC,
+]
+
+
+def _shapes():
+    """(BP, WP, NJ) triples of NM_SHAPES in nm_variants.h."""
+    text = open(os.path.join(CSRC, "nm_variants.h")).read()
+    body = text[text.index("#define NM_SHAPES(X)"):]
+    body = body[:body.index("\n\n")]
+    return [tuple(int(v) for v in m) for m in re.findall(r"X\((\d+),\s*(\d+),\s*(\d+)\)", body)]
+
+
+def _jobs():
+    jobs = []
+    for src in ("nm_api.hip", "nm_prune_kernels.hip", "nm_conv_registry.hip"):
+        jobs.append((os.path.join(CSRC, src), os.path.join(OBJDIR, src.replace(".hip", ".o")), []))
+    inst = os.path.join(CSRC, "nm_conv_inst.hip")
+    for bp, wp, nj in _shapes():
+        jobs.append((inst, os.path.join(OBJDIR, f"nm_conv_inst_{bp}_{wp}_{nj}.o"),
+                     [f"-DNM_INST_BP={bp}", f"-DNM_INST_WP={wp}", f"-DNM_INST_NJ={nj}"]))
+    jobs.append((inst, os.path.join(OBJDIR, "nm_conv_inst_scalar.o"), ["-DNM_INST_SCALAR"]))
+    return jobs
+
+
+def _newest_header():
+    hs = [os.path.join(CSRC, f) for f in os.listdir(CSRC) if f.endswith(".h")]
+    hs += [os.path.join(INCLUDE, f) for f in os.listdir(INCLUDE) if f.endswith(".h")]
+    return max(os.path.getmtime(h) for h in hs)
+
+
+def _compile(job, force, hdr_time):
+    src, obj, defs = job
+    if (not force and os.path.exists(obj)
+            and os.path.getmtime(obj) >= max(os.path.getmtime(src), hdr_time)):
+        return obj
+    cmd = [HIPCC] + FLAGS + defs + ["-c", src, "-o", obj]
+    r = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
+    if r.returncode != 0:
+        raise RuntimeError("hipcc failed:\n" + " ".join(cmd) + "\n" + r.stdout)
+    warn = [l for l in r.stdout.splitlines() if "packed-fp32-ops" not in l and l.strip()]
+    if any("warning" in l for l in warn):
+        sys.stderr.write("\n".join(warn) + "\n")
+    return obj
+
+
+def build(jobs: int = 8, force: bool = True) -> str:
+    """Compile every translation unit and link libnmconv.so.  With force=False
+    only out-of-date objects are rebuilt."""
+    os.makedirs(OBJDIR, exist_ok=True)
+    hdr_time = _newest_header()
+    todo = _jobs()
+    with ThreadPoolExecutor(max_workers=max(1, jobs)) as ex:
+        objs = list(ex.map(lambda j: _compile(j, force, hdr_time), todo))
+    cmd = [HIPCC, "-shared", "-fPIC", "--offload-arch=gfx950", "-o", LIB] + objs
+    r = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
+    if r.returncode != 0:
+        raise RuntimeError("link failed:\n" + r.stdout)
+    return LIB
+
+
+if __name__ == "__main__":
+    ap = argparse.ArgumentParser()
+    ap.add_argument("-j", type=int, default=min(8, os.cpu_count() or 1))
+    ap.add_argument("--incremental", action="store_true", help="rebuild only stale objects")
+    a = ap.parse_args()
+    print(build(a.j, force=not a.incremental))

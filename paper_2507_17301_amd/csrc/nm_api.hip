@@ -1,0 +1,661 @@
+// C ABI of libnmconv: argument checking, the packed-weights handle, variant
+// choice, the tuning cache and the profiler-driven tuner.  All arithmetic of
+// the method runs in the kernels; this file only plans and launches.
+#include <math.h>
+#include <stdarg.h>
+#include <stdio.h>
+#include <string.h>
+
+#include <algorithm>
+#include <mutex>
+
+#include "nm_internal.h"
+
+namespace nm {
+
+static thread_local char g_err[512] = "";
+
+void set_error(const char* fmt, ...)
+{
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof(g_err), fmt, ap);
+    va_end(ap);
+}
+
+namespace {
+
+constexpr int kMaxLdsBytes = 160 * 1024;
+constexpr int kNumCU = 256;
+
+struct ShapeKey {
+    int v[21];
+    bool operator<(const ShapeKey& o) const { return memcmp(v, o.v, sizeof(v)) < 0; }
+};
+struct CacheVal {
+    int variant;
+    float ms;
+};
+
+std::mutex g_mu;
+std::map<ShapeKey, CacheVal> g_cache;
+int g_forced = -1;
+
+ShapeKey make_key(nm_dtype_t xdt, nm_dtype_t ydt, int b, int h, int w, const nm_packed* wp,
+                  int sh, int sw, int ph, int pw, int dh, int dw)
+{
+    ShapeKey k;
+    const int vals[21] = {(int)xdt, (int)ydt, b, h, w, wp->cin, wp->cout, wp->kh, wp->kw,
+                          sh, sw, ph, pw, dh, dw, wp->n, wp->m, wp->tile, (int)wp->value_dtype, 0, 0};
+    memcpy(k.v, vals, sizeof(vals));
+    return k;
+}
+
+size_t lds_bytes(const VariantDesc& d) { return (size_t)2 * d.CK * (d.BP + 4) * sizeof(float); }
+
+const Prepack* find_prepack(const nm_packed* wp, const VariantDesc& d)
+{
+    for (const Prepack& pp : wp->prepacks)
+        if (pp.geom.CK == d.CK && pp.geom.vec == d.vec && pp.SPC == d.SPC) return &pp;
+    return nullptr;
+}
+
+bool variant_legal(int v, const nm_packed* wp)
+{
+    if (v < 0 || v >= variant_count()) return false;
+    const VariantDesc& d = variant_desc(v);
+    if (lds_bytes(d) > (size_t)kMaxLdsBytes) return false;
+    return find_prepack(wp, d) != nullptr;
+}
+
+// Largest number of kept columns any (tile, chunk) pair holds.
+int max_kept_per_chunk(const nm_packed* wp, const ChunkGeom& g)
+{
+    std::vector<int> cnt(g.nchunks);
+    int best = 0;
+    for (int j = 0; j < wp->n_tiles; ++j) {
+        std::fill(cnt.begin(), cnt.end(), 0);
+        for (int kk = 0; kk < wp->kprime; ++kk) {
+            const int k = wp->h_idx[(size_t)j * wp->kprime + kk];
+            int c;
+            if (g.vec) {
+                const int tap = k / wp->cin, ci = k - tap * wp->cin;
+                c = tap * g.ncpt + ci / g.CK;
+            } else {
+                c = k / g.CK;
+            }
+            best = std::max(best, ++cnt[c]);
+        }
+    }
+    return best;
+}
+
+struct Geometry {
+    int Ho, Wo, P;
+};
+
+int conv_geometry(int b, int h, int w, const nm_packed* wp, int sh, int sw, int ph, int pw, int dh,
+                  int dw, Geometry* g)
+{
+    if (b < 1 || h < 1 || w < 1 || sh < 1 || sw < 1 || ph < 0 || pw < 0 || dh < 1 || dw < 1) {
+        set_error("bad convolution arguments (sizes, stride, dilation must be >= 1, padding >= 0)");
+        return NM_ERR_ARG;
+    }
+    const long eh = (long)h + 2L * ph - (long)dh * (wp->kh - 1) - 1;
+    const long ew = (long)w + 2L * pw - (long)dw * (wp->kw - 1) - 1;
+    if (eh < 0 || ew < 0) {
+        set_error("output would be empty: input %dx%d, kernel %dx%d, pad %d,%d, dilation %d,%d", h, w,
+                  wp->kh, wp->kw, ph, pw, dh, dw);
+        return NM_ERR_SHAPE;
+    }
+    g->Ho = (int)(eh / sh) + 1;
+    g->Wo = (int)(ew / sw) + 1;
+    const long long P = (long long)b * g->Ho * g->Wo;
+    const long long xin = (long long)b * h * w * wp->cin;
+    const long long yout = P * wp->cout;
+    if (P > 0x7fffffffLL - 1024 || xin > 0x7fffffffLL || yout > 0x7fffffffLL) {
+        set_error("tensor too large: more than 2^31 - 1 elements");
+        return NM_ERR_SHAPE;
+    }
+    g->P = (int)P;
+    return NM_OK;
+}
+
+void fill_params(ConvParams& p, const VariantDesc& d, const Prepack& pp, const nm_packed* wp,
+                 const void* x, void* y, const float* bias, int b, int h, int w, const Geometry& g,
+                 int sh, int sw, int ph, int pw, int dh, int dw, int relu)
+{
+    p.x = x; p.y = y; p.bias = bias;
+    p.wfrag = pp.d_wfrag; p.rows = pp.d_rows;
+    p.B = b; p.H = h; p.W = w; p.Cin = wp->cin; p.Cout = wp->cout; p.Kh = wp->kh; p.Kw = wp->kw;
+    p.Ho = g.Ho; p.Wo = g.Wo;
+    p.sh = sh; p.sw = sw; p.ph = ph; p.pw = pw; p.dh = dh; p.dw = dw;
+    p.relu = relu ? 1 : 0;
+    p.P = g.P; p.K = wp->K;
+    p.nchunks = pp.geom.nchunks; p.ncpt = pp.geom.ncpt;
+    p.tile = wp->tile; p.rbpt = wp->rbpt; p.n_rowblocks = wp->n_rowblocks;
+    const int rb_per_wg = (4 / d.WP) * d.NJ;
+    p.n_ptiles = (g.P + d.BP - 1) / d.BP;
+    p.n_cblocks = (wp->n_rowblocks + rb_per_wg - 1) / rb_per_wg;
+    p.n_wg = p.n_ptiles * p.n_cblocks;
+    p.wg_per_xcd = (p.n_wg + 7) / 8;
+}
+
+// Deterministic default when the shape has not been tuned: a small model of
+// "rounds of workgroups x work per workgroup", preferring tiles that fill the
+// 256 CUs and reuse the staged strip across many row blocks.
+int heuristic_variant(const nm_packed* wp, int P)
+{
+    int best = -1;
+    double best_cost = 0;
+    for (int v = 0; v < variant_count(); ++v) {
+        if (!variant_legal(v, wp)) continue;
+        const VariantDesc& d = variant_desc(v);
+        const int rb_per_wg = (4 / d.WP) * d.NJ;
+        const long n_pt = (P + d.BP - 1) / d.BP;
+        const long n_cb = (wp->n_rowblocks + rb_per_wg - 1) / rb_per_wg;
+        const long n_wg = n_pt * n_cb;
+        int occ = (int)std::min<size_t>(2, kMaxLdsBytes / lds_bytes(d));
+        if (occ < 1) occ = 1;
+        const long rounds = (n_wg + (long)kNumCU * occ - 1) / ((long)kNumCU * occ);
+        const double mfma = (double)d.BP * rb_per_wg;            // per chunk step, relative
+        const double stage = (double)d.BP * 2.0;                 // staging cost per chunk, relative
+        const double cost = (double)rounds * occ * (mfma + stage);
+        if (best < 0 || cost < best_cost * 0.999) {
+            best = v;
+            best_cost = cost;
+        }
+    }
+    return best;
+}
+
+int check_conv_args(const void* x, nm_dtype_t xdt, int cin, const nm_packed* wp, void* y,
+                    nm_dtype_t ydt)
+{
+    if (!wp || !x || !y) {
+        set_error("null pointer argument");
+        return NM_ERR_ARG;
+    }
+    if (cin != wp->cin) {
+        set_error("cin %d does not match the packed weights (%d)", cin, wp->cin);
+        return NM_ERR_ARG;
+    }
+    if ((xdt != NM_F32 && xdt != NM_BF16) || (ydt != NM_F32 && ydt != NM_BF16)) {
+        set_error("unknown dtype");
+        return NM_ERR_ARG;
+    }
+    if (xdt != ydt) {
+        set_error("unsupported dtype pair: input and output must both be fp32 or both bf16");
+        return NM_ERR_UNSUPPORTED;
+    }
+    const size_t align = xdt == NM_F32 ? 16 : 8;
+    if (((uintptr_t)x % align) || ((uintptr_t)y % align)) {
+        set_error("x and y must be 16-byte aligned");
+        return NM_ERR_ARG;
+    }
+    int dev = -1;
+    NM_HIP_CHECK(hipGetDevice(&dev));
+    if (dev != wp->device) {
+        set_error("packed weights live on device %d, current device is %d", wp->device, dev);
+        return NM_ERR_ARG;
+    }
+    return NM_OK;
+}
+
+void free_packed(nm_packed* wp)
+{
+    if (!wp) return;
+    (void)hipFree(wp->d_idx);
+    (void)hipFree(wp->d_vals);
+    for (Prepack& pp : wp->prepacks) {
+        (void)hipFree(pp.d_rows);
+        (void)hipFree(pp.d_wfrag);
+    }
+    delete wp;
+}
+
+}  // namespace
+}  // namespace nm
+
+using namespace nm;
+
+extern "C" {
+
+const char* nm_last_error(void) { return g_err; }
+
+int nm_variant_count(void) { return variant_count(); }
+
+const char* nm_variant_name(int variant)
+{
+    if (variant < 0 || variant >= variant_count()) return nullptr;
+    return variant_desc(variant).name;
+}
+
+int nm_prune(const float* w, int cout, int kh, int kw, int cin, int n, int m, int tile,
+             nm_dtype_t value_dtype, nm_packed_t** out)
+{
+    if (!w || !out) {
+        set_error("null pointer argument");
+        return NM_ERR_ARG;
+    }
+    *out = nullptr;
+    if (cout < 1 || kh < 1 || kw < 1 || cin < 1 || n < 1 || m < 1 || tile < 1 || n > m) {
+        set_error("bad sizes: cout %d kh %d kw %d cin %d n %d m %d tile %d", cout, kh, kw, cin, n, m, tile);
+        return NM_ERR_ARG;
+    }
+    if (value_dtype != NM_F32 && value_dtype != NM_BF16) {
+        set_error("unknown value dtype");
+        return NM_ERR_ARG;
+    }
+    const long long K = (long long)kh * kw * cin;
+    if (K % m != 0) {
+        set_error("K = %lld is not a multiple of m = %d", K, m);
+        return NM_ERR_ARG;
+    }
+    if (m > 16384) {
+        set_error("m = %d exceeds the supported group size 16384", m);
+        return NM_ERR_ARG;
+    }
+    if (K * cout > 0x7fffffffLL) {
+        set_error("weight tensor too large");
+        return NM_ERR_ARG;
+    }
+    const size_t nw = (size_t)cout * K;
+    for (size_t i = 0; i < nw; ++i)
+        if (!isfinite(w[i])) {
+            set_error("weight %zu is not finite", i);
+            return NM_ERR_ARG;
+        }
+
+    nm_packed* wp = new (std::nothrow) nm_packed();
+    if (!wp) {
+        set_error("out of host memory");
+        return NM_ERR_ALLOC;
+    }
+    wp->cout = cout; wp->kh = kh; wp->kw = kw; wp->cin = cin; wp->K = (int)K;
+    wp->n = n; wp->m = m; wp->tile = tile;
+    wp->G = (int)(K / m); wp->kprime = wp->G * n; wp->n_tiles = (cout + tile - 1) / tile;
+    wp->rbpt = (tile + 15) / 16; wp->n_rowblocks = wp->n_tiles * wp->rbpt;
+    wp->value_dtype = value_dtype;
+
+    float* d_w = nullptr;
+    int rc = NM_OK;
+    hipStream_t s = nullptr;
+    auto fail = [&](int code) {
+        (void)hipFree(d_w);
+        free_packed(wp);
+        return code;
+    };
+#define NM_TRY_HIP(expr, code)                                                             \
+    do {                                                                                   \
+        hipError_t e__ = (expr);                                                           \
+        if (e__ != hipSuccess) {                                                           \
+            set_error("%s failed: %s", #expr, hipGetErrorString(e__));                     \
+            return fail(code);                                                             \
+        }                                                                                  \
+    } while (0)
+
+    NM_TRY_HIP(hipGetDevice(&wp->device), NM_ERR_HIP);
+    NM_TRY_HIP(hipMalloc(&d_w, nw * sizeof(float)), NM_ERR_ALLOC);
+    NM_TRY_HIP(hipMalloc(&wp->d_idx, (size_t)wp->n_tiles * wp->kprime * sizeof(int32_t)), NM_ERR_ALLOC);
+    NM_TRY_HIP(hipMalloc(&wp->d_vals, (size_t)wp->n_tiles * wp->kprime * tile * sizeof(float)), NM_ERR_ALLOC);
+    NM_TRY_HIP(hipMemcpyAsync(d_w, w, nw * sizeof(float), hipMemcpyHostToDevice, s), NM_ERR_HIP);
+    rc = run_prune(d_w, wp, s);
+    if (rc != NM_OK) return fail(rc);
+    wp->h_idx.resize((size_t)wp->n_tiles * wp->kprime);
+    NM_TRY_HIP(hipMemcpyAsync(wp->h_idx.data(), wp->d_idx, wp->h_idx.size() * sizeof(int32_t),
+                              hipMemcpyDeviceToHost, s), NM_ERR_HIP);
+    NM_TRY_HIP(hipStreamSynchronize(s), NM_ERR_HIP);
+
+    // Operand tables for every chunk geometry a kernel variant may ask for.
+    const bool vec_ok = cin % 4 == 0;
+    for (int v = 0; v < variant_count(); ++v) {
+        const VariantDesc& d = variant_desc(v);
+        if ((d.vec != 0) != vec_ok) continue;
+        if (find_prepack(wp, d)) continue;
+        const ChunkGeom g = make_chunk_geom(cin, wp->K, d.CK, d.vec);
+        const int need = (max_kept_per_chunk(wp, g) + 3) / 4;
+        // smallest instantiated SPC >= need for this (CK, vec)
+        int pick = 0;
+        for (int u = 0; u < variant_count(); ++u) {
+            const VariantDesc& e = variant_desc(u);
+            if (e.CK == d.CK && e.vec == d.vec && e.SPC >= need && (pick == 0 || e.SPC < pick))
+                pick = e.SPC;
+        }
+        if (pick == 0 || pick != d.SPC) continue;
+        Prepack pp;
+        pp.geom = g;
+        pp.SPC = d.SPC;
+        pp.ROWB = d.SPC < 4 ? 4 : d.SPC;
+        const size_t rows_bytes = (size_t)wp->n_tiles * g.nchunks * 4 * pp.ROWB;
+        const size_t wf_bytes = (size_t)wp->n_rowblocks * g.nchunks * 64 * pp.SPC * sizeof(float);
+        NM_TRY_HIP(hipMalloc(&pp.d_rows, rows_bytes), NM_ERR_ALLOC);
+        wp->prepacks.push_back(pp);   // owned by the handle from here on
+        Prepack& ref = wp->prepacks.back();
+        NM_TRY_HIP(hipMalloc(&ref.d_wfrag, wf_bytes), NM_ERR_ALLOC);
+        NM_TRY_HIP(hipMemsetAsync(ref.d_rows, 0, rows_bytes, s), NM_ERR_HIP);
+        NM_TRY_HIP(hipMemsetAsync(ref.d_wfrag, 0, wf_bytes, s), NM_ERR_HIP);
+        rc = run_build_prepack(wp, ref, s);
+        if (rc != NM_OK) return fail(rc);
+    }
+#undef NM_TRY_HIP
+    (void)hipFree(d_w);
+    if (wp->prepacks.empty()) {
+        set_error("no kernel variant can run this layer (cin %d, n:m %d:%d, tile %d)", cin, n, m, tile);
+        free_packed(wp);
+        return NM_ERR_UNSUPPORTED;
+    }
+    *out = wp;
+    return NM_OK;
+}
+
+int nm_packed_free(nm_packed_t* wp)
+{
+    free_packed(wp);
+    return NM_OK;
+}
+
+int nm_packed_dims(const nm_packed_t* wp, int* n_tiles, int* groups, int* n, int* kprime)
+{
+    if (!wp) {
+        set_error("null handle");
+        return NM_ERR_ARG;
+    }
+    if (n_tiles) *n_tiles = wp->n_tiles;
+    if (groups) *groups = wp->G;
+    if (n) *n = wp->n;
+    if (kprime) *kprime = wp->kprime;
+    return NM_OK;
+}
+
+int nm_packed_indices(const nm_packed_t* wp, int32_t* idx_host)
+{
+    if (!wp || !idx_host) {
+        set_error("null pointer argument");
+        return NM_ERR_ARG;
+    }
+    NM_HIP_CHECK(hipMemcpy(idx_host, wp->d_idx, (size_t)wp->n_tiles * wp->kprime * sizeof(int32_t),
+                           hipMemcpyDeviceToHost));
+    return NM_OK;
+}
+
+int nm_packed_values(const nm_packed_t* wp, float* vals_host)
+{
+    if (!wp || !vals_host) {
+        set_error("null pointer argument");
+        return NM_ERR_ARG;
+    }
+    NM_HIP_CHECK(hipMemcpy(vals_host, wp->d_vals,
+                           (size_t)wp->n_tiles * wp->kprime * wp->tile * sizeof(float),
+                           hipMemcpyDeviceToHost));
+    return NM_OK;
+}
+
+int nm_packed_mask(const nm_packed_t* wp, uint8_t* mask_host)
+{
+    if (!wp || !mask_host) {
+        set_error("null pointer argument");
+        return NM_ERR_ARG;
+    }
+    uint8_t* d_mask = nullptr;
+    const size_t bytes = (size_t)wp->cout * wp->K;
+    hipError_t e = hipMalloc(&d_mask, bytes);
+    if (e != hipSuccess) {
+        set_error("hipMalloc(%zu) failed: %s", bytes, hipGetErrorString(e));
+        return NM_ERR_ALLOC;
+    }
+    int rc = run_build_mask(wp, d_mask, nullptr);
+    if (rc == NM_OK) {
+        e = hipMemcpy(mask_host, d_mask, bytes, hipMemcpyDeviceToHost);
+        if (e != hipSuccess) {
+            set_error("hipMemcpy failed: %s", hipGetErrorString(e));
+            rc = NM_ERR_HIP;
+        }
+    }
+    (void)hipFree(d_mask);
+    return rc;
+}
+
+int nm_force_variant(int v)
+{
+    if (v < -1 || v >= variant_count()) {
+        set_error("variant %d out of range", v);
+        return NM_ERR_ARG;
+    }
+    std::lock_guard<std::mutex> lk(g_mu);
+    g_forced = v;
+    return NM_OK;
+}
+
+int nm_variant_legal(int variant, const nm_packed_t* wp, nm_dtype_t xdt, nm_dtype_t ydt)
+{
+    if (!wp || variant < 0 || variant >= variant_count()) {
+        set_error("bad arguments");
+        return NM_ERR_ARG;
+    }
+    if (xdt != ydt) return 0;
+    return variant_legal(variant, wp) ? 1 : 0;
+}
+
+int nm_conv2d(const void* x, nm_dtype_t xdt, int b, int h, int w, int cin, const nm_packed_t* wp,
+              const float* bias, int sh, int sw, int ph, int pw, int dh, int dw, int relu, void* y,
+              nm_dtype_t ydt, void* stream)
+{
+    int rc = check_conv_args(x, xdt, cin, wp, y, ydt);
+    if (rc != NM_OK) return rc;
+    Geometry g;
+    rc = conv_geometry(b, h, w, wp, sh, sw, ph, pw, dh, dw, &g);
+    if (rc != NM_OK) return rc;
+
+    int v = -1;
+    {
+        std::lock_guard<std::mutex> lk(g_mu);
+        if (g_forced >= 0) {
+            v = g_forced;
+        } else {
+            auto it = g_cache.find(make_key(xdt, ydt, b, h, w, wp, sh, sw, ph, pw, dh, dw));
+            if (it != g_cache.end()) v = it->second.variant;
+        }
+    }
+    if (v >= 0 && !variant_legal(v, wp)) {
+        if (g_forced >= 0) {
+            set_error("variant %d (%s) cannot run this layer", v, nm_variant_name(v));
+            return NM_ERR_UNSUPPORTED;
+        }
+        v = -1;   // stale cache entry: fall back to the default
+    }
+    if (v < 0) v = heuristic_variant(wp, g.P);
+    if (v < 0) {
+        set_error("no kernel variant can run this layer");
+        return NM_ERR_UNSUPPORTED;
+    }
+    const VariantDesc& d = variant_desc(v);
+    ConvParams p;
+    fill_params(p, d, *find_prepack(wp, d), wp, x, y, bias, b, h, w, g, sh, sw, ph, pw, dh, dw, relu);
+    return launch_conv(v, xdt, ydt, p, (hipStream_t)stream);
+}
+
+int nm_autotune(nm_dtype_t xdt, int b, int h, int w, int cin, const nm_packed_t* wp, int has_bias,
+                int sh, int sw, int ph, int pw, int dh, int dw, int relu, nm_dtype_t ydt,
+                void* stream, int* chosen, float* best_ms)
+{
+    if (!wp) {
+        set_error("null handle");
+        return NM_ERR_ARG;
+    }
+    if (cin != wp->cin) {
+        set_error("cin %d does not match the packed weights (%d)", cin, wp->cin);
+        return NM_ERR_ARG;
+    }
+    if (xdt != ydt || (xdt != NM_F32 && xdt != NM_BF16)) {
+        set_error("unsupported dtype pair: input and output must both be fp32 or both bf16");
+        return NM_ERR_UNSUPPORTED;
+    }
+    Geometry g;
+    int rc = conv_geometry(b, h, w, wp, sh, sw, ph, pw, dh, dw, &g);
+    if (rc != NM_OK) return rc;
+    const ShapeKey key = make_key(xdt, ydt, b, h, w, wp, sh, sw, ph, pw, dh, dw);
+    {
+        std::lock_guard<std::mutex> lk(g_mu);
+        auto it = g_cache.find(key);
+        if (it != g_cache.end() && variant_legal(it->second.variant, wp)) {
+            if (chosen) *chosen = it->second.variant;
+            if (best_ms) *best_ms = it->second.ms;
+            return NM_OK;
+        }
+    }
+    hipStream_t s = (hipStream_t)stream;
+    const size_t es = xdt == NM_F32 ? 4 : 2;
+    const size_t xn = (size_t)b * h * w * cin, yn = (size_t)g.P * wp->cout;
+    void *dx = nullptr, *dy = nullptr;
+    float* dbias = nullptr;
+    hipEvent_t e0 = nullptr, e1 = nullptr;
+    auto cleanup = [&]() {
+        (void)hipFree(dx); (void)hipFree(dy); (void)hipFree(dbias);
+        if (e0) (void)hipEventDestroy(e0);
+        if (e1) (void)hipEventDestroy(e1);
+    };
+#define NM_TRY(expr, code)                                                       \
+    do {                                                                         \
+        hipError_t e__ = (expr);                                                 \
+        if (e__ != hipSuccess) {                                                 \
+            set_error("%s failed: %s", #expr, hipGetErrorString(e__));           \
+            cleanup();                                                           \
+            return code;                                                         \
+        }                                                                        \
+    } while (0)
+    NM_TRY(hipMalloc(&dx, xn * es), NM_ERR_ALLOC);
+    NM_TRY(hipMalloc(&dy, yn * es), NM_ERR_ALLOC);
+    if (has_bias) {
+        NM_TRY(hipMalloc(&dbias, wp->cout * sizeof(float)), NM_ERR_ALLOC);
+        rc = run_fill_random(dbias, wp->cout, NM_F32, 7u, s);
+        if (rc != NM_OK) { cleanup(); return rc; }
+    }
+    rc = run_fill_random(dx, xn, xdt, 1u, s);
+    if (rc != NM_OK) { cleanup(); return rc; }
+    NM_TRY(hipEventCreate(&e0), NM_ERR_HIP);
+    NM_TRY(hipEventCreate(&e1), NM_ERR_HIP);
+
+    int best_v = -1;
+    float best = 0.f;
+    for (int v = 0; v < variant_count(); ++v) {
+        if (!variant_legal(v, wp)) continue;
+        const VariantDesc& d = variant_desc(v);
+        ConvParams p;
+        fill_params(p, d, *find_prepack(wp, d), wp, dx, dy, dbias, b, h, w, g, sh, sw, ph, pw, dh, dw, relu);
+        // warm-up, then the median of 5 timed groups
+        rc = launch_conv(v, xdt, ydt, p, s);
+        if (rc != NM_OK) { cleanup(); return rc; }
+        NM_TRY(hipStreamSynchronize(s), NM_ERR_HIP);
+        float t[5];
+        const int reps = 3;
+        for (int r = 0; r < 5; ++r) {
+            NM_TRY(hipEventRecord(e0, s), NM_ERR_HIP);
+            for (int i = 0; i < reps; ++i) {
+                rc = launch_conv(v, xdt, ydt, p, s);
+                if (rc != NM_OK) { cleanup(); return rc; }
+            }
+            NM_TRY(hipEventRecord(e1, s), NM_ERR_HIP);
+            NM_TRY(hipEventSynchronize(e1), NM_ERR_HIP);
+            NM_TRY(hipEventElapsedTime(&t[r], e0, e1), NM_ERR_HIP);
+            t[r] /= reps;
+        }
+        std::sort(t, t + 5);
+        if (best_v < 0 || t[2] < best) {
+            best_v = v;
+            best = t[2];
+        }
+    }
+#undef NM_TRY
+    cleanup();
+    if (best_v < 0) {
+        set_error("no kernel variant can run this layer");
+        return NM_ERR_UNSUPPORTED;
+    }
+    {
+        std::lock_guard<std::mutex> lk(g_mu);
+        g_cache[key] = CacheVal{best_v, best};
+    }
+    if (chosen) *chosen = best_v;
+    if (best_ms) *best_ms = best;
+    return NM_OK;
+}
+
+int nm_cache_clear(void)
+{
+    std::lock_guard<std::mutex> lk(g_mu);
+    g_cache.clear();
+    return NM_OK;
+}
+
+int nm_cache_size(void)
+{
+    std::lock_guard<std::mutex> lk(g_mu);
+    return (int)g_cache.size();
+}
+
+// File format: first line "nmconv-cache 1 <variant count>", then one line per
+// shape: the 21 key integers, the variant's name, its time in ms.  Variants are
+// stored by name so that a cache written by a build with a different variant
+// table cannot select the wrong kernel.
+int nm_cache_save(const char* path)
+{
+    if (!path) {
+        set_error("null path");
+        return NM_ERR_ARG;
+    }
+    FILE* f = fopen(path, "w");
+    if (!f) {
+        set_error("cannot open %s for writing", path);
+        return NM_ERR_IO;
+    }
+    std::lock_guard<std::mutex> lk(g_mu);
+    fprintf(f, "nmconv-cache 1 %d\n", variant_count());
+    for (const auto& kv : g_cache) {
+        for (int i = 0; i < 21; ++i) fprintf(f, "%d ", kv.first.v[i]);
+        fprintf(f, "%s %.6f\n", variant_desc(kv.second.variant).name, kv.second.ms);
+    }
+    const bool ok = fclose(f) == 0;
+    if (!ok) {
+        set_error("write to %s failed", path);
+        return NM_ERR_IO;
+    }
+    return NM_OK;
+}
+
+int nm_cache_load(const char* path)
+{
+    if (!path) {
+        set_error("null path");
+        return NM_ERR_ARG;
+    }
+    FILE* f = fopen(path, "r");
+    if (!f) {
+        set_error("cannot open %s", path);
+        return NM_ERR_IO;
+    }
+    int ver = 0, cnt = 0;
+    if (fscanf(f, "nmconv-cache %d %d", &ver, &cnt) != 2 || ver != 1) {
+        fclose(f);
+        set_error("%s is not an nmconv cache file", path);
+        return NM_ERR_IO;
+    }
+    std::lock_guard<std::mutex> lk(g_mu);
+    while (true) {
+        ShapeKey k;
+        bool ok = true;
+        for (int i = 0; i < 21 && ok; ++i) ok = fscanf(f, "%d", &k.v[i]) == 1;
+        char name[128];
+        float ms = 0.f;
+        if (!ok || fscanf(f, "%127s %f", name, &ms) != 2) break;
+        for (int v = 0; v < variant_count(); ++v)
+            if (strcmp(name, variant_desc(v).name) == 0) {
+                g_cache[k] = CacheVal{v, ms};
+                break;
+            }
+    }
+    fclose(f);
+    return NM_OK;
+}
+
+}  // extern "C"

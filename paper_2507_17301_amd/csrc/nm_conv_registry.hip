@@ -1,0 +1,38 @@
+// Table of kernel variants: description + launcher per dtype pair.
+#include "nm_launch_decl.h"
+#include "nm_variants.h"
+
+namespace nm {
+namespace {
+typedef int (*LaunchFn)(const ConvParams&, hipStream_t);
+struct Entry {
+    VariantDesc d;
+    LaunchFn ff;   // fp32 in, fp32 out
+    LaunchFn bb;   // bf16 in, bf16 out
+};
+
+#define NM_ENTRY(BP, WP, NJ, CK, SPC, VEC)                                              \
+    {{"BP" #BP "_WP" #WP "_NJ" #NJ "_CK" #CK "_SPC" #SPC "_V" #VEC, BP, WP, NJ, CK, SPC, VEC}, \
+     &launch_t<BP, WP, NJ, CK, SPC, (VEC) != 0, float, float>,                          \
+     &launch_t<BP, WP, NJ, CK, SPC, (VEC) != 0, bf16_t, bf16_t>},
+#define NM_SHAPE_ENTRIES(BP, WP, NJ) NM_VEC_CHUNKS(NM_ENTRY, BP, WP, NJ)
+
+const Entry kEntries[] = {NM_SHAPES(NM_SHAPE_ENTRIES) NM_SCALAR_VARIANTS(NM_ENTRY)};
+constexpr int kCount = (int)(sizeof(kEntries) / sizeof(kEntries[0]));
+}  // namespace
+
+int variant_count() { return kCount; }
+const VariantDesc& variant_desc(int v) { return kEntries[v].d; }
+
+int launch_conv(int v, nm_dtype_t xdt, nm_dtype_t ydt, const ConvParams& p, hipStream_t s)
+{
+    if (v < 0 || v >= kCount) {
+        set_error("variant %d out of range", v);
+        return NM_ERR_UNSUPPORTED;
+    }
+    if (xdt == NM_F32 && ydt == NM_F32) return kEntries[v].ff(p, s);
+    if (xdt == NM_BF16 && ydt == NM_BF16) return kEntries[v].bb(p, s);
+    set_error("unsupported dtype pair: input and output must both be fp32 or both bf16");
+    return NM_ERR_UNSUPPORTED;
+}
+}  // namespace nm

@@ -1,0 +1,130 @@
+// Internal declarations shared by the translation units of libnmconv.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include <map>
+#include <string>
+#include <vector>
+
+#include "nm_conv.h"
+
+namespace nm {
+
+void set_error(const char* fmt, ...);
+
+#define NM_HIP_CHECK(expr)                                                        \
+    do {                                                                          \
+        hipError_t e__ = (expr);                                                  \
+        if (e__ != hipSuccess) {                                                  \
+            nm::set_error("%s failed: %s (%s:%d)", #expr, hipGetErrorString(e__), \
+                          __FILE__, __LINE__);                                    \
+            return NM_ERR_HIP;                                                    \
+        }                                                                         \
+    } while (0)
+
+// ---------------------------------------------------------------------------
+// K chunking.  The K axis is cut into chunks of at most CK consecutive k; one
+// chunk of the im2col matrix (rows k0 .. k0+len-1, all pixels of the
+// workgroup's pixel tile) is resident in LDS at a time.
+//   vector mode (Cin % 4 == 0): a chunk never crosses a kernel tap, so it is
+//     `len` consecutive input channels of one tap and is fetched with 16-byte
+//     loads.  ncpt = ceil(Cin / CK) chunks per tap.
+//   scalar mode (any Cin): chunks are cut on the flat k axis.
+// ---------------------------------------------------------------------------
+struct ChunkGeom {
+    int vec;      // 1 = vector mode
+    int CK;       // rows per chunk
+    int ncpt;     // chunks per tap (vector mode)
+    int nchunks;  // total
+};
+
+inline ChunkGeom make_chunk_geom(int cin, int K, int CK, int vec)
+{
+    ChunkGeom g;
+    g.vec = vec;
+    g.CK = CK;
+    if (vec) {
+        g.ncpt = (cin + CK - 1) / CK;
+        g.nchunks = (K / cin) * g.ncpt;
+    } else {
+        g.ncpt = 0;
+        g.nchunks = (K + CK - 1) / CK;
+    }
+    return g;
+}
+
+// Operand tables for one chunk geometry (device memory, built once in nm_prune).
+// The contraction of one column tile is cut into k-steps of four kept columns
+// (the K depth of one 16x16x4 MFMA).  Every chunk owns exactly SPC k-steps per
+// tile; the i-th kept column of the chunk is quarter i % 4 of step i / 4, and
+// unused slots carry weight 0 and row 0.
+struct Prepack {
+    ChunkGeom geom{};
+    int SPC = 0;                      // k-steps per chunk (1, 2, 4 or 8)
+    int ROWB = 0;                     // bytes per (tile, chunk, quarter) in d_rows = max(SPC, 4)
+    unsigned char* d_rows = nullptr;  // [n_tiles][nchunks][4][ROWB]  byte s = LDS row (k - k0) used by step s
+    float* d_wfrag = nullptr;         // [n_rowblocks][nchunks][64][SPC]  MFMA A-operand lane values
+};
+
+}  // namespace nm
+
+struct nm_packed {
+    int cout, kh, kw, cin, K;
+    int n, m, tile;
+    int G, kprime, n_tiles;
+    int rbpt;         // 16-row blocks per column tile = ceil(tile / 16)
+    int n_rowblocks;  // n_tiles * rbpt
+    nm_dtype_t value_dtype;
+    int device;
+    int32_t* d_idx = nullptr;   // [n_tiles][kprime]
+    float* d_vals = nullptr;    // [n_tiles][kprime][tile]
+    std::vector<int32_t> h_idx; // host copy of d_idx
+    std::vector<nm::Prepack> prepacks;
+};
+
+namespace nm {
+
+// ---------------------------------------------------------------------------
+// Convolution kernel parameters (passed by value).
+// ---------------------------------------------------------------------------
+struct ConvParams {
+    const void* x;
+    void* y;
+    const float* bias;
+    const float* wfrag;
+    const unsigned char* rows;
+    int B, H, W, Cin, Cout, Kh, Kw, Ho, Wo;
+    int sh, sw, ph, pw, dh, dw;
+    int relu;
+    int P;             // B*Ho*Wo
+    int K;
+    int nchunks, ncpt;
+    int tile, rbpt, n_rowblocks;
+    int n_ptiles, n_cblocks, n_wg;   // pixel tiles, row-block groups, product
+    int wg_per_xcd;
+};
+
+struct VariantDesc {
+    const char* name;
+    int BP;    // pixels per workgroup
+    int WP;    // waves along the pixel axis (the other 4/WP split the row blocks)
+    int NJ;    // row blocks (16 output channels each) per wave
+    int CK;    // K rows per LDS chunk
+    int SPC;   // k-steps per chunk
+    int vec;   // chunk mode: 1 = 16-byte channel loads, 0 = element-wise on flat k
+};
+
+int variant_count();
+const VariantDesc& variant_desc(int v);
+// Launches variant v; x/y dtypes select the instantiation.
+int launch_conv(int v, nm_dtype_t xdt, nm_dtype_t ydt, const ConvParams& p, hipStream_t s);
+
+// prune-side kernels (nm_prune_kernels.hip)
+int run_prune(const float* d_w, nm_packed* wp, hipStream_t s);
+int run_build_prepack(nm_packed* wp, Prepack& pp, hipStream_t s);
+int run_build_mask(const nm_packed* wp, uint8_t* d_mask, hipStream_t s);
+int run_fill_random(void* d, size_t n_elems, nm_dtype_t dt, uint32_t seed, hipStream_t s);
+
+}  // namespace nm

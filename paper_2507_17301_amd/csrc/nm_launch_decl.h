@@ -1,0 +1,11 @@
+// Declaration of the per-variant launchers (defined by explicit instantiation
+// in nm_conv_inst.hip, referenced by the registry).
+#pragma once
+#include "nm_internal.h"
+
+namespace nm {
+struct bf16_t { unsigned short v; };
+
+template <int BP, int WP, int NJ, int CK, int SPC, bool VEC, typename TIN, typename TOUT>
+int launch_t(const ConvParams& p, hipStream_t s);
+}  // namespace nm

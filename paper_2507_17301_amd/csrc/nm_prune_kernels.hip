@@ -1,0 +1,267 @@
+// Pruning, packing and operand-table kernels (gfx950).
+//
+// Column-wise N:M selection with L1-norm importance (paper section 3.1), the
+// compressed weight + index array (section 2.1, inputs of Alg. 1), and the
+// repacking of both into the order the convolution kernel consumes.
+#include "nm_internal.h"
+
+namespace nm {
+
+namespace {
+
+constexpr int kPruneThreads = 256;
+
+// One workgroup handles `gpb` groups of one column tile (gpb*M columns, or one
+// group of M > 256 columns).  Per column: L1 norm over the tile's rows in fp64,
+// rows ascending (adds only, so the sum is reproducible bit for bit); then the
+// rank of the column inside its group (number of columns that beat it, a lower
+// index beating an equal norm); ranks < N survive.  Kept positions are written
+// ascending.
+__global__ __launch_bounds__(kPruneThreads) void prune_select_kernel(
+    const float* __restrict__ w, int cout, int K, int N, int M, int T, int G, int gpb,
+    int32_t* __restrict__ idx)
+{
+    extern __shared__ double sm_score[];
+    const int cols = gpb * M;
+    unsigned char* keep = reinterpret_cast<unsigned char*>(sm_score + cols);
+    const int j = blockIdx.y;
+    const int g0 = blockIdx.x * gpb;
+    const int r0 = j * T;
+    const int r1 = min(r0 + T, cout);
+
+    for (int i = threadIdx.x; i < cols; i += kPruneThreads) {
+        const int lg = i / M, c = i - lg * M;
+        const int g = g0 + lg;
+        double s = 0.0;
+        if (g < G) {
+            const float* col = w + (size_t)g * M + c;
+            for (int r = r0; r < r1; ++r) s += fabs((double)col[(size_t)r * K]);
+        }
+        sm_score[i] = s;
+    }
+    __syncthreads();
+    for (int i = threadIdx.x; i < cols; i += kPruneThreads) {
+        const int lg = i / M, c = i - lg * M;
+        const double mine = sm_score[i];
+        const double* grp = sm_score + lg * M;
+        int rank = 0;
+        for (int c2 = 0; c2 < M; ++c2) {
+            const double o = grp[c2];
+            rank += (o > mine || (o == mine && c2 < c)) ? 1 : 0;
+        }
+        keep[i] = rank < N ? 1 : 0;
+    }
+    __syncthreads();
+    for (int i = threadIdx.x; i < cols; i += kPruneThreads) {
+        const int lg = i / M, c = i - lg * M;
+        const int g = g0 + lg;
+        if (g >= G || !keep[i]) continue;
+        const unsigned char* grp = keep + lg * M;
+        int pos = 0;
+        for (int c2 = 0; c2 < c; ++c2) pos += grp[c2];
+        idx[((size_t)j * G + g) * N + pos] = g * M + c;
+    }
+}
+
+__device__ inline float round_bf16_rne(float v)
+{
+    unsigned u = __float_as_uint(v);
+    u += 0x7fffu + ((u >> 16) & 1u);
+    return __uint_as_float(u & 0xffff0000u);
+}
+
+// vals[j][kk][t] = w[j*T + t][idx[j][kk]] (zero beyond Cout), optionally
+// rounded to bf16.
+__global__ void pack_values_kernel(const float* __restrict__ w, const int32_t* __restrict__ idx,
+                                   int cout, int K, int kprime, int T, int n_tiles, int to_bf16,
+                                   float* __restrict__ vals)
+{
+    const size_t total = (size_t)n_tiles * kprime * T;
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < total;
+         i += (size_t)gridDim.x * blockDim.x) {
+        const int t = (int)(i % T);
+        const size_t jk = i / T;
+        const int j = (int)(jk / kprime);
+        const int r = j * T + t;
+        float v = 0.f;
+        if (r < cout) v = w[(size_t)r * K + idx[jk]];
+        if (to_bf16) v = round_bf16_rne(v);
+        vals[i] = v;
+    }
+}
+
+__device__ inline void chunk_of(int k, int cin, int CK, int vec, int ncpt, int* c, int* r)
+{
+    if (vec) {
+        const int tap = k / cin, ci = k - tap * cin;
+        *c = tap * ncpt + ci / CK;
+        *r = ci % CK;
+    } else {
+        *c = k / CK;
+        *r = k % CK;
+    }
+}
+
+// One workgroup per column tile.  Kept columns are ascending in k, hence
+// grouped by chunk; the i-th kept column of a chunk becomes quarter i % 4 of
+// k-step i / 4 of that chunk.  Outputs (zero-initialised by the caller):
+//   rows [j][c][q][ROWB] bytes   LDS row of the kept column, byte s = step s
+//   wfrag[rb][c][lane][SPC]      weight for MFMA A-operand lane (q*16 + t)
+// err[0] is set if a chunk holds more than 4*SPC kept columns.
+__global__ __launch_bounds__(256) void build_prepack_kernel(
+    const int32_t* __restrict__ idx, const float* __restrict__ vals, int kprime, int T, int rbpt,
+    int cin, int CK, int vec, int ncpt, int nchunks, int SPC, int ROWB,
+    unsigned char* __restrict__ rows, float* __restrict__ wfrag, int* __restrict__ err)
+{
+    extern __shared__ int sm_int[];
+    int* cnt = sm_int;             // [nchunks]
+    int* first = sm_int + nchunks; // [nchunks]
+    const int j = blockIdx.x;
+    const int32_t* idxj = idx + (size_t)j * kprime;
+    for (int c = threadIdx.x; c < nchunks; c += blockDim.x) cnt[c] = 0;
+    __syncthreads();
+    for (int kk = threadIdx.x; kk < kprime; kk += blockDim.x) {
+        int c, r;
+        chunk_of(idxj[kk], cin, CK, vec, ncpt, &c, &r);
+        atomicAdd(&cnt[c], 1);
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        int run = 0;
+        for (int c = 0; c < nchunks; ++c) {
+            first[c] = run;
+            run += cnt[c];
+            if (cnt[c] > 4 * SPC) err[0] = 1;
+        }
+    }
+    __syncthreads();
+    for (int kk = threadIdx.x; kk < kprime; kk += blockDim.x) {
+        int c, r;
+        chunk_of(idxj[kk], cin, CK, vec, ncpt, &c, &r);
+        const int i = kk - first[c];
+        const int step = i >> 2, q = i & 3;
+        if (step >= SPC) continue;
+        rows[(((size_t)j * nchunks + c) * 4 + q) * ROWB + step] = (unsigned char)r;
+        for (int sub = 0; sub < rbpt; ++sub) {
+            const size_t rb = (size_t)j * rbpt + sub;
+            for (int t = 0; t < 16; ++t) {
+                const int tt = sub * 16 + t;
+                const float v = tt < T ? vals[((size_t)j * kprime + kk) * T + tt] : 0.f;
+                wfrag[((rb * nchunks + c) * 64 + q * 16 + t) * SPC + step] = v;
+            }
+        }
+    }
+}
+
+__global__ void build_mask_kernel(const int32_t* __restrict__ idx, int cout, int K, int kprime,
+                                  int T, int n_tiles, unsigned char* __restrict__ mask)
+{
+    const size_t total = (size_t)n_tiles * kprime * T;
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < total;
+         i += (size_t)gridDim.x * blockDim.x) {
+        const int t = (int)(i % T);
+        const size_t jk = i / T;
+        const int j = (int)(jk / kprime);
+        const int r = j * T + t;
+        if (r < cout) mask[(size_t)r * K + idx[jk]] = 1;
+    }
+}
+
+__device__ inline unsigned hash32(unsigned x)
+{
+    x ^= x >> 16; x *= 0x7feb352du;
+    x ^= x >> 15; x *= 0x846ca68bu;
+    x ^= x >> 16;
+    return x;
+}
+
+__global__ void fill_random_kernel(void* dst, size_t n, int bf16, unsigned seed)
+{
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n;
+         i += (size_t)gridDim.x * blockDim.x) {
+        const unsigned h = hash32((unsigned)i * 2654435761u + seed);
+        const float v = (float)(h >> 8) * (1.0f / 16777216.0f);   // [0,1)
+        if (bf16)
+            reinterpret_cast<unsigned short*>(dst)[i] =
+                (unsigned short)(__float_as_uint(round_bf16_rne(v)) >> 16);
+        else
+            reinterpret_cast<float*>(dst)[i] = v;
+    }
+}
+
+int grid_for(size_t total, int threads)
+{
+    size_t g = (total + threads - 1) / threads;
+    if (g > 65535u * 16u) g = 65535u * 16u;
+    if (g < 1) g = 1;
+    return (int)g;
+}
+
+}  // namespace
+
+int run_prune(const float* d_w, nm_packed* wp, hipStream_t s)
+{
+    const int M = wp->m;
+    const int gpb = M <= kPruneThreads ? kPruneThreads / M : 1;
+    const size_t lds = (size_t)gpb * M * (sizeof(double) + 1);
+    if (lds > 64 * 1024) {
+        NM_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void*>(prune_select_kernel),
+                                         hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+    }
+    dim3 grid((wp->G + gpb - 1) / gpb, wp->n_tiles);
+    hipLaunchKernelGGL(prune_select_kernel, grid, dim3(kPruneThreads), lds, s, d_w, wp->cout,
+                       wp->K, wp->n, M, wp->tile, wp->G, gpb, wp->d_idx);
+    NM_HIP_CHECK(hipGetLastError());
+    const size_t total = (size_t)wp->n_tiles * wp->kprime * wp->tile;
+    hipLaunchKernelGGL(pack_values_kernel, dim3(grid_for(total, 256)), dim3(256), 0, s, d_w,
+                       wp->d_idx, wp->cout, wp->K, wp->kprime, wp->tile, wp->n_tiles,
+                       wp->value_dtype == NM_BF16 ? 1 : 0, wp->d_vals);
+    NM_HIP_CHECK(hipGetLastError());
+    return NM_OK;
+}
+
+int run_build_prepack(nm_packed* wp, Prepack& pp, hipStream_t s)
+{
+    const ChunkGeom& g = pp.geom;
+    int* d_err = nullptr;
+    NM_HIP_CHECK(hipMalloc(&d_err, sizeof(int)));
+    NM_HIP_CHECK(hipMemsetAsync(d_err, 0, sizeof(int), s));
+    const size_t lds = (size_t)2 * g.nchunks * sizeof(int);
+    hipLaunchKernelGGL(build_prepack_kernel, dim3(wp->n_tiles), dim3(256), lds, s, wp->d_idx,
+                       wp->d_vals, wp->kprime, wp->tile, wp->rbpt, wp->cin, g.CK, g.vec, g.ncpt,
+                       g.nchunks, pp.SPC, pp.ROWB, pp.d_rows, pp.d_wfrag, d_err);
+    hipError_t e = hipGetLastError();
+    int h_err = 0;
+    if (e == hipSuccess) e = hipMemcpyAsync(&h_err, d_err, sizeof(int), hipMemcpyDeviceToHost, s);
+    if (e == hipSuccess) e = hipStreamSynchronize(s);
+    (void)hipFree(d_err);
+    if (e != hipSuccess) {
+        set_error("build_prepack failed: %s", hipGetErrorString(e));
+        return NM_ERR_HIP;
+    }
+    if (h_err) {
+        set_error("internal: a K chunk holds more kept columns than the operand table allows");
+        return NM_ERR_UNSUPPORTED;
+    }
+    return NM_OK;
+}
+
+int run_build_mask(const nm_packed* wp, unsigned char* d_mask, hipStream_t s)
+{
+    NM_HIP_CHECK(hipMemsetAsync(d_mask, 0, (size_t)wp->cout * wp->K, s));
+    const size_t total = (size_t)wp->n_tiles * wp->kprime * wp->tile;
+    hipLaunchKernelGGL(build_mask_kernel, dim3(grid_for(total, 256)), dim3(256), 0, s, wp->d_idx,
+                       wp->cout, wp->K, wp->kprime, wp->tile, wp->n_tiles, d_mask);
+    NM_HIP_CHECK(hipGetLastError());
+    return NM_OK;
+}
+
+int run_fill_random(void* d, size_t n_elems, nm_dtype_t dt, uint32_t seed, hipStream_t s)
+{
+    hipLaunchKernelGGL(fill_random_kernel, dim3(grid_for(n_elems, 256)), dim3(256), 0, s, d,
+                       n_elems, dt == NM_BF16 ? 1 : 0, seed);
+    NM_HIP_CHECK(hipGetLastError());
+    return NM_OK;
+}
+
+}  // namespace nm
