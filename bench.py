@@ -1,0 +1,234 @@
+#!/usr/bin/env python3
+"""Benchmark: ResNet-50 convolution stack, column-wise 2:4 (T = 16), batch 64,
+on one MI355X.
+
+A step is one pass of the hot path over one batch: all 53 convolutions
+(fused im2col+pack, kept-column contraction, bias + ReLU) launched back to back
+through the C ABI on one stream, each on its own resident synthetic input of the
+standard shape.  Pruning, packing and the per-layer tuning are one-time set-up,
+as in the paper (weights are pruned once, every candidate kernel is profiled
+once per layer), and are reported separately.
+
+Prints ONE JSON line on stdout; everything else goes to stderr.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_TFLOPS = {"f32": 157.3, "bf16": 2500.0}   # dense MFMA peaks of MI355X
+PEAK_HBM_GBS = 8000.0
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--dtype", choices=["f32", "bf16"], default="f32")
+    ap.add_argument("--batch", type=int, default=64)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-tune", action="store_true", help="use the untuned default variant")
+    ap.add_argument("--cache", default=None, help="tuning cache file to load/save")
+    ap.add_argument("--report", default=None, help="write the per-layer table (JSON) here")
+    args = ap.parse_args()
+
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on ONE GPU only (no sharding, no collectives); "
+              "use --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    from paper_2507_17301_amd import binding as nm
+    from paper_2507_17301_amd import workloads as wl
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible; the library has no CPU fallback", file=sys.stderr)
+        sys.exit(3)
+    torch.cuda.set_device(0)
+    dev = torch.device("cuda:0")
+    nm.lib()
+
+    B = args.batch
+    layers = wl.resnet50_stack(2, 4, 16)
+    bf16 = args.dtype == "bf16"
+    tdt = torch.bfloat16 if bf16 else torch.float32
+    ndt = nm.NM_BF16 if bf16 else nm.NM_F32
+    esize = 2 if bf16 else 4
+
+    # ---- one-time set-up: weights, pruning, tuning, resident inputs ---------
+    if args.cache and os.path.exists(args.cache):
+        nm.nm_cache_load(args.cache)
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(1234)
+    t0 = time.time()
+    packed, xs, ys, biases, variants = [], [], [], [], []
+    prune_s = 0.0
+    for i, l in enumerate(layers):
+        _, w, bias = wl.make_tensors(l, B, 4000 + i, with_input=False)
+        tp = time.time()
+        wp = nm.nm_prune(w, l.n, l.m, l.tile, ndt)
+        prune_s += time.time() - tp
+        packed.append(wp)
+        x = torch.rand((B, l.H, l.W, l.Cin), generator=gen, device=dev, dtype=torch.float32).to(tdt)
+        xs.append(x)
+        ys.append(torch.empty((B, l.Ho, l.Wo, l.Cout), device=dev, dtype=tdt))
+        biases.append(torch.from_numpy(bias).to(dev))
+    tune_s = 0.0
+    for i, l in enumerate(layers):
+        if args.no_tune:
+            variants.append(None)
+            continue
+        tp = time.time()
+        v, ms = nm.nm_autotune(ndt, B, l.H, l.W, l.Cin, packed[i], True, l.stride, l.pad, l.dil, True)
+        tune_s += time.time() - tp
+        variants.append(v)
+    torch.cuda.synchronize()
+    if args.cache:
+        nm.nm_cache_save(args.cache)
+    log(f"set-up {time.time() - t0:.1f}s (prune+pack {prune_s:.2f}s, tune {tune_s:.2f}s), "
+        f"{len(layers)} layers, {nm.nm_cache_size()} tuned shapes")
+
+    stream = torch.cuda.current_stream()
+
+    def step():
+        for i, l in enumerate(layers):
+            nm.nm_conv2d(xs[i], packed[i], biases[i], l.stride, l.pad, l.dil, True, y=ys[i],
+                         stream=stream)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    e0 = torch.cuda.Event(enable_timing=True)
+    e1 = torch.cuda.Event(enable_timing=True)
+    t_host0 = time.time()
+    e0.record(stream)
+    for _ in range(args.steps):
+        step()
+    e1.record(stream)
+    torch.cuda.synchronize()
+    t_host = time.time() - t_host0
+    ms_step = e0.elapsed_time(e1) / args.steps
+    ms_step_host = t_host * 1e3 / args.steps
+
+    # ---- per-layer kernel durations (HIP events on the launch stream) --------
+    reps = 5
+    per_layer = []
+    for i, l in enumerate(layers):
+        a = torch.cuda.Event(enable_timing=True)
+        b = torch.cuda.Event(enable_timing=True)
+        nm.nm_conv2d(xs[i], packed[i], biases[i], l.stride, l.pad, l.dil, True, y=ys[i], stream=stream)
+        a.record(stream)
+        for _ in range(reps):
+            nm.nm_conv2d(xs[i], packed[i], biases[i], l.stride, l.pad, l.dil, True, y=ys[i],
+                         stream=stream)
+        b.record(stream)
+        b.synchronize()
+        ms = a.elapsed_time(b) / reps
+        eff = l.effective_flops(B)
+        byts = l.algorithmic_bytes(B, esize, esize)
+        t_flop = eff / (PEAK_TFLOPS[args.dtype] * 1e12) * 1e3
+        t_mem = byts / (PEAK_HBM_GBS * 1e9) * 1e3
+        per_layer.append({
+            "layer": l.name, "variant": nm.nm_variant_name(variants[i]) if variants[i] is not None else "default",
+            "ms": ms, "dense_gflops": l.dense_flops(B) / ms / 1e6, "eff_gflops": eff / ms / 1e6,
+            "alg_bytes": byts, "gbs": byts / ms / 1e6, "t_min_ms": max(t_flop, t_mem),
+            "bound": "mfma" if t_flop >= t_mem else "hbm", "frac": max(t_flop, t_mem) / ms,
+        })
+
+    dense = sum(l.dense_flops(B) for l in layers)
+    eff = sum(l.effective_flops(B) for l in layers)
+    byts = sum(l.algorithmic_bytes(B, esize, esize) for l in layers)
+    kern_ms = sum(r["ms"] for r in per_layer)
+    tmin_ms = sum(r["t_min_ms"] for r in per_layer)
+    for r in per_layer:
+        log(f"{r['layer']:>18s} {r['variant']:>34s} {r['ms'] * 1e3:9.1f} us  "
+            f"{r['eff_gflops'] / 1e3:7.1f} eff TF/s {r['gbs']:8.0f} GB/s  {r['bound']:4s} {r['frac'] * 100:5.1f}%")
+    log(f"sum of kernel times {kern_ms:.3f} ms, step {ms_step:.3f} ms (host {ms_step_host:.3f} ms), "
+        f"sum of per-layer lower bounds {tmin_ms:.3f} ms -> {tmin_ms / kern_ms * 100:.1f}% of binding roofline")
+
+    roofline = {
+        # the convolution kernel, all 53 launches of a step taken together:
+        # flops actually contracted (2*P*K'*Cout per launch) over their summed duration
+        "bound": "mfma", "achieved": eff / kern_ms / 1e9, "peak": PEAK_TFLOPS[args.dtype],
+        "unit": "TFLOP/s", "frac": eff / kern_ms / 1e9 / PEAK_TFLOPS[args.dtype],
+        "traffic": None,
+        "kernel": "nm_conv_kernel", "launches_per_step": len(layers),
+        "avg_launch_ms": kern_ms / len(layers),
+        "frac_of_binding_roofline_per_layer": tmin_ms / kern_ms,
+        "algorithmic_gbytes_per_step": byts / 1e9, "achieved_gbs": byts / kern_ms / 1e6,
+    }
+
+    cpu = None
+    if not args.no_cpu_baseline:
+        cpu = cpu_baseline(layers, B, bf16)
+
+    out = {
+        "metric": "dense-equiv GFLOP/s, ResNet-50 conv stack 2:4 @batch 64",
+        "value": dense / ms_step / 1e6, "unit": "GFLOP/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_step, "ms_per_img": ms_step / B,
+        "effective_gflops": eff / ms_step / 1e6,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": args.dtype, "data": "synthetic",
+        "config": {"workload": f"resnet50_conv_stack_53layers_2of4_T16_batch{B}_{args.dtype}",
+                   "batch": B, "layers": len(layers), "tuned": not args.no_tune},
+        "setup": {"prune_pack_s": prune_s, "autotune_s": tune_s},
+        "roofline": roofline, "cpu_baseline": cpu,
+    }
+    if args.report:
+        with open(args.report, "w") as f:
+            json.dump({"summary": out, "layers": per_layer}, f, indent=1)
+    print(json.dumps(out), flush=True)
+
+
+def cpu_baseline(layers, B, bf16):
+    """The CPU oracle, as it stands, on the first images of the same workload."""
+    import numpy as np
+    import oracle
+    from paper_2507_17301_amd import workloads as wl
+
+    cores = min(16, os.cpu_count() or 1)
+    prepared = []
+    for i, l in enumerate(layers):
+        _, w, bias = wl.make_tensors(l, 1, 4000 + i, with_input=False)
+        _, _, wz = oracle.prune(w, l.n, l.m, l.tile)
+        if bf16:
+            wz = oracle.round_bf16(wz)
+        prepared.append((l, wz, bias))
+    rng = np.random.default_rng(99)
+
+    def run(nimg):
+        total = 0.0
+        for l, wz, bias in prepared:
+            x = rng.random((nimg, l.H, l.W, l.Cin), dtype=np.float32)
+            t = time.time()
+            oracle.conv2d(x, wz, bias, l.stride, l.pad, l.dil, True, out_bf16=bf16, nthreads=cores)
+            total += time.time() - t
+        return total
+
+    t1 = run(1)
+    nimg = int(max(2, min(B, round(15.0 / max(t1, 1e-3)))))
+    t = run(nimg)
+    dense_per_img = sum(l.dense_flops(1) for l, _, _ in prepared)
+    log(f"cpu oracle: {nimg} images in {t:.2f}s on {cores} threads")
+    return {"value": dense_per_img * nimg / t / 1e9, "unit": "GFLOP/s", "cores": cores,
+            "kind": "oracle", "ms_per_img": t * 1e3 / nimg,
+            "sample": f"first {nimg} of {B} images through all {len(prepared)} layers "
+                      f"(direct convolution on zero-filled weights, fp64 accumulate)"}
+
+
+if __name__ == "__main__":
+    main()
