@@ -34,7 +34,7 @@ extern "C" {
 typedef enum {
     NM_OK = 0,
     NM_ERR_ARG = -1,         /* null pointer, n < 1, n > m, tile < 1, K % m != 0, non-finite weight, ... */
-    NM_ERR_SHAPE = -2,       /* output height or width would be < 1, or a tensor exceeds 2^31 - 1 elements */
+    NM_ERR_SHAPE = -2,       /* output height or width < 1, a tensor of more than 2^31 - 1 elements, or x of 2 GiB or more */
     NM_ERR_UNSUPPORTED = -3, /* no GPU kernel for this tile size / dtype pair / variant id */
     NM_ERR_ALLOC = -4,       /* host or device allocation failed */
     NM_ERR_HIP = -5,         /* a HIP call failed (no device, launch failure, ...) */

@@ -95,7 +95,7 @@ struct Geometry {
 };
 
 int conv_geometry(int b, int h, int w, const nm_packed* wp, int sh, int sw, int ph, int pw, int dh,
-                  int dw, Geometry* g)
+                  int dw, size_t es, Geometry* g)
 {
     if (b < 1 || h < 1 || w < 1 || sh < 1 || sw < 1 || ph < 0 || pw < 0 || dh < 1 || dw < 1) {
         set_error("bad convolution arguments (sizes, stride, dilation must be >= 1, padding >= 0)");
@@ -117,13 +117,17 @@ int conv_geometry(int b, int h, int w, const nm_packed* wp, int sh, int sw, int 
         set_error("tensor too large: more than 2^31 - 1 elements");
         return NM_ERR_SHAPE;
     }
+    if (xin * (long long)es >= 0x80000000LL) {
+        set_error("input tensor too large: the kernels address x through a 2 GiB buffer window");
+        return NM_ERR_SHAPE;
+    }
     g->P = (int)P;
     return NM_OK;
 }
 
 void fill_params(ConvParams& p, const VariantDesc& d, const Prepack& pp, const nm_packed* wp,
                  const void* x, void* y, const float* bias, int b, int h, int w, const Geometry& g,
-                 int sh, int sw, int ph, int pw, int dh, int dw, int relu)
+                 int sh, int sw, int ph, int pw, int dh, int dw, int relu, size_t es)
 {
     p.x = x; p.y = y; p.bias = bias;
     p.wfrag = pp.d_wfrag; p.rows = pp.d_rows;
@@ -139,6 +143,7 @@ void fill_params(ConvParams& p, const VariantDesc& d, const Prepack& pp, const n
     p.n_cblocks = (wp->n_rowblocks + rb_per_wg - 1) / rb_per_wg;
     p.n_wg = p.n_ptiles * p.n_cblocks;
     p.wg_per_xcd = (p.n_wg + 7) / 8;
+    p.x_bytes = (unsigned)((size_t)b * h * w * wp->cin * es);
 }
 
 // Deterministic default when the shape has not been tuned: a small model of
@@ -444,7 +449,7 @@ int nm_conv2d(const void* x, nm_dtype_t xdt, int b, int h, int w, int cin, const
     int rc = check_conv_args(x, xdt, cin, wp, y, ydt);
     if (rc != NM_OK) return rc;
     Geometry g;
-    rc = conv_geometry(b, h, w, wp, sh, sw, ph, pw, dh, dw, &g);
+    rc = conv_geometry(b, h, w, wp, sh, sw, ph, pw, dh, dw, xdt == NM_F32 ? 4 : 2, &g);
     if (rc != NM_OK) return rc;
 
     int v = -1;
@@ -471,7 +476,8 @@ int nm_conv2d(const void* x, nm_dtype_t xdt, int b, int h, int w, int cin, const
     }
     const VariantDesc& d = variant_desc(v);
     ConvParams p;
-    fill_params(p, d, *find_prepack(wp, d), wp, x, y, bias, b, h, w, g, sh, sw, ph, pw, dh, dw, relu);
+    fill_params(p, d, *find_prepack(wp, d), wp, x, y, bias, b, h, w, g, sh, sw, ph, pw, dh, dw, relu,
+                xdt == NM_F32 ? 4 : 2);
     return launch_conv(v, xdt, ydt, p, (hipStream_t)stream);
 }
 
@@ -492,7 +498,7 @@ int nm_autotune(nm_dtype_t xdt, int b, int h, int w, int cin, const nm_packed_t*
         return NM_ERR_UNSUPPORTED;
     }
     Geometry g;
-    int rc = conv_geometry(b, h, w, wp, sh, sw, ph, pw, dh, dw, &g);
+    int rc = conv_geometry(b, h, w, wp, sh, sw, ph, pw, dh, dw, xdt == NM_F32 ? 4 : 2, &g);
     if (rc != NM_OK) return rc;
     const ShapeKey key = make_key(xdt, ydt, b, h, w, wp, sh, sw, ph, pw, dh, dw);
     {
@@ -542,7 +548,7 @@ int nm_autotune(nm_dtype_t xdt, int b, int h, int w, int cin, const nm_packed_t*
         if (!variant_legal(v, wp)) continue;
         const VariantDesc& d = variant_desc(v);
         ConvParams p;
-        fill_params(p, d, *find_prepack(wp, d), wp, dx, dy, dbias, b, h, w, g, sh, sw, ph, pw, dh, dw, relu);
+        fill_params(p, d, *find_prepack(wp, d), wp, dx, dy, dbias, b, h, w, g, sh, sw, ph, pw, dh, dw, relu, es);
         // warm-up, then the median of 5 timed groups
         rc = launch_conv(v, xdt, ydt, p, s);
         if (rc != NM_OK) { cleanup(); return rc; }

@@ -93,6 +93,33 @@ __device__ inline void load_ops(StepOps<SPC>& o, const float* __restrict__ wf,
     for (int i = 0; i < (SPC + 3) / 4; ++i) o.rw[i] = reinterpret_cast<const unsigned*>(rows)[i];
 }
 
+// Buffer loads: an offset at or beyond the descriptor's size returns zeros, which
+// is how padding, ragged pixel tiles and partial chunks are filled without a branch.
+typedef unsigned u4v __attribute__((ext_vector_type(4)));
+typedef unsigned u2v __attribute__((ext_vector_type(2)));
+constexpr unsigned kOOB = 0x80000000u;   // beyond any tensor this library accepts (< 2 GiB)
+
+__device__ inline f4 buf_load4(__amdgpu_buffer_rsrc_t r, unsigned off, const float*)
+{
+    const u4v v = __builtin_amdgcn_raw_buffer_load_b128(r, off, 0, 0);
+    return f4{__uint_as_float(v.x), __uint_as_float(v.y), __uint_as_float(v.z), __uint_as_float(v.w)};
+}
+__device__ inline f4 buf_load4(__amdgpu_buffer_rsrc_t r, unsigned off, const bf16_t*)
+{
+    const u2v u = __builtin_amdgcn_raw_buffer_load_b64(r, off, 0, 0);
+    return f4{__uint_as_float(u.x << 16), __uint_as_float(u.x & 0xffff0000u),
+              __uint_as_float(u.y << 16), __uint_as_float(u.y & 0xffff0000u)};
+}
+__device__ inline float buf_load1(__amdgpu_buffer_rsrc_t r, unsigned off, const float*)
+{
+    return __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(r, off, 0, 0));
+}
+__device__ inline float buf_load1(__amdgpu_buffer_rsrc_t r, unsigned off, const bf16_t*)
+{
+    return __uint_as_float((unsigned)__builtin_amdgcn_raw_buffer_load_b16(r, off, 0, 0) << 16);
+}
+
+
 template <int BP, int WP, int NJ, int CK, int SPC, bool VEC, typename TIN, typename TOUT>
 __global__ __launch_bounds__(256) void nm_conv_kernel(const ConvParams p)
 {
@@ -102,6 +129,7 @@ __global__ __launch_bounds__(256) void nm_conv_kernel(const ConvParams p)
     constexpr int NBLK = NSEG * 4;        // 16-pixel MFMA blocks per wavefront
     constexpr int WC = 4 / WP;            // wavefronts along the row-block axis
     constexpr int ROWB = SPC < 4 ? 4 : SPC;
+    constexpr int ES = (int)sizeof(TIN);
     static_assert(BPW % 64 == 0 && NSEG >= 1, "a wavefront owns whole 64-pixel segments");
 
     extern __shared__ float lds[];        // [2][CK][SP]
@@ -127,7 +155,9 @@ __global__ __launch_bounds__(256) void nm_conv_kernel(const ConvParams p)
     const int rb0 = (cblock * WC + wcx) * NJ;
     const int wpix = wpx * BPW;
 
-    const TIN* __restrict__ x = reinterpret_cast<const TIN*>(p.x);
+    const __amdgpu_buffer_rsrc_t xr = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<void*>(p.x), 0, (int)p.x_bytes, 0x00020000);
+    const TIN* const xtag = nullptr;
 
     // ---- staging geometry -------------------------------------------------
     // vector mode: item = (pixel, 4-channel quad); a thread keeps the same quad
@@ -138,10 +168,13 @@ __global__ __launch_bounds__(256) void nm_conv_kernel(const ConvParams p)
     static_assert(!VEC || (BP * QPR) % 256 == 0, "staging items must divide evenly");
     static_assert(VEC || (256 % BP == 0 || BP % 256 == 0), "scalar staging keeps one pixel per thread");
     constexpr int NITS = VEC ? 1 : (BP * CK) / 256;   // scalar items per thread
+    constexpr int RSTEP = BP >= 256 ? 1 : 256 / BP;
 
     const int quad = tid % QPR;
     const int pl0 = VEC ? tid / QPR : tid % BP;
-    int hi0[NIT], wi0[NIT], boff[NIT];
+    const int r0s = BP >= 256 ? 0 : __builtin_amdgcn_readfirstlane(tid / BP);
+    int hi0[NIT], wi0[NIT];
+    unsigned base[NIT];                   // byte offset of (b, hi0, wi0, quad*4); may wrap, used only with valid taps
     const int HoWo = p.Ho * p.Wo;
 #pragma unroll
     for (int it = 0; it < NIT; ++it) {
@@ -153,71 +186,67 @@ __global__ __launch_bounds__(256) void nm_conv_kernel(const ConvParams p)
             const int wo = rem - ho * p.Wo;
             hi0[it] = ho * p.sh - p.ph;
             wi0[it] = wo * p.sw - p.pw;
-            boff[it] = b * p.H * p.W;
+            base[it] = (unsigned)(((b * p.H + hi0[it]) * p.W + wi0[it]) * p.Cin + (VEC ? quad * 4 : 0)) * ES;
         } else {
             hi0[it] = -(1 << 28);   // every tap lands outside the image
             wi0[it] = 0;
-            boff[it] = 0;
+            base[it] = 0;
         }
     }
 
+    constexpr int NST = VEC ? NIT : NITS;   // staging items per thread and chunk
     f4 st[VEC ? NIT : 1];
     float sts[VEC ? 1 : NITS];
 
-    auto fetch = [&](int c) {
+    // Fetch iterator: the chunk that the next fetch brings in, as (chunk id, tap
+    // row, tap column, first channel); it runs two chunks ahead of the
+    // contraction and stays on the last chunk once it gets there.
+    int f_c = 0, f_kh = 0, f_kw = 0, f_ci0 = 0;
+    auto fetch_item = [&](int it) {
         if constexpr (VEC) {
-            const int tap = c / p.ncpt;
-            const int ci0 = (c - tap * p.ncpt) * CK;
+            const int dhh = f_kh * p.dh, dww = f_kw * p.dw;
+            const unsigned choff = (unsigned)((dhh * p.W + dww) * p.Cin + f_ci0) * ES;
+            const bool cok = f_ci0 + quad * 4 < p.Cin;
+            const int hi = hi0[it] + dhh, wi = wi0[it] + dww;
+            const bool inb = cok & ((unsigned)hi < (unsigned)p.H) & ((unsigned)wi < (unsigned)p.W);
+            st[it] = buf_load4(xr, inb ? base[it] + choff : kOOB, xtag);
+        } else {
+            const int r = r0s + it * RSTEP;
+            const int k = f_c * CK + r;
+            const int tap = k / p.Cin;
+            const int ci = k - tap * p.Cin;
             const int kh = tap / p.Kw;
             const int kw = tap - kh * p.Kw;
             const int dhh = kh * p.dh, dww = kw * p.dw;
-            const int cq = ci0 + quad * 4;
-            const bool cok = cq < p.Cin;
-#pragma unroll
-            for (int it = 0; it < NIT; ++it) {
-                const int hi = hi0[it] + dhh, wi = wi0[it] + dww;
-                const bool inb = cok && (unsigned)hi < (unsigned)p.H && (unsigned)wi < (unsigned)p.W;
-                f4 v = {0.f, 0.f, 0.f, 0.f};
-                if (inb) v = load4(x + ((size_t)(boff[it] + hi * p.W + wi) * p.Cin + cq));
-                st[it] = v;
-            }
-        } else {
-            constexpr int RSTEP = BP >= 256 ? 1 : 256 / BP;
-            const int r0 = BP >= 256 ? 0 : __builtin_amdgcn_readfirstlane(tid / BP);
-#pragma unroll
-            for (int it = 0; it < NITS; ++it) {
-                const int r = r0 + it * RSTEP;
-                const int k = c * CK + r;
-                float v = 0.f;
-                if (k < p.K) {
-                    const int tap = k / p.Cin;
-                    const int ci = k - tap * p.Cin;
-                    const int kh = tap / p.Kw;
-                    const int kw = tap - kh * p.Kw;
-                    const int hi = hi0[0] + kh * p.dh, wi = wi0[0] + kw * p.dw;
-                    if ((unsigned)hi < (unsigned)p.H && (unsigned)wi < (unsigned)p.W)
-                        v = load1(x + ((size_t)(boff[0] + hi * p.W + wi) * p.Cin + ci));
-                }
-                sts[it] = v;
-            }
+            const int hi = hi0[0] + dhh, wi = wi0[0] + dww;
+            const bool inb = (k < p.K) & ((unsigned)hi < (unsigned)p.H) & ((unsigned)wi < (unsigned)p.W);
+            const unsigned off = base[0] + (unsigned)((dhh * p.W + dww) * p.Cin + ci) * ES;
+            sts[it] = buf_load1(xr, inb ? off : kOOB, xtag);
         }
     };
-    auto stash = [&](int buf) {
+    auto fetch_advance = [&]() {
+        const int adv = f_c + 1 < p.nchunks ? 1 : 0;
+        f_c += adv;
+        if constexpr (VEC) {
+            const int nci = f_ci0 + CK;
+            const int wrap = (adv && nci >= p.Cin) ? 1 : 0;
+            f_ci0 = wrap ? 0 : (adv ? nci : f_ci0);
+            const int nkw = f_kw + wrap;
+            const int wrap2 = nkw == p.Kw ? 1 : 0;
+            f_kw = wrap2 ? 0 : nkw;
+            f_kh += wrap2;
+        }
+    };
+    auto stash_item = [&](int it, int buf) {
         float* dst = lds + buf * (CK * SP);
         if constexpr (VEC) {
-#pragma unroll
-            for (int it = 0; it < NIT; ++it) {
-                float* d = dst + (quad * 4) * SP + pl0 + it * PSTEP;
-                d[0] = st[it].x;
-                d[SP] = st[it].y;
-                d[2 * SP] = st[it].z;
-                d[3 * SP] = st[it].w;
-            }
+            float* d = dst + (quad * 4) * SP + pl0 + it * PSTEP;
+            d[0] = st[it].x;
+            d[SP] = st[it].y;
+            d[2 * SP] = st[it].z;
+            d[3 * SP] = st[it].w;
         } else {
-            constexpr int RSTEP = BP >= 256 ? 1 : 256 / BP;
-            const int r0 = BP >= 256 ? 0 : __builtin_amdgcn_readfirstlane(tid / BP);
-#pragma unroll
-            for (int it = 0; it < NITS; ++it) dst[(r0 + it * RSTEP) * SP + pl0] = sts[it];
+            dst[(r0s + it * RSTEP) * SP + pl0] = sts[it];
         }
     };
 
@@ -243,44 +272,81 @@ __global__ __launch_bounds__(256) void nm_conv_kernel(const ConvParams p)
 
     StepOps<SPC> cur[NJ], nxt[NJ];
 
-    fetch(0);
+    // Prologue: operands of chunk 0, strip of chunk 0 into LDS, strip of chunk 1
+    // into registers.  The operand loads go out first so that the wait for the
+    // strip also covers them.
 #pragma unroll
     for (int jj = 0; jj < NJ; ++jj) load_ops<SPC>(cur[jj], wfp[jj], rwp[jj]);
-    stash(0);
+#pragma unroll
+    for (int it = 0; it < NST; ++it) fetch_item(it);
+    fetch_advance();
+#pragma unroll
+    for (int it = 0; it < NST; ++it) stash_item(it, 0);
+#pragma unroll
+    for (int it = 0; it < NST; ++it) fetch_item(it);
+    fetch_advance();
     __syncthreads();
 
+    constexpr int TOT = NJ * SPC;          // k-steps per chunk for this wavefront
+    constexpr int DEPTH = NSEG == 1 ? 2 : 1;   // LDS reads run this many k-steps ahead
+    constexpr int RING = DEPTH + 1;
+    constexpr int NM = TOT * NBLK;         // MFMAs per chunk for this wavefront
+    // Staging work of one iteration, cut into tasks that are dealt out behind the
+    // MFMAs: write item i of the strip held in registers to LDS, fetch item i of
+    // the strip two chunks ahead, load the operands of the next chunk, advance.
+    constexpr int NTASK = 2 * NST + NJ + 1;
+
+    // Steady state, one iteration per chunk c, no branch inside:
+    //   registers `st` (chunk c+1, fetched one iteration ago) go to the other LDS
+    //   buffer; the fetch of chunk c+2 and the operands of chunk c+1 are issued;
+    //   chunk c is contracted out of LDS.  Past the last chunk the same code
+    //   re-fetches the last chunk and writes it to the buffer nobody reads.
     for (int c = 0; c < p.nchunks; ++c) {
-        const bool more = c + 1 < p.nchunks;
-        if (more) {
-            fetch(c + 1);
-#pragma unroll
-            for (int jj = 0; jj < NJ; ++jj)
-                load_ops<SPC>(nxt[jj], wfp[jj] + (size_t)(c + 1) * 64 * SPC,
-                              rwp[jj] + (size_t)(c + 1) * 4 * ROWB);
-        }
+        const int cn = c + 1 < p.nchunks ? c + 1 : c;
+        const int nb = (c + 1) & 1;
+        auto task = [&](int i) {
+            if (i < NST) {
+                stash_item(i, nb);
+            } else if (i < 2 * NST) {
+                fetch_item(i - NST);
+            } else if (i < 2 * NST + NJ) {
+                const int jj = i - 2 * NST;
+                load_ops<SPC>(nxt[jj], wfp[jj] + (size_t)cn * 64 * SPC, rwp[jj] + (size_t)cn * 4 * ROWB);
+            } else {
+                fetch_advance();
+            }
+        };
+
         const float* buf = lds + (c & 1) * (CK * SP) + wpix + n * 4;
+        f4 bv[RING][NSEG];
+        auto read_b = [&](int t, f4 (&dst)[NSEG]) {
+            const int jj = t / SPC, s = t % SPC;
+            const unsigned ro = (cur[jj].rw[s >> 2] >> (8 * (s & 3))) & 0xffu;
+            const float* bp = buf + ro * SP;
 #pragma unroll
-        for (int jj = 0; jj < NJ; ++jj) {
+            for (int seg = 0; seg < NSEG; ++seg) dst[seg] = *reinterpret_cast<const f4*>(bp + seg * 64);
+        };
 #pragma unroll
-            for (int s = 0; s < SPC; ++s) {
-                const unsigned ro = (cur[jj].rw[s >> 2] >> (8 * (s & 3))) & 0xffu;
-                const float* bp = buf + ro * SP;
-                const float a = cur[jj].a[s];
+        for (int t = 0; t < DEPTH && t < TOT; ++t) read_b(t, bv[t % RING]);
 #pragma unroll
-                for (int seg = 0; seg < NSEG; ++seg) {
-                    const f4 bv = *reinterpret_cast<const f4*>(bp + seg * 64);
-                    acc[jj][seg * 4 + 0] = __builtin_amdgcn_mfma_f32_16x16x4f32(a, bv.x, acc[jj][seg * 4 + 0], 0, 0, 0);
-                    acc[jj][seg * 4 + 1] = __builtin_amdgcn_mfma_f32_16x16x4f32(a, bv.y, acc[jj][seg * 4 + 1], 0, 0, 0);
-                    acc[jj][seg * 4 + 2] = __builtin_amdgcn_mfma_f32_16x16x4f32(a, bv.z, acc[jj][seg * 4 + 2], 0, 0, 0);
-                    acc[jj][seg * 4 + 3] = __builtin_amdgcn_mfma_f32_16x16x4f32(a, bv.w, acc[jj][seg * 4 + 3], 0, 0, 0);
-                }
+        for (int t = 0; t < TOT; ++t) {
+            // the LDS reads of k-step t+DEPTH lead the MFMAs of k-step t
+            if (t + DEPTH < TOT) read_b(t + DEPTH, bv[(t + DEPTH) % RING]);
+            __builtin_amdgcn_sched_barrier(0);
+            const int jj = t / SPC, s = t % SPC;
+            const float a = cur[jj].a[s];
+#pragma unroll
+            for (int b = 0; b < NBLK; ++b) {
+                const int m = t * NBLK + b;
+                acc[jj][b] = __builtin_amdgcn_mfma_f32_16x16x4f32(a, bv[t % RING][b >> 2][b & 3], acc[jj][b], 0, 0, 0);
+                // a slice of the staging work issues while this MFMA occupies the matrix pipe
+#pragma unroll
+                for (int i = m * NTASK / NM; i < (m + 1) * NTASK / NM; ++i) task(i);
+                __builtin_amdgcn_sched_barrier(0);
             }
         }
-        if (more) {
-            stash((c + 1) & 1);
 #pragma unroll
-            for (int jj = 0; jj < NJ; ++jj) cur[jj] = nxt[jj];
-        }
+        for (int jj = 0; jj < NJ; ++jj) cur[jj] = nxt[jj];
         __syncthreads();
     }
 

@@ -104,6 +104,7 @@ struct ConvParams {
     int tile, rbpt, n_rowblocks;
     int n_ptiles, n_cblocks, n_wg;   // pixel tiles, row-block groups, product
     int wg_per_xcd;
+    unsigned x_bytes;  // size of x in bytes (< 2 GiB), the range of the buffer descriptor
 };
 
 struct VariantDesc {
