@@ -26,12 +26,15 @@ FLAGS = [
     "-O3", "--offload-arch=gfx950", "-fPIC", "-std=c++17", "-Wall", "-Wno-unused-function",
     # the compiler must not form packed fp32 instructions on this target
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+    # MFMA accumulators stay in ordinary VGPRs: with the AGPR form the register
+    # allocator shuffles them through v_accvgpr moves inside the chunk loop
+    "-mllvm", "-amdgpu-mfma-vgpr-form=1",
     "-I", INCLUDE, "-I", CSRC,
 ]
 
 
 def _shapes():
-    """(BP, WP, NJ) triples of NM_SHAPES in nm_variants.h."""
+    """(NBLK, WP, NJ) triples of NM_SHAPES in nm_variants.h."""
     text = open(os.path.join(CSRC, "nm_variants.h")).read()
     body = text[text.index("#define NM_SHAPES(X)"):]
     body = body[:body.index("\n\n")]
@@ -43,9 +46,9 @@ def _jobs():
     for src in ("nm_api.hip", "nm_prune_kernels.hip", "nm_conv_registry.hip"):
         jobs.append((os.path.join(CSRC, src), os.path.join(OBJDIR, src.replace(".hip", ".o")), []))
     inst = os.path.join(CSRC, "nm_conv_inst.hip")
-    for bp, wp, nj in _shapes():
-        jobs.append((inst, os.path.join(OBJDIR, f"nm_conv_inst_{bp}_{wp}_{nj}.o"),
-                     [f"-DNM_INST_BP={bp}", f"-DNM_INST_WP={wp}", f"-DNM_INST_NJ={nj}"]))
+    for nb, wp, nj in _shapes():
+        jobs.append((inst, os.path.join(OBJDIR, f"nm_conv_inst_{nb}_{wp}_{nj}.o"),
+                     [f"-DNM_INST_NBLK={nb}", f"-DNM_INST_WP={wp}", f"-DNM_INST_NJ={nj}"]))
     jobs.append((inst, os.path.join(OBJDIR, "nm_conv_inst_scalar.o"), ["-DNM_INST_SCALAR"]))
     return jobs
 

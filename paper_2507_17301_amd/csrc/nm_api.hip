@@ -51,7 +51,10 @@ ShapeKey make_key(nm_dtype_t xdt, nm_dtype_t ydt, int b, int h, int w, const nm_
     return k;
 }
 
-size_t lds_bytes(const VariantDesc& d) { return (size_t)2 * d.CK * (d.BP + 4) * sizeof(float); }
+size_t lds_bytes(const VariantDesc& d)
+{
+    return (size_t)2 * d.CK * strip_stride(d.BP, d.CK, d.vec != 0) * sizeof(float);
+}
 
 const Prepack* find_prepack(const nm_packed* wp, const VariantDesc& d)
 {
@@ -131,6 +134,7 @@ void fill_params(ConvParams& p, const VariantDesc& d, const Prepack& pp, const n
 {
     p.x = x; p.y = y; p.bias = bias;
     p.wfrag = pp.d_wfrag; p.rows = pp.d_rows;
+    p.wfrag_bytes = (unsigned)pp.wfrag_bytes; p.rows_bytes = (unsigned)pp.rows_bytes;
     p.B = b; p.H = h; p.W = w; p.Cin = wp->cin; p.Cout = wp->cout; p.Kh = wp->kh; p.Kw = wp->kw;
     p.Ho = g.Ho; p.Wo = g.Wo;
     p.sh = sh; p.sw = sw; p.ph = ph; p.pw = pw; p.dh = dh; p.dw = dw;
@@ -331,9 +335,11 @@ int nm_prune(const float* w, int cout, int kh, int kw, int cin, int n, int m, in
         Prepack pp;
         pp.geom = g;
         pp.SPC = d.SPC;
-        pp.ROWB = d.SPC < 4 ? 4 : d.SPC;
-        const size_t rows_bytes = (size_t)wp->n_tiles * g.nchunks * 4 * pp.ROWB;
+        const size_t rows_bytes = (size_t)wp->n_tiles * g.nchunks * 4 * pp.SPC * sizeof(uint32_t);
         const size_t wf_bytes = (size_t)wp->n_rowblocks * g.nchunks * 64 * pp.SPC * sizeof(float);
+        if (wf_bytes >= 0x80000000ull) continue;   // operand streams are addressed through a 2 GiB window
+        pp.rows_bytes = rows_bytes;
+        pp.wfrag_bytes = wf_bytes;
         NM_TRY_HIP(hipMalloc(&pp.d_rows, rows_bytes), NM_ERR_ALLOC);
         wp->prepacks.push_back(pp);   // owned by the handle from here on
         Prepack& ref = wp->prepacks.back();

@@ -1,17 +1,17 @@
 // Explicit instantiations of the convolution kernel.  Compiled once per shape
-// (-DNM_INST_BP=.. -DNM_INST_WP=.. -DNM_INST_NJ=..) and once with
+// (-DNM_INST_NBLK=.. -DNM_INST_WP=.. -DNM_INST_NJ=..) and once with
 // -DNM_INST_SCALAR for the element-wise staging variants.
 #include "nm_conv_kernel.h"
 #include "nm_variants.h"
 
 namespace nm {
-#define NM_INST(BP, WP, NJ, CK, SPC, VEC)                                                        \
-    template int launch_t<BP, WP, NJ, CK, SPC, (VEC) != 0, float, float>(const ConvParams&, hipStream_t); \
-    template int launch_t<BP, WP, NJ, CK, SPC, (VEC) != 0, bf16_t, bf16_t>(const ConvParams&, hipStream_t);
+#define NM_INST(NB, WP, NJ, CK, SPC, VEC)                                                        \
+    template int launch_t<NB, WP, NJ, CK, SPC, (VEC) != 0, float, float>(const ConvParams&, hipStream_t); \
+    template int launch_t<NB, WP, NJ, CK, SPC, (VEC) != 0, bf16_t, bf16_t>(const ConvParams&, hipStream_t);
 
 #ifdef NM_INST_SCALAR
 NM_SCALAR_VARIANTS(NM_INST)
 #else
-NM_VEC_CHUNKS(NM_INST, NM_INST_BP, NM_INST_WP, NM_INST_NJ)
+NM_VEC_CHUNKS(NM_INST, NM_INST_NBLK, NM_INST_WP, NM_INST_NJ)
 #endif
 }  // namespace nm

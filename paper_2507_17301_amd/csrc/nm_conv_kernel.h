@@ -1,8 +1,8 @@
 // Fused im2col + packing + column-wise N:M contraction + bias/ReLU for gfx950.
 //
-// One workgroup (4 wavefronts of 64) produces BP output pixels x (4/WP)*NJ*16
-// output channels.  The K axis is walked in chunks of CK rows of the im2col
-// matrix (paper section 2.2); for each chunk the workgroup gathers
+// One workgroup (4 wavefronts of 64) produces BP = 16*NBLK*WP output pixels x
+// (4/WP)*NJ*16 output channels.  The K axis is walked in chunks of CK rows of
+// the im2col matrix (paper section 2.2); for each chunk the workgroup gathers
 // rows k0..k0+CK-1 of the im2col matrix for its BP pixels straight from the
 // NHWC feature map into LDS, laid out [row][pixel] -- the K-by-V strip of the
 // paper's data packing (section 3.2, Alg. 2) with V = BP, built in one pass and
@@ -17,8 +17,16 @@
 //   A[i][k]  lane i + 16k  = weight of output channel i for kept column k
 //   B[k][j]  lane j + 16k  = im2col value of kept column k at pixel j
 //   D[i][j]  lane j + 16*(i/4), register i%4
-// A lane's 16-byte LDS read returns four consecutive pixels of one row, which
-// feed four MFMAs; so MFMA block e of a 64-pixel segment owns pixels 4j + e.
+// A wavefront's 16*NBLK pixels are cut into 64-pixel segments read with one
+// 16-byte LDS load per lane (pixels 4j..4j+3 feed four MFMAs), then at most one
+// 32-pixel piece (8-byte loads) and one 16-pixel piece (4-byte loads).
+//
+// On this machine every VALU, LDS or memory instruction a wavefront issues
+// takes issue time away from its own MFMAs, so the loop is built to keep such
+// instructions few: input addresses are per-tap registers plus a scalar,
+// operand streams are buffer loads with scalar offsets, row offsets come
+// ready-made from the operand table, and the operand registers ping-pong
+// between two sets instead of being copied.
 #pragma once
 
 #include "nm_launch_decl.h"
@@ -27,26 +35,8 @@ namespace nm {
 
 typedef float f4 __attribute__((ext_vector_type(4)));
 typedef float f2 __attribute__((ext_vector_type(2)));
-
-
-
-template <typename T> struct elem;
-template <> struct elem<float> { static constexpr nm_dtype_t dt = NM_F32; };
-template <> struct elem<bf16_t> { static constexpr nm_dtype_t dt = NM_BF16; };
-
-__device__ inline f4 load4(const float* p) { return *reinterpret_cast<const f4*>(p); }
-__device__ inline f4 load4(const bf16_t* p)
-{
-    const uint2 u = *reinterpret_cast<const uint2*>(p);
-    f4 r;
-    r.x = __uint_as_float(u.x << 16);
-    r.y = __uint_as_float(u.x & 0xffff0000u);
-    r.z = __uint_as_float(u.y << 16);
-    r.w = __uint_as_float(u.y & 0xffff0000u);
-    return r;
-}
-__device__ inline float load1(const float* p) { return *p; }
-__device__ inline float load1(const bf16_t* p) { return __uint_as_float((unsigned)p->v << 16); }
+typedef unsigned u4v __attribute__((ext_vector_type(4)));
+typedef unsigned u2v __attribute__((ext_vector_type(2)));
 
 __device__ inline unsigned short to_bf16_bits(float v)
 {
@@ -66,71 +56,70 @@ __device__ inline void store4(bf16_t* p, f4 v)
 __device__ inline void store1(float* p, float v) { *p = v; }
 __device__ inline void store1(bf16_t* p, float v) { p->v = to_bf16_bits(v); }
 
-// Per-lane operand fetch for one (row block, chunk): SPC weights and the SPC
-// LDS rows (one byte each) of this lane's quarter.
-template <int SPC> struct StepOps {
-    float a[SPC];
-    unsigned rw[(SPC + 3) / 4];
-};
-
-template <int SPC>
-__device__ inline void load_ops(StepOps<SPC>& o, const float* __restrict__ wf,
-                                const unsigned char* __restrict__ rows)
-{
-    if constexpr (SPC == 1) {
-        o.a[0] = wf[0];
-    } else if constexpr (SPC == 2) {
-        const f2 v = *reinterpret_cast<const f2*>(wf);
-        o.a[0] = v.x; o.a[1] = v.y;
-    } else {
-#pragma unroll
-        for (int i = 0; i < SPC / 4; ++i) {
-            const f4 v = *reinterpret_cast<const f4*>(wf + 4 * i);
-            o.a[4 * i + 0] = v.x; o.a[4 * i + 1] = v.y; o.a[4 * i + 2] = v.z; o.a[4 * i + 3] = v.w;
-        }
-    }
-#pragma unroll
-    for (int i = 0; i < (SPC + 3) / 4; ++i) o.rw[i] = reinterpret_cast<const unsigned*>(rows)[i];
-}
-
 // Buffer loads: an offset at or beyond the descriptor's size returns zeros, which
 // is how padding, ragged pixel tiles and partial chunks are filled without a branch.
-typedef unsigned u4v __attribute__((ext_vector_type(4)));
-typedef unsigned u2v __attribute__((ext_vector_type(2)));
 constexpr unsigned kOOB = 0x80000000u;   // beyond any tensor this library accepts (< 2 GiB)
 
-__device__ inline f4 buf_load4(__amdgpu_buffer_rsrc_t r, unsigned off, const float*)
+__device__ inline __amdgpu_buffer_rsrc_t make_rsrc(const void* ptr, unsigned bytes)
 {
-    const u4v v = __builtin_amdgcn_raw_buffer_load_b128(r, off, 0, 0);
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(ptr), 0, (int)bytes, 0x00020000);
+}
+__device__ inline f4 buf_load4(__amdgpu_buffer_rsrc_t r, unsigned voff, unsigned soff, const float*)
+{
+    const u4v v = __builtin_amdgcn_raw_buffer_load_b128(r, voff, soff, 0);
     return f4{__uint_as_float(v.x), __uint_as_float(v.y), __uint_as_float(v.z), __uint_as_float(v.w)};
 }
-__device__ inline f4 buf_load4(__amdgpu_buffer_rsrc_t r, unsigned off, const bf16_t*)
+__device__ inline f4 buf_load4(__amdgpu_buffer_rsrc_t r, unsigned voff, unsigned soff, const bf16_t*)
 {
-    const u2v u = __builtin_amdgcn_raw_buffer_load_b64(r, off, 0, 0);
+    const u2v u = __builtin_amdgcn_raw_buffer_load_b64(r, voff, soff, 0);
     return f4{__uint_as_float(u.x << 16), __uint_as_float(u.x & 0xffff0000u),
               __uint_as_float(u.y << 16), __uint_as_float(u.y & 0xffff0000u)};
 }
-__device__ inline float buf_load1(__amdgpu_buffer_rsrc_t r, unsigned off, const float*)
+__device__ inline float buf_load1(__amdgpu_buffer_rsrc_t r, unsigned voff, const float*)
 {
-    return __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(r, off, 0, 0));
+    return __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(r, voff, 0, 0));
 }
-__device__ inline float buf_load1(__amdgpu_buffer_rsrc_t r, unsigned off, const bf16_t*)
+__device__ inline float buf_load1(__amdgpu_buffer_rsrc_t r, unsigned voff, const bf16_t*)
 {
-    return __uint_as_float((unsigned)__builtin_amdgcn_raw_buffer_load_b16(r, off, 0, 0) << 16);
+    return __uint_as_float((unsigned)__builtin_amdgcn_raw_buffer_load_b16(r, voff, 0, 0) << 16);
 }
 
+// Per-lane operands of one (row block, chunk): SPC weights and, for this lane's
+// quarter, the LDS row of each of the SPC k-steps.
+template <int SPC> struct StepOps {
+    float a[SPC];
+    unsigned row[SPC];
+};
 
-template <int BP, int WP, int NJ, int CK, int SPC, bool VEC, typename TIN, typename TOUT>
+template <int SPC>
+__device__ inline void load_words(unsigned (&dst)[SPC], __amdgpu_buffer_rsrc_t r, unsigned voff, unsigned soff)
+{
+    if constexpr (SPC == 1) {
+        dst[0] = __builtin_amdgcn_raw_buffer_load_b32(r, voff, soff, 0);
+    } else if constexpr (SPC == 2) {
+        const u2v v = __builtin_amdgcn_raw_buffer_load_b64(r, voff, soff, 0);
+        dst[0] = v.x; dst[1] = v.y;
+    } else {
+#pragma unroll
+        for (int i = 0; i < SPC / 4; ++i) {
+            const u4v v = __builtin_amdgcn_raw_buffer_load_b128(r, voff + 16 * i, soff, 0);
+            dst[4 * i + 0] = v.x; dst[4 * i + 1] = v.y; dst[4 * i + 2] = v.z; dst[4 * i + 3] = v.w;
+        }
+    }
+}
+
+template <int NBLK, int WP, int NJ, int CK, int SPC, bool VEC, typename TIN, typename TOUT>
 __global__ __launch_bounds__(256) void nm_conv_kernel(const ConvParams p)
 {
-    constexpr int SP = BP + 4;            // LDS row stride (floats); rows stay 16-byte aligned
-    constexpr int BPW = BP / WP;          // pixels per wavefront
-    constexpr int NSEG = BPW / 64;        // 64-pixel segments per wavefront
-    constexpr int NBLK = NSEG * 4;        // 16-pixel MFMA blocks per wavefront
+    constexpr int BPW = 16 * NBLK;        // pixels per wavefront
+    constexpr int BP = BPW * WP;          // pixels per workgroup
+    constexpr int SP = strip_stride(BP, CK, VEC);
     constexpr int WC = 4 / WP;            // wavefronts along the row-block axis
-    constexpr int ROWB = SPC < 4 ? 4 : SPC;
     constexpr int ES = (int)sizeof(TIN);
-    static_assert(BPW % 64 == 0 && NSEG >= 1, "a wavefront owns whole 64-pixel segments");
+    constexpr int NF = NBLK / 4;          // whole 64-pixel segments of a wavefront
+    constexpr int R = NBLK % 4;           // MFMA blocks in the ragged tail: a pair, a single, or both
+    constexpr int OFF2 = NF * 64;                     // first pixel of the 32-pixel piece
+    constexpr int OFF1 = NF * 64 + (R >= 2 ? 32 : 0); // first pixel of the 16-pixel piece
 
     extern __shared__ float lds[];        // [2][CK][SP]
 
@@ -155,31 +144,34 @@ __global__ __launch_bounds__(256) void nm_conv_kernel(const ConvParams p)
     const int rb0 = (cblock * WC + wcx) * NJ;
     const int wpix = wpx * BPW;
 
-    const __amdgpu_buffer_rsrc_t xr = __builtin_amdgcn_make_buffer_rsrc(
-        const_cast<void*>(p.x), 0, (int)p.x_bytes, 0x00020000);
+    const __amdgpu_buffer_rsrc_t xr = make_rsrc(p.x, p.x_bytes);
+    const __amdgpu_buffer_rsrc_t wr = make_rsrc(p.wfrag, p.wfrag_bytes);
+    const __amdgpu_buffer_rsrc_t rr = make_rsrc(p.rows, p.rows_bytes);
     const TIN* const xtag = nullptr;
 
     // ---- staging geometry -------------------------------------------------
     // vector mode: item = (pixel, 4-channel quad); a thread keeps the same quad
     // and NIT pixels.  scalar mode: a thread keeps one pixel and walks rows.
     constexpr int QPR = CK / 4;
-    constexpr int NIT = VEC ? (BP * QPR) / 256 : 1;
     constexpr int PSTEP = 256 / QPR;
-    static_assert(!VEC || (BP * QPR) % 256 == 0, "staging items must divide evenly");
+    constexpr int NIT = VEC ? (BP * QPR + 255) / 256 : 1;
     static_assert(VEC || (256 % BP == 0 || BP % 256 == 0), "scalar staging keeps one pixel per thread");
     constexpr int NITS = VEC ? 1 : (BP * CK) / 256;   // scalar items per thread
     constexpr int RSTEP = BP >= 256 ? 1 : 256 / BP;
+    constexpr int NST = VEC ? NIT : NITS;             // staging items per thread and chunk
 
     const int quad = tid % QPR;
     const int pl0 = VEC ? tid / QPR : tid % BP;
     const int r0s = BP >= 256 ? 0 : __builtin_amdgcn_readfirstlane(tid / BP);
     int hi0[NIT], wi0[NIT];
-    unsigned base[NIT];                   // byte offset of (b, hi0, wi0, quad*4); may wrap, used only with valid taps
+    unsigned base[NIT];   // byte offset of (b, hi0, wi0, quad*4); wraps for border pixels, only used with valid taps
+    unsigned voff[NIT];   // base + current tap, or kOOB when that tap falls outside the image
     const int HoWo = p.Ho * p.Wo;
 #pragma unroll
     for (int it = 0; it < NIT; ++it) {
-        const int pp = p0 + pl0 + it * PSTEP;
-        if (pp < p.P) {
+        const int pl = pl0 + it * PSTEP;
+        const int pp = p0 + pl;
+        if (pp < p.P && pl < BP) {
             const int b = pp / HoWo;
             const int rem = pp - b * HoWo;
             const int ho = rem / p.Wo;
@@ -194,7 +186,6 @@ __global__ __launch_bounds__(256) void nm_conv_kernel(const ConvParams p)
         }
     }
 
-    constexpr int NST = VEC ? NIT : NITS;   // staging items per thread and chunk
     f4 st[VEC ? NIT : 1];
     float sts[VEC ? 1 : NITS];
 
@@ -202,14 +193,21 @@ __global__ __launch_bounds__(256) void nm_conv_kernel(const ConvParams p)
     // row, tap column, first channel); it runs two chunks ahead of the
     // contraction and stays on the last chunk once it gets there.
     int f_c = 0, f_kh = 0, f_kw = 0, f_ci0 = 0;
+    auto retap = [&]() {   // per-pixel offsets of the tap (f_kh, f_kw)
+        const int dhh = f_kh * p.dh, dww = f_kw * p.dw;
+        const unsigned tapoff = (unsigned)((dhh * p.W + dww) * p.Cin) * ES;
+#pragma unroll
+        for (int it = 0; it < NIT; ++it) {
+            const int hi = hi0[it] + dhh, wi = wi0[it] + dww;
+            const bool inb = ((unsigned)hi < (unsigned)p.H) & ((unsigned)wi < (unsigned)p.W);
+            voff[it] = inb ? base[it] + tapoff : kOOB;
+        }
+    };
     auto fetch_item = [&](int it) {
         if constexpr (VEC) {
-            const int dhh = f_kh * p.dh, dww = f_kw * p.dw;
-            const unsigned choff = (unsigned)((dhh * p.W + dww) * p.Cin + f_ci0) * ES;
-            const bool cok = f_ci0 + quad * 4 < p.Cin;
-            const int hi = hi0[it] + dhh, wi = wi0[it] + dww;
-            const bool inb = cok & ((unsigned)hi < (unsigned)p.H) & ((unsigned)wi < (unsigned)p.W);
-            st[it] = buf_load4(xr, inb ? base[it] + choff : kOOB, xtag);
+            // the channel offset of the chunk rides in the vector offset so that
+            // the range check sees the whole address
+            st[it] = buf_load4(xr, voff[it] + (unsigned)(f_ci0 * ES), 0, xtag);
         } else {
             const int r = r0s + it * RSTEP;
             const int k = f_c * CK + r;
@@ -231,14 +229,16 @@ __global__ __launch_bounds__(256) void nm_conv_kernel(const ConvParams p)
             const int nci = f_ci0 + CK;
             const int wrap = (adv && nci >= p.Cin) ? 1 : 0;
             f_ci0 = wrap ? 0 : (adv ? nci : f_ci0);
-            const int nkw = f_kw + wrap;
-            const int wrap2 = nkw == p.Kw ? 1 : 0;
-            f_kw = wrap2 ? 0 : nkw;
-            f_kh += wrap2;
+            if (wrap) {   // uniform, once per tap
+                const int nkw = f_kw + 1;
+                const int wrap2 = nkw == p.Kw ? 1 : 0;
+                f_kw = wrap2 ? 0 : nkw;
+                f_kh += wrap2;
+                retap();
+            }
         }
     };
-    auto stash_item = [&](int it, int buf) {
-        float* dst = lds + buf * (CK * SP);
+    auto stash_item = [&](int it, float* dst) {
         if constexpr (VEC) {
             float* d = dst + (quad * 4) * SP + pl0 + it * PSTEP;
             d[0] = st[it].x;
@@ -253,16 +253,24 @@ __global__ __launch_bounds__(256) void nm_conv_kernel(const ConvParams p)
     // ---- operand streams ----------------------------------------------------
     // A wavefront whose row blocks lie beyond the last one still takes part in
     // staging and barriers; it computes on a clamped row block and stores nothing.
-    const float* wfp[NJ];
-    const unsigned char* rwp[NJ];
+    const unsigned wvoff = (unsigned)lane * SPC * 4;   // lane part of the weight offset
+    const unsigned rvoff = (unsigned)q * SPC * 4;      // quarter part of the row-table offset
+    unsigned wsoff[NJ], rsoff[NJ];                     // scalar parts at chunk 0
 #pragma unroll
     for (int jj = 0; jj < NJ; ++jj) {
         int rb = rb0 + jj;
         if (rb >= p.n_rowblocks) rb = p.n_rowblocks - 1;
         const int j = rb / p.rbpt;
-        wfp[jj] = p.wfrag + ((size_t)rb * p.nchunks * 64 + lane) * SPC;
-        rwp[jj] = p.rows + ((size_t)j * p.nchunks * 4 + q) * ROWB;
+        wsoff[jj] = (unsigned)rb * p.nchunks * (64 * SPC * 4);
+        rsoff[jj] = (unsigned)j * p.nchunks * (4 * SPC * 4);
     }
+    auto load_ops = [&](StepOps<SPC>& o, int jj, int c) {
+        unsigned w[SPC];
+        load_words<SPC>(w, wr, wvoff, wsoff[jj] + (unsigned)c * (64 * SPC * 4));
+#pragma unroll
+        for (int s = 0; s < SPC; ++s) o.a[s] = __uint_as_float(w[s]);
+        load_words<SPC>(o.row, rr, rvoff, rsoff[jj] + (unsigned)c * (4 * SPC * 4));
+    };
 
     f4 acc[NJ][NBLK];
 #pragma unroll
@@ -270,61 +278,75 @@ __global__ __launch_bounds__(256) void nm_conv_kernel(const ConvParams p)
 #pragma unroll
         for (int b = 0; b < NBLK; ++b) acc[jj][b] = f4{0.f, 0.f, 0.f, 0.f};
 
-    StepOps<SPC> cur[NJ], nxt[NJ];
+    StepOps<SPC> opsA[NJ], opsB[NJ];
 
     // Prologue: operands of chunk 0, strip of chunk 0 into LDS, strip of chunk 1
     // into registers.  The operand loads go out first so that the wait for the
     // strip also covers them.
 #pragma unroll
-    for (int jj = 0; jj < NJ; ++jj) load_ops<SPC>(cur[jj], wfp[jj], rwp[jj]);
+    for (int jj = 0; jj < NJ; ++jj) load_ops(opsA[jj], jj, 0);
+    if constexpr (VEC) retap();
 #pragma unroll
     for (int it = 0; it < NST; ++it) fetch_item(it);
     fetch_advance();
 #pragma unroll
-    for (int it = 0; it < NST; ++it) stash_item(it, 0);
+    for (int it = 0; it < NST; ++it) stash_item(it, lds);
 #pragma unroll
     for (int it = 0; it < NST; ++it) fetch_item(it);
     fetch_advance();
     __syncthreads();
 
     constexpr int TOT = NJ * SPC;          // k-steps per chunk for this wavefront
-    constexpr int DEPTH = NSEG == 1 ? 2 : 1;   // LDS reads run this many k-steps ahead
+    constexpr int DEPTH = NBLK <= 4 ? 2 : 1;   // LDS reads run this many k-steps ahead
     constexpr int RING = DEPTH + 1;
     constexpr int NM = TOT * NBLK;         // MFMAs per chunk for this wavefront
     // Staging work of one iteration, cut into tasks that are dealt out behind the
-    // MFMAs: write item i of the strip held in registers to LDS, fetch item i of
-    // the strip two chunks ahead, load the operands of the next chunk, advance.
+    // MFMAs: load the operands of the next chunk, write item i of the strip held
+    // in registers to LDS, fetch item i of the strip two chunks ahead, advance.
     constexpr int NTASK = 2 * NST + NJ + 1;
 
-    // Steady state, one iteration per chunk c, no branch inside:
-    //   registers `st` (chunk c+1, fetched one iteration ago) go to the other LDS
-    //   buffer; the fetch of chunk c+2 and the operands of chunk c+1 are issued;
-    //   chunk c is contracted out of LDS.  Past the last chunk the same code
-    //   re-fetches the last chunk and writes it to the buffer nobody reads.
-    for (int c = 0; c < p.nchunks; ++c) {
+    // lane parts of the three kinds of LDS read (bytes)
+    const unsigned lane128 = (unsigned)(wpix + n * 4) * 4;
+    const unsigned lane64 = (unsigned)(wpix + OFF2 + n * 2) * 4;
+    const unsigned lane32 = (unsigned)(wpix + OFF1 + n) * 4;
+
+    // One chunk: registers `st` (chunk c+1, fetched one iteration ago) go to the
+    // other LDS buffer; the fetch of chunk c+2 and the operands of chunk c+1 are
+    // issued; chunk c is contracted out of LDS.  No branch except the per-tap
+    // one.  Past the last chunk the same code re-fetches the last chunk and
+    // writes it to the buffer nobody reads.
+    auto chunk = [&](int c, const int parity, StepOps<SPC> (&cur)[NJ], StepOps<SPC> (&nxt)[NJ]) {
         const int cn = c + 1 < p.nchunks ? c + 1 : c;
-        const int nb = (c + 1) & 1;
+        float* const wbuf = lds + (parity ^ 1) * (CK * SP);
+        const unsigned rbuf = (unsigned)(parity * (CK * SP) * 4);
+        const unsigned l128 = lane128 + rbuf, l64 = lane64 + rbuf, l32 = lane32 + rbuf;
         auto task = [&](int i) {
-            if (i < NST) {
-                stash_item(i, nb);
-            } else if (i < 2 * NST) {
-                fetch_item(i - NST);
-            } else if (i < 2 * NST + NJ) {
-                const int jj = i - 2 * NST;
-                load_ops<SPC>(nxt[jj], wfp[jj] + (size_t)cn * 64 * SPC, rwp[jj] + (size_t)cn * 4 * ROWB);
+            if (i < NJ) {
+                load_ops(nxt[i], i, cn);
+            } else if (i < NJ + NST) {
+                stash_item(i - NJ, wbuf);
+            } else if (i < NJ + 2 * NST) {
+                fetch_item(i - NJ - NST);
             } else {
                 fetch_advance();
             }
         };
-
-        const float* buf = lds + (c & 1) * (CK * SP) + wpix + n * 4;
-        f4 bv[RING][NSEG];
-        auto read_b = [&](int t, f4 (&dst)[NSEG]) {
+        float bv[RING][NBLK];
+        auto read_b = [&](int t, float (&dst)[NBLK]) {
             const int jj = t / SPC, s = t % SPC;
-            const unsigned ro = (cur[jj].rw[s >> 2] >> (8 * (s & 3))) & 0xffu;
-            const float* bp = buf + ro * SP;
+            const unsigned row = cur[jj].row[s];
+            const char* base8 = reinterpret_cast<const char*>(lds);
 #pragma unroll
-            for (int seg = 0; seg < NSEG; ++seg) dst[seg] = *reinterpret_cast<const f4*>(bp + seg * 64);
+            for (int seg = 0; seg < NF; ++seg) {
+                const f4 v = *reinterpret_cast<const f4*>(base8 + (__umul24(row, SP * 4) + l128) + seg * 256);
+                dst[seg * 4 + 0] = v.x; dst[seg * 4 + 1] = v.y; dst[seg * 4 + 2] = v.z; dst[seg * 4 + 3] = v.w;
+            }
+            if constexpr (R >= 2) {
+                const f2 v = *reinterpret_cast<const f2*>(base8 + (__umul24(row, SP * 4) + l64));
+                dst[NF * 4 + 0] = v.x; dst[NF * 4 + 1] = v.y;
+            }
+            if constexpr (R == 1 || R == 3)
+                dst[NBLK - 1] = *reinterpret_cast<const float*>(base8 + (__umul24(row, SP * 4) + l32));
         };
 #pragma unroll
         for (int t = 0; t < DEPTH && t < TOT; ++t) read_b(t, bv[t % RING]);
@@ -338,21 +360,30 @@ __global__ __launch_bounds__(256) void nm_conv_kernel(const ConvParams p)
 #pragma unroll
             for (int b = 0; b < NBLK; ++b) {
                 const int m = t * NBLK + b;
-                acc[jj][b] = __builtin_amdgcn_mfma_f32_16x16x4f32(a, bv[t % RING][b >> 2][b & 3], acc[jj][b], 0, 0, 0);
-                // a slice of the staging work issues while this MFMA occupies the matrix pipe
+                acc[jj][b] = __builtin_amdgcn_mfma_f32_16x16x4f32(a, bv[t % RING][b], acc[jj][b], 0, 0, 0);
 #pragma unroll
                 for (int i = m * NTASK / NM; i < (m + 1) * NTASK / NM; ++i) task(i);
                 __builtin_amdgcn_sched_barrier(0);
             }
         }
-#pragma unroll
-        for (int jj = 0; jj < NJ; ++jj) cur[jj] = nxt[jj];
         __syncthreads();
+    };
+
+    int c = 0;
+    for (; c + 1 < p.nchunks; c += 2) {
+        chunk(c, 0, opsA, opsB);
+        chunk(c + 1, 1, opsB, opsA);
     }
+    if (c < p.nchunks) chunk(c, 0, opsA, opsB);
 
     // ---- epilogue: bias, ReLU, cast, NHWC store ------------------------------
     TOUT* __restrict__ y = reinterpret_cast<TOUT*>(p.y);
     const bool fast = (p.tile % 4 == 0) && (p.Cout % 4 == 0);
+    auto pixel_of = [&](int b) {   // pixel (inside the wavefront's range) of MFMA block b for this lane
+        if (b < 4 * NF) return (b >> 2) * 64 + n * 4 + (b & 3);
+        if (R >= 2 && b < 4 * NF + 2) return OFF2 + n * 2 + (b - 4 * NF);
+        return OFF1 + n;
+    };
 #pragma unroll
     for (int jj = 0; jj < NJ; ++jj) {
         const int rb = rb0 + jj;
@@ -367,7 +398,7 @@ __global__ __launch_bounds__(256) void nm_conv_kernel(const ConvParams p)
             if (p.bias) bb = *reinterpret_cast<const f4*>(p.bias + co);
 #pragma unroll
             for (int b = 0; b < NBLK; ++b) {
-                const int pp = p0 + wpix + (b >> 2) * 64 + n * 4 + (b & 3);
+                const int pp = p0 + wpix + pixel_of(b);
                 if (pp >= p.P) continue;
                 f4 v = acc[jj][b] + bb;
                 if (p.relu) {
@@ -379,7 +410,7 @@ __global__ __launch_bounds__(256) void nm_conv_kernel(const ConvParams p)
         } else {
 #pragma unroll
             for (int b = 0; b < NBLK; ++b) {
-                const int pp = p0 + wpix + (b >> 2) * 64 + n * 4 + (b & 3);
+                const int pp = p0 + wpix + pixel_of(b);
                 if (pp >= p.P) continue;
 #pragma unroll
                 for (int r = 0; r < 4; ++r) {
@@ -393,11 +424,11 @@ __global__ __launch_bounds__(256) void nm_conv_kernel(const ConvParams p)
     }
 }
 
-template <int BP, int WP, int NJ, int CK, int SPC, bool VEC, typename TIN, typename TOUT>
+template <int NBLK, int WP, int NJ, int CK, int SPC, bool VEC, typename TIN, typename TOUT>
 int launch_t(const ConvParams& p, hipStream_t s)
 {
-    auto kern = nm_conv_kernel<BP, WP, NJ, CK, SPC, VEC, TIN, TOUT>;
-    constexpr size_t lds = (size_t)2 * CK * (BP + 4) * sizeof(float);
+    auto kern = nm_conv_kernel<NBLK, WP, NJ, CK, SPC, VEC, TIN, TOUT>;
+    constexpr size_t lds = (size_t)2 * CK * strip_stride(16 * NBLK * WP, CK, VEC) * sizeof(float);
     if (lds > 64 * 1024) {
         static hipError_t once = hipFuncSetAttribute(
             reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);

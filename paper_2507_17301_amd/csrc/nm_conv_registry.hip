@@ -11,11 +11,11 @@ struct Entry {
     LaunchFn bb;   // bf16 in, bf16 out
 };
 
-#define NM_ENTRY(BP, WP, NJ, CK, SPC, VEC)                                              \
-    {{"BP" #BP "_WP" #WP "_NJ" #NJ "_CK" #CK "_SPC" #SPC "_V" #VEC, BP, WP, NJ, CK, SPC, VEC}, \
-     &launch_t<BP, WP, NJ, CK, SPC, (VEC) != 0, float, float>,                          \
-     &launch_t<BP, WP, NJ, CK, SPC, (VEC) != 0, bf16_t, bf16_t>},
-#define NM_SHAPE_ENTRIES(BP, WP, NJ) NM_VEC_CHUNKS(NM_ENTRY, BP, WP, NJ)
+#define NM_ENTRY(NB, WP, NJ, CK, SPC, VEC)                                                     \
+    {{"NB" #NB "_WP" #WP "_NJ" #NJ "_CK" #CK "_SPC" #SPC "_V" #VEC, 16 * NB * WP, NB, WP, NJ, CK, SPC, VEC}, \
+     &launch_t<NB, WP, NJ, CK, SPC, (VEC) != 0, float, float>,                                 \
+     &launch_t<NB, WP, NJ, CK, SPC, (VEC) != 0, bf16_t, bf16_t>},
+#define NM_SHAPE_ENTRIES(NB, WP, NJ) NM_VEC_CHUNKS(NM_ENTRY, NB, WP, NJ)
 
 const Entry kEntries[] = {NM_SHAPES(NM_SHAPE_ENTRIES) NM_SCALAR_VARIANTS(NM_ENTRY)};
 constexpr int kCount = (int)(sizeof(kEntries) / sizeof(kEntries[0]));

@@ -63,10 +63,21 @@ inline ChunkGeom make_chunk_geom(int cin, int K, int CK, int vec)
 struct Prepack {
     ChunkGeom geom{};
     int SPC = 0;                      // k-steps per chunk (1, 2, 4 or 8)
-    int ROWB = 0;                     // bytes per (tile, chunk, quarter) in d_rows = max(SPC, 4)
-    unsigned char* d_rows = nullptr;  // [n_tiles][nchunks][4][ROWB]  byte s = LDS row (k - k0) used by step s
+    uint32_t* d_rows = nullptr;       // [n_tiles][nchunks][4][SPC]  LDS row (k - k0) that quarter q reads in step s
     float* d_wfrag = nullptr;         // [n_rowblocks][nchunks][64][SPC]  MFMA A-operand lane values
+    size_t rows_bytes = 0, wfrag_bytes = 0;
 };
+
+// LDS row stride (floats) of the im2col strip: the pixel tile, widened to what
+// the staging threads write, plus 4 so that rows stay 16-byte aligned and the
+// transposing writes spread over the banks.
+constexpr int strip_stride(int BP, int CK, bool vec)
+{
+    const int pstep = 256 / (CK / 4);
+    const int nit = (BP * (CK / 4) + 255) / 256;
+    const int cols = vec && nit * pstep > BP ? nit * pstep : BP;
+    return cols + 4;
+}
 
 }  // namespace nm
 
@@ -94,7 +105,7 @@ struct ConvParams {
     void* y;
     const float* bias;
     const float* wfrag;
-    const unsigned char* rows;
+    const uint32_t* rows;
     int B, H, W, Cin, Cout, Kh, Kw, Ho, Wo;
     int sh, sw, ph, pw, dh, dw;
     int relu;
@@ -105,11 +116,13 @@ struct ConvParams {
     int n_ptiles, n_cblocks, n_wg;   // pixel tiles, row-block groups, product
     int wg_per_xcd;
     unsigned x_bytes;  // size of x in bytes (< 2 GiB), the range of the buffer descriptor
+    unsigned wfrag_bytes, rows_bytes;
 };
 
 struct VariantDesc {
     const char* name;
-    int BP;    // pixels per workgroup
+    int BP;    // pixels per workgroup = 16 * NBLK * WP
+    int NBLK;  // 16-pixel MFMA blocks per wavefront
     int WP;    // waves along the pixel axis (the other 4/WP split the row blocks)
     int NJ;    // row blocks (16 output channels each) per wave
     int CK;    // K rows per LDS chunk

@@ -6,6 +6,6 @@
 namespace nm {
 struct bf16_t { unsigned short v; };
 
-template <int BP, int WP, int NJ, int CK, int SPC, bool VEC, typename TIN, typename TOUT>
+template <int NBLK, int WP, int NJ, int CK, int SPC, bool VEC, typename TIN, typename TOUT>
 int launch_t(const ConvParams& p, hipStream_t s);
 }  // namespace nm

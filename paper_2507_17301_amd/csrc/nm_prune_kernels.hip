@@ -105,13 +105,13 @@ __device__ inline void chunk_of(int k, int cin, int CK, int vec, int ncpt, int* 
 // One workgroup per column tile.  Kept columns are ascending in k, hence
 // grouped by chunk; the i-th kept column of a chunk becomes quarter i % 4 of
 // k-step i / 4 of that chunk.  Outputs (zero-initialised by the caller):
-//   rows [j][c][q][ROWB] bytes   LDS row of the kept column, byte s = step s
+//   rows [j][c][q][SPC] u32      LDS row of the kept column used by quarter q in step s
 //   wfrag[rb][c][lane][SPC]      weight for MFMA A-operand lane (q*16 + t)
 // err[0] is set if a chunk holds more than 4*SPC kept columns.
 __global__ __launch_bounds__(256) void build_prepack_kernel(
     const int32_t* __restrict__ idx, const float* __restrict__ vals, int kprime, int T, int rbpt,
-    int cin, int CK, int vec, int ncpt, int nchunks, int SPC, int ROWB,
-    unsigned char* __restrict__ rows, float* __restrict__ wfrag, int* __restrict__ err)
+    int cin, int CK, int vec, int ncpt, int nchunks, int SPC,
+    uint32_t* __restrict__ rows, float* __restrict__ wfrag, int* __restrict__ err)
 {
     extern __shared__ int sm_int[];
     int* cnt = sm_int;             // [nchunks]
@@ -141,7 +141,7 @@ __global__ __launch_bounds__(256) void build_prepack_kernel(
         const int i = kk - first[c];
         const int step = i >> 2, q = i & 3;
         if (step >= SPC) continue;
-        rows[(((size_t)j * nchunks + c) * 4 + q) * ROWB + step] = (unsigned char)r;
+        rows[(((size_t)j * nchunks + c) * 4 + q) * SPC + step] = (uint32_t)r;
         for (int sub = 0; sub < rbpt; ++sub) {
             const size_t rb = (size_t)j * rbpt + sub;
             for (int t = 0; t < 16; ++t) {
@@ -229,7 +229,7 @@ int run_build_prepack(nm_packed* wp, Prepack& pp, hipStream_t s)
     const size_t lds = (size_t)2 * g.nchunks * sizeof(int);
     hipLaunchKernelGGL(build_prepack_kernel, dim3(wp->n_tiles), dim3(256), lds, s, wp->d_idx,
                        wp->d_vals, wp->kprime, wp->tile, wp->rbpt, wp->cin, g.CK, g.vec, g.ncpt,
-                       g.nchunks, pp.SPC, pp.ROWB, pp.d_rows, pp.d_wfrag, d_err);
+                       g.nchunks, pp.SPC, pp.d_rows, pp.d_wfrag, d_err);
     hipError_t e = hipGetLastError();
     int h_err = 0;
     if (e == hipSuccess) e = hipMemcpyAsync(&h_err, d_err, sizeof(int), hipMemcpyDeviceToHost, s);
