@@ -40,6 +40,8 @@ def main():
     ap.add_argument("--batch", type=int, default=64)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-tune", action="store_true", help="use the untuned default variant")
+    ap.add_argument("--no-graph", action="store_true",
+                    help="launch the 53 kernels of a step one by one instead of replaying a HIP graph")
     ap.add_argument("--cache", default=None, help="tuning cache file to load/save")
     ap.add_argument("--report", default=None, help="write the per-layer table (JSON) here")
     args = ap.parse_args()
@@ -108,35 +110,51 @@ def main():
             nm.nm_conv2d(xs[i], packed[i], biases[i], l.stride, l.pad, l.dil, True, y=ys[i],
                          stream=stream)
 
+    # The launch-bound sequence of a step is captured once into a HIP graph (the
+    # library only enqueues kernels, so it can be captured) and replayed per step.
+    step()
+    torch.cuda.synchronize()
+    graph = None
+    if not args.no_graph:
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            nonlocal_stream = torch.cuda.current_stream()
+            for i, l in enumerate(layers):
+                nm.nm_conv2d(xs[i], packed[i], biases[i], l.stride, l.pad, l.dil, True, y=ys[i],
+                             stream=nonlocal_stream)
+    run_step = graph.replay if graph is not None else step
+
     for _ in range(args.warmup):
-        step()
+        run_step()
     torch.cuda.synchronize()
     e0 = torch.cuda.Event(enable_timing=True)
     e1 = torch.cuda.Event(enable_timing=True)
     t_host0 = time.time()
     e0.record(stream)
     for _ in range(args.steps):
-        step()
+        run_step()
     e1.record(stream)
     torch.cuda.synchronize()
     t_host = time.time() - t_host0
     ms_step = e0.elapsed_time(e1) / args.steps
     ms_step_host = t_host * 1e3 / args.steps
 
-    # ---- per-layer kernel durations (HIP events on the launch stream) --------
-    reps = 5
-    per_layer = []
-    for i, l in enumerate(layers):
-        a = torch.cuda.Event(enable_timing=True)
-        b = torch.cuda.Event(enable_timing=True)
-        nm.nm_conv2d(xs[i], packed[i], biases[i], l.stride, l.pad, l.dil, True, y=ys[i], stream=stream)
-        a.record(stream)
-        for _ in range(reps):
+    # ---- per-layer kernel durations, in the stack (HIP events on the launch stream):
+    # an event after every layer of a few extra steps, so that each layer is timed
+    # with the caches in the state the stack leaves them in
+    inst_steps = 3
+    marks = [[torch.cuda.Event(enable_timing=True) for _ in range(len(layers) + 1)]
+             for _ in range(inst_steps)]
+    for k in range(inst_steps):
+        marks[k][0].record(stream)
+        for i, l in enumerate(layers):
             nm.nm_conv2d(xs[i], packed[i], biases[i], l.stride, l.pad, l.dil, True, y=ys[i],
                          stream=stream)
-        b.record(stream)
-        b.synchronize()
-        ms = a.elapsed_time(b) / reps
+            marks[k][i + 1].record(stream)
+    torch.cuda.synchronize()
+    per_layer = []
+    for i, l in enumerate(layers):
+        ms = sorted(marks[k][i].elapsed_time(marks[k][i + 1]) for k in range(inst_steps))[inst_steps // 2]
         eff = l.effective_flops(B)
         byts = l.algorithmic_bytes(B, esize, esize)
         t_flop = eff / (PEAK_TFLOPS[args.dtype] * 1e12) * 1e3
@@ -184,7 +202,8 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": args.dtype, "data": "synthetic",
         "config": {"workload": f"resnet50_conv_stack_53layers_2of4_T16_batch{B}_{args.dtype}",
-                   "batch": B, "layers": len(layers), "tuned": not args.no_tune},
+                   "batch": B, "layers": len(layers), "tuned": not args.no_tune,
+                   "launch": "hip_graph_replay" if graph is not None else "one_launch_per_layer"},
         "setup": {"prune_pack_s": prune_s, "autotune_s": tune_s},
         "roofline": roofline, "cpu_baseline": cpu,
     }

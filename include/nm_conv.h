@@ -129,8 +129,10 @@ int nm_conv2d(const void* x_dev, nm_dtype_t x_dtype, int b, int h, int w, int ci
  * nm_autotune -- per-layer choice of the fastest kernel variant (section 3.3:
  * every candidate is run on the target and the fastest kept).  Runs each legal
  * variant for this shape on library-allocated scratch tensors (pseudo-random
- * input), times it with HIP events on `hip_stream`, stores the winner in the
- * process-wide cache keyed by (shape, N:M, T, dtypes) and returns it.
+ * input; a ring of input/output sets of about 768 MB so that, as inside a
+ * network, no launch finds its tensors in the last-level cache), times it with
+ * HIP events on `hip_stream`, stores the winner in the process-wide cache keyed
+ * by (shape, N:M, T, dtypes) and returns it.
  * Synchronous.  A cached shape returns immediately with the cached result.
  *   chosen_variant, best_ms   may be NULL
  */

@@ -59,7 +59,8 @@ size_t lds_bytes(const VariantDesc& d)
 const Prepack* find_prepack(const nm_packed* wp, const VariantDesc& d)
 {
     for (const Prepack& pp : wp->prepacks)
-        if (pp.geom.CK == d.CK && pp.geom.vec == d.vec && pp.SPC == d.SPC) return &pp;
+        if (pp.geom.CK == d.CK && pp.geom.vec == d.vec && pp.SPC == d.SPC && (d.vec || pp.d_ktab))
+            return &pp;
     return nullptr;
 }
 
@@ -133,7 +134,7 @@ void fill_params(ConvParams& p, const VariantDesc& d, const Prepack& pp, const n
                  int sh, int sw, int ph, int pw, int dh, int dw, int relu, size_t es)
 {
     p.x = x; p.y = y; p.bias = bias;
-    p.wfrag = pp.d_wfrag; p.rows = pp.d_rows;
+    p.wfrag = pp.d_wfrag; p.rows = pp.d_rows; p.ktab = pp.d_ktab;
     p.wfrag_bytes = (unsigned)pp.wfrag_bytes; p.rows_bytes = (unsigned)pp.rows_bytes;
     p.B = b; p.H = h; p.W = w; p.Cin = wp->cin; p.Cout = wp->cout; p.Kh = wp->kh; p.Kw = wp->kw;
     p.Ho = g.Ho; p.Wo = g.Wo;
@@ -219,6 +220,7 @@ void free_packed(nm_packed* wp)
     for (Prepack& pp : wp->prepacks) {
         (void)hipFree(pp.d_rows);
         (void)hipFree(pp.d_wfrag);
+        (void)hipFree(pp.d_ktab);
     }
     delete wp;
 }
@@ -348,6 +350,18 @@ int nm_prune(const float* w, int cout, int kh, int kw, int cin, int n, int m, in
         NM_TRY_HIP(hipMemsetAsync(ref.d_wfrag, 0, wf_bytes, s), NM_ERR_HIP);
         rc = run_build_prepack(wp, ref, s);
         if (rc != NM_OK) return fail(rc);
+        if (!g.vec) {
+            // decode table of the flat k axis (layout only: which tap and channel row k is)
+            if (kh > 255 || kw > 255 || cin > 65535) continue;
+            std::vector<uint32_t> kt((size_t)g.nchunks * g.CK, 0xffffffffu);
+            for (int k = 0; k < wp->K; ++k) {
+                const int tap = k / cin, ci = k - tap * cin;
+                kt[k] = (uint32_t)(tap / kw) | ((uint32_t)(tap % kw) << 8) | ((uint32_t)ci << 16);
+            }
+            NM_TRY_HIP(hipMalloc(&ref.d_ktab, kt.size() * sizeof(uint32_t)), NM_ERR_ALLOC);
+            NM_TRY_HIP(hipMemcpy(ref.d_ktab, kt.data(), kt.size() * sizeof(uint32_t), hipMemcpyHostToDevice),
+                       NM_ERR_HIP);
+        }
     }
 #undef NM_TRY_HIP
     (void)hipFree(d_w);
@@ -519,11 +533,18 @@ int nm_autotune(nm_dtype_t xdt, int b, int h, int w, int cin, const nm_packed_t*
     hipStream_t s = (hipStream_t)stream;
     const size_t es = xdt == NM_F32 ? 4 : 2;
     const size_t xn = (size_t)b * h * w * cin, yn = (size_t)g.P * wp->cout;
-    void *dx = nullptr, *dy = nullptr;
+    // Cold-cache protocol: in a network every layer finds the 256 MB last-level
+    // cache full of other layers' data, so the candidates are timed on a ring
+    // of input/output sets (about 768 MB in total) and no launch reuses the
+    // set of a recent one.
+    const size_t xbytes = (xn * es + 255) & ~(size_t)255, ybytes = (yn * es + 255) & ~(size_t)255;
+    const size_t pool = (size_t)768 << 20;
+    int nbuf = (int)std::min<size_t>(64, std::max<size_t>(1, pool / (xbytes + ybytes)));
+    char* dpool = nullptr;
     float* dbias = nullptr;
     hipEvent_t e0 = nullptr, e1 = nullptr;
     auto cleanup = [&]() {
-        (void)hipFree(dx); (void)hipFree(dy); (void)hipFree(dbias);
+        (void)hipFree(dpool); (void)hipFree(dbias);
         if (e0) (void)hipEventDestroy(e0);
         if (e1) (void)hipEventDestroy(e1);
     };
@@ -536,27 +557,34 @@ int nm_autotune(nm_dtype_t xdt, int b, int h, int w, int cin, const nm_packed_t*
             return code;                                                         \
         }                                                                        \
     } while (0)
-    NM_TRY(hipMalloc(&dx, xn * es), NM_ERR_ALLOC);
-    NM_TRY(hipMalloc(&dy, yn * es), NM_ERR_ALLOC);
+    NM_TRY(hipMalloc(&dpool, (xbytes + ybytes) * nbuf), NM_ERR_ALLOC);
     if (has_bias) {
         NM_TRY(hipMalloc(&dbias, wp->cout * sizeof(float)), NM_ERR_ALLOC);
         rc = run_fill_random(dbias, wp->cout, NM_F32, 7u, s);
         if (rc != NM_OK) { cleanup(); return rc; }
     }
-    rc = run_fill_random(dx, xn, xdt, 1u, s);
-    if (rc != NM_OK) { cleanup(); return rc; }
+    for (int i = 0; i < nbuf; ++i) {
+        rc = run_fill_random(dpool + (xbytes + ybytes) * i, xn, xdt, 1u + i, s);
+        if (rc != NM_OK) { cleanup(); return rc; }
+    }
     NM_TRY(hipEventCreate(&e0), NM_ERR_HIP);
     NM_TRY(hipEventCreate(&e1), NM_ERR_HIP);
 
     int best_v = -1;
     float best = 0.f;
+    int turn = 0;
     for (int v = 0; v < variant_count(); ++v) {
         if (!variant_legal(v, wp)) continue;
         const VariantDesc& d = variant_desc(v);
         ConvParams p;
-        fill_params(p, d, *find_prepack(wp, d), wp, dx, dy, dbias, b, h, w, g, sh, sw, ph, pw, dh, dw, relu, es);
-        // warm-up, then the median of 5 timed groups
-        rc = launch_conv(v, xdt, ydt, p, s);
+        auto launch_next = [&]() {
+            char* set = dpool + (xbytes + ybytes) * (turn++ % nbuf);
+            fill_params(p, d, *find_prepack(wp, d), wp, set, set + xbytes, dbias, b, h, w, g, sh, sw, ph, pw,
+                        dh, dw, relu, es);
+            return launch_conv(v, xdt, ydt, p, s);
+        };
+        // warm-up (code object, attributes), then the median of 5 timed groups
+        rc = launch_next();
         if (rc != NM_OK) { cleanup(); return rc; }
         NM_TRY(hipStreamSynchronize(s), NM_ERR_HIP);
         float t[5];
@@ -564,7 +592,7 @@ int nm_autotune(nm_dtype_t xdt, int b, int h, int w, int cin, const nm_packed_t*
         for (int r = 0; r < 5; ++r) {
             NM_TRY(hipEventRecord(e0, s), NM_ERR_HIP);
             for (int i = 0; i < reps; ++i) {
-                rc = launch_conv(v, xdt, ydt, p, s);
+                rc = launch_next();
                 if (rc != NM_OK) { cleanup(); return rc; }
             }
             NM_TRY(hipEventRecord(e1, s), NM_ERR_HIP);

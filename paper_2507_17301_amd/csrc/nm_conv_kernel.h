@@ -157,7 +157,6 @@ __global__ __launch_bounds__(256) void nm_conv_kernel(const ConvParams p)
     constexpr int NIT = VEC ? (BP * QPR + 255) / 256 : 1;
     static_assert(VEC || (256 % BP == 0 || BP % 256 == 0), "scalar staging keeps one pixel per thread");
     constexpr int NITS = VEC ? 1 : (BP * CK) / 256;   // scalar items per thread
-    constexpr int RSTEP = BP >= 256 ? 1 : 256 / BP;
     constexpr int NST = VEC ? NIT : NITS;             // staging items per thread and chunk
 
     const int quad = tid % QPR;
@@ -209,13 +208,13 @@ __global__ __launch_bounds__(256) void nm_conv_kernel(const ConvParams p)
             // the range check sees the whole address
             st[it] = buf_load4(xr, voff[it] + (unsigned)(f_ci0 * ES), 0, xtag);
         } else {
-            const int r = r0s + it * RSTEP;
+            // row r of the chunk is the same for the whole wavefront, so its
+            // (tap row, tap column, channel) comes from a table through scalar loads
+            const int r = r0s * NITS + it;
             const int k = f_c * CK + r;
-            const int tap = k / p.Cin;
-            const int ci = k - tap * p.Cin;
-            const int kh = tap / p.Kw;
-            const int kw = tap - kh * p.Kw;
-            const int dhh = kh * p.dh, dww = kw * p.dw;
+            const unsigned e = p.ktab[k];
+            const int dhh = (int)(e & 0xffu) * p.dh, dww = (int)((e >> 8) & 0xffu) * p.dw;
+            const int ci = (int)(e >> 16);
             const int hi = hi0[0] + dhh, wi = wi0[0] + dww;
             const bool inb = (k < p.K) & ((unsigned)hi < (unsigned)p.H) & ((unsigned)wi < (unsigned)p.W);
             const unsigned off = base[0] + (unsigned)((dhh * p.W + dww) * p.Cin + ci) * ES;
@@ -246,7 +245,7 @@ __global__ __launch_bounds__(256) void nm_conv_kernel(const ConvParams p)
             d[2 * SP] = st[it].z;
             d[3 * SP] = st[it].w;
         } else {
-            dst[(r0s + it * RSTEP) * SP + pl0] = sts[it];
+            dst[(r0s * NITS + it) * SP + pl0] = sts[it];
         }
     };
 

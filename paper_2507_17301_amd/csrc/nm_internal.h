@@ -66,6 +66,7 @@ struct Prepack {
     uint32_t* d_rows = nullptr;       // [n_tiles][nchunks][4][SPC]  LDS row (k - k0) that quarter q reads in step s
     float* d_wfrag = nullptr;         // [n_rowblocks][nchunks][64][SPC]  MFMA A-operand lane values
     size_t rows_bytes = 0, wfrag_bytes = 0;
+    uint32_t* d_ktab = nullptr;       // scalar mode only: [nchunks*CK] (kh | kw << 8 | ci << 16) per im2col row
 };
 
 // LDS row stride (floats) of the im2col strip: the pixel tile, widened to what
@@ -106,6 +107,7 @@ struct ConvParams {
     const float* bias;
     const float* wfrag;
     const uint32_t* rows;
+    const uint32_t* ktab;   // scalar mode: [nchunks*CK] (kh | kw << 8 | ci << 16) of each im2col row
     int B, H, W, Cin, Cout, Kh, Kw, Ho, Wo;
     int sh, sw, ph, pw, dh, dw;
     int relu;

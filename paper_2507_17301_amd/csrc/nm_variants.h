@@ -11,7 +11,11 @@
 // X(NBLK, WP, NJ)
 #define NM_SHAPES(X) \
     X(8, 1, 2) X(8, 1, 4) X(4, 2, 4) X(4, 2, 2) X(8, 2, 2) X(4, 4, 4) \
-    X(4, 1, 2) X(4, 1, 4) X(4, 1, 1)
+    X(4, 1, 2) X(4, 1, 4) X(4, 1, 1)                                  \
+    X(1, 4, 1) X(1, 4, 2) X(2, 1, 1) X(2, 1, 2) X(2, 2, 1) X(2, 2, 2) \
+    X(3, 1, 1) X(3, 1, 2) X(5, 1, 1) X(6, 1, 1) X(6, 1, 2) X(7, 1, 1) \
+    X(7, 1, 2) X(7, 2, 1) X(8, 1, 1) X(10, 1, 1) X(12, 1, 1)          \
+    X(13, 1, 1) X(13, 1, 2) X(14, 1, 1) X(16, 1, 1) X(16, 1, 2)
 
 // Y(NBLK, WP, NJ, CK, SPC, VEC)
 #define NM_VEC_CHUNKS(Y, NB, WP, NJ)                                              \
