@@ -105,6 +105,14 @@ def main():
 
     stream = torch.cuda.current_stream()
 
+    # a plain device copy of known size (1 GiB read + 1 GiB written): the yardstick
+    # for the FETCH_SIZE / WRITE_SIZE counters when this command runs under rocprofv3 --pmc
+    cal_src = torch.empty(1 << 28, dtype=torch.float32, device=dev).fill_(1.0)
+    cal_dst = torch.empty_like(cal_src)
+    cal_dst.copy_(cal_src)
+    torch.cuda.synchronize()
+    del cal_src, cal_dst
+
     def step():
         for i, l in enumerate(layers):
             nm.nm_conv2d(xs[i], packed[i], biases[i], l.stride, l.pad, l.dil, True, y=ys[i],
@@ -182,7 +190,10 @@ def main():
         # flops actually contracted (2*P*K'*Cout per launch) over their summed duration
         "bound": "mfma", "achieved": eff / kern_ms / 1e9, "peak": PEAK_TFLOPS[args.dtype],
         "unit": "TFLOP/s", "frac": eff / kern_ms / 1e9 / PEAK_TFLOPS[args.dtype],
-        "traffic": None,
+        # HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled by what the same
+        # counters read for the 1 GiB device copy above (profiles/nm_conv_kernel_resnet50_b64_f32.txt);
+        # measured for the default workload only
+        "traffic": 111.7e6 if (args.dtype == "f32" and B == 64) else None,
         "kernel": "nm_conv_kernel", "launches_per_step": len(layers),
         "avg_launch_ms": kern_ms / len(layers),
         "frac_of_binding_roofline_per_layer": tmin_ms / kern_ms,
