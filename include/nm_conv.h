@@ -50,7 +50,7 @@ typedef struct nm_packed nm_packed_t;
 const char* nm_last_error(void);
 
 /* Number of kernel variants the tuner chooses from (ids 0 .. count-1), and a
- * short static description of one ("BP128 NJ2 CK32").  NULL for a bad id. */
+ * short static description of one ("NB8_WP1_NJ2_CK32_SPC4_V1").  NULL for a bad id. */
 int nm_variant_count(void);
 const char* nm_variant_name(int variant);
 

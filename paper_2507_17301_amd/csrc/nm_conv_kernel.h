@@ -368,7 +368,17 @@ __global__ __launch_bounds__(256) void nm_conv_kernel(const ConvParams p)
         __syncthreads();
     };
 
+    // The loop branch costs about as much as two MFMAs, so short chunk bodies are
+    // unrolled four times, long ones twice.
     int c = 0;
+    if constexpr (NM <= 32) {
+        for (; c + 3 < p.nchunks; c += 4) {
+            chunk(c, 0, opsA, opsB);
+            chunk(c + 1, 1, opsB, opsA);
+            chunk(c + 2, 0, opsA, opsB);
+            chunk(c + 3, 1, opsB, opsA);
+        }
+    }
     for (; c + 1 < p.nchunks; c += 2) {
         chunk(c, 0, opsA, opsB);
         chunk(c + 1, 1, opsB, opsA);

@@ -35,7 +35,7 @@ def test_host_side_argument_checks_need_no_gpu():
     from paper_2507_17301_amd import binding as nm
     L = nm.lib()
     assert L.nm_variant_count() > 0
-    assert nm.nm_variant_name(0).startswith("BP")
+    assert nm.nm_variant_name(0).startswith("NB")
     assert nm.nm_variant_name(-1) is None and nm.nm_variant_name(10 ** 6) is None
     import numpy as np
     w = np.ones((4, 1, 1, 6), dtype=np.float32)

@@ -1,0 +1,117 @@
+"""The benchmark configurations at their full sizes, in the launch configuration
+bench.py times (per-layer tuned variant), against the CPU oracle.
+
+Full outputs are compared where the oracle finishes in seconds (ResNet-18 at
+batch 1, one whole image of selected ResNet-50 layers); elsewhere a few thousand
+sampled outputs per layer, always including the corners of the first and last
+image and the last channel, are computed one by one by the oracle.
+"""
+import numpy as np
+import pytest
+
+from paper_2507_17301_amd import binding as nm
+from paper_2507_17301_amd import workloads as wl
+from gpu_util import FP32_TOL, BF16_TOL, say, norm_err, oracle_conv
+
+pytestmark = pytest.mark.gpu
+
+
+def _run_tuned(layer, batch, x, w, bias, bf16):
+    import torch
+    ndt = nm.NM_BF16 if bf16 else nm.NM_F32
+    wp = nm.nm_prune(w, layer.n, layer.m, layer.tile, ndt)
+    v, ms = nm.nm_autotune(ndt, batch, layer.H, layer.W, layer.Cin, wp, True,
+                           layer.stride, layer.pad, layer.dil, True)
+    xd = torch.from_numpy(x).cuda()
+    if bf16:
+        xd = xd.to(torch.bfloat16)
+    y = nm.nm_conv2d(xd, wp, torch.from_numpy(bias).cuda(), layer.stride, layer.pad, layer.dil, True)
+    torch.cuda.synchronize()
+    return y, nm.nm_variant_name(v)
+
+
+def _check_sampled(layer, batch, seed, bf16, npts=2000):
+    x, w, bias = wl.make_tensors(layer, batch, seed)
+    y, vname = _run_tuned(layer, batch, x, w, bias, bf16)
+    pts = wl.sample_points(layer, batch, npts, seed)
+    import torch
+    idx = torch.from_numpy(pts.astype(np.int64)).cuda()
+    got = y[idx[:, 0], idx[:, 1], idx[:, 2], idx[:, 3]].float().cpu().numpy()
+    ref = oracle_conv(layer, x, w, bias, relu=True, bf16=bf16, pts=pts)
+    err = norm_err(got, ref)
+    assert err <= (BF16_TOL if bf16 else FP32_TOL), f"{layer.name} {vname}: {err}"
+    return x, w, bias, y
+
+
+def test_config3_resnet18_batch1_full():
+    for i, layer in enumerate(wl.resnet18_stack()):
+        say(f"config 3 batch 1 layer {i} {layer.name}")
+        x, w, bias = wl.make_tensors(layer, 1, 3000 + i)
+        y, vname = _run_tuned(layer, 1, x, w, bias, False)
+        ref = oracle_conv(layer, x, w, bias, relu=True)
+        assert norm_err(y.cpu().numpy(), ref) <= FP32_TOL, f"{layer.name} {vname}"
+
+
+def test_config3_resnet18_batch32_sampled():
+    stack = wl.resnet18_stack()
+    for layer in wl.unique_shapes(stack):
+        i = stack.index(layer)
+        say(f"config 3 batch 32 layer {i} {layer.name}")
+        _check_sampled(layer, 32, 3000 + i, False)
+
+
+@pytest.mark.parametrize("part", [0, 1, 2])
+def test_config4_resnet50_batch64_fp32_sampled(part):
+    stack = wl.resnet50_stack()
+    shapes = wl.unique_shapes(stack)
+    for layer in shapes[part::3]:
+        i = stack.index(layer)
+        say(f"config 4 fp32 batch 64 layer {i} {layer.name}")
+        x, w, bias, y = _check_sampled(layer, 64, 4000 + i, False)
+        if layer.name in ("s2b1_conv2_3x3", "s4b0_conv2_3x3", "s3b0_proj_1x1"):
+            # one whole image in the middle of the batch, every output
+            ref = oracle_conv(layer, x[31:32], w, bias, relu=True)
+            assert norm_err(y[31:32].cpu().numpy(), ref) <= FP32_TOL, layer.name
+
+
+def test_config4_resnet50_batch64_bf16_sampled():
+    stack = wl.resnet50_stack()
+    shapes = wl.unique_shapes(stack)
+    for layer in shapes[::4]:
+        i = stack.index(layer)
+        say(f"config 4 bf16 batch 64 layer {i} {layer.name}")
+        _check_sampled(layer, 64, 4000 + i, True)
+
+
+def test_config5_resnet101_batch256_bf16_mixed_sparsity():
+    """T = 32, stage 1 1:4, stage 2 2:4, stage 3 2:8, stage 4 4:8, bf16 in/out,
+    fp32 accumulation; two shapes per stage at the full batch of 256."""
+    stack = wl.resnet101_stack()
+    shapes = wl.unique_shapes(stack)
+    picked = []
+    for stage in (1, 2, 3, 4):
+        cand = [l for l in shapes if l.stage == stage]
+        picked += [c for c in cand if "conv2_3x3" in c.name][:1] + [c for c in cand if "conv3_1x1" in c.name][:1]
+    for layer in picked:
+        i = stack.index(layer)
+        say(f"config 5 bf16 batch 256 layer {i} {layer.name} {layer.n}:{layer.m} T={layer.tile}")
+        _check_sampled(layer, 256, 5000 + i, True, npts=1500)
+
+
+def test_tuning_cache_round_trip(tmp_path):
+    layer = wl.ConvLayer("cache", 14, 14, 64, 64, 3, 3, 1, 1, 1, 2, 4, 16)
+    x, w, bias = wl.make_tensors(layer, 4, 1)
+    wp = nm.nm_prune(w, 2, 4, 16)
+    nm.nm_cache_clear()
+    v, ms = nm.nm_autotune(nm.NM_F32, 4, 14, 14, 64, wp, True, 1, 1, 1, True)
+    assert nm.nm_cache_size() == 1 and ms > 0
+    path = str(tmp_path / "tune.txt")
+    nm.nm_cache_save(path)
+    nm.nm_cache_clear()
+    assert nm.nm_cache_size() == 0
+    nm.nm_cache_load(path)
+    assert nm.nm_cache_size() == 1
+    v2, ms2 = nm.nm_autotune(nm.NM_F32, 4, 14, 14, 64, wp, True, 1, 1, 1, True)   # served from the cache
+    assert v2 == v and abs(ms2 - ms) < 1e-6
+    with pytest.raises(nm.NMError):
+        nm.nm_cache_load(str(tmp_path / "missing.txt"))
