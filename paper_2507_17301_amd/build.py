@@ -41,6 +41,15 @@ def _shapes():
     return [tuple(int(v) for v in m) for m in re.findall(r"X\((\d+),\s*(\d+),\s*(\d+)\)", body)]
 
 
+def _shapes16():
+    """(NBLK, WP, NJ, SHARE) of NM16_SHAPES in nm_variants.h."""
+    text = open(os.path.join(CSRC, "nm_variants.h")).read()
+    body = text[text.index("#define NM16_SHAPES(X)"):]
+    body = body[:body.index("// Y(")]
+    return [tuple(int(v) for v in m)
+            for m in re.findall(r"X\((\d+),\s*(\d+),\s*(\d+),\s*(\d+)\)", body)]
+
+
 def _jobs():
     jobs = []
     for src in ("nm_api.hip", "nm_prune_kernels.hip", "nm_conv_registry.hip"):
@@ -50,6 +59,11 @@ def _jobs():
         jobs.append((inst, os.path.join(OBJDIR, f"nm_conv_inst_{nb}_{wp}_{nj}.o"),
                      [f"-DNM_INST_NBLK={nb}", f"-DNM_INST_WP={wp}", f"-DNM_INST_NJ={nj}"]))
     jobs.append((inst, os.path.join(OBJDIR, "nm_conv_inst_scalar.o"), ["-DNM_INST_SCALAR"]))
+    inst16 = os.path.join(CSRC, "nm_conv16_inst.hip")
+    for nb, wp, nj, sh in _shapes16():
+        jobs.append((inst16, os.path.join(OBJDIR, f"nm_conv16_inst_{nb}_{wp}_{nj}_{sh}.o"),
+                     [f"-DNM_INST_NBLK={nb}", f"-DNM_INST_WP={wp}", f"-DNM_INST_NJ={nj}",
+                      f"-DNM_INST_SHARE={sh}"]))
     return jobs
 
 

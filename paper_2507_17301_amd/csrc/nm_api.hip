@@ -53,22 +53,34 @@ ShapeKey make_key(nm_dtype_t xdt, nm_dtype_t ydt, int b, int h, int w, const nm_
 
 size_t lds_bytes(const VariantDesc& d)
 {
+    if (d.kind == 1) {
+        const int opr = d.CK / 8, pstep = 256 / opr, nit = (d.BP * opr + 255) / 256;
+        const int rows = nit * pstep > d.BP ? nit * pstep : d.BP;
+        return (size_t)2 * rows * (d.CK * 2 + 4);
+    }
     return (size_t)2 * d.CK * strip_stride(d.BP, d.CK, d.vec != 0) * sizeof(float);
 }
 
 const Prepack* find_prepack(const nm_packed* wp, const VariantDesc& d)
 {
     for (const Prepack& pp : wp->prepacks)
-        if (pp.geom.CK == d.CK && pp.geom.vec == d.vec && pp.SPC == d.SPC && (d.vec || pp.d_ktab))
+        if (pp.kind == d.kind && pp.geom.CK == d.CK && pp.geom.vec == d.vec && pp.SPC == d.SPC &&
+            (d.vec || pp.d_ktab))
             return &pp;
     return nullptr;
 }
 
-bool variant_legal(int v, const nm_packed* wp)
+bool variant_legal(int v, const nm_packed* wp, nm_dtype_t xdt)
 {
     if (v < 0 || v >= variant_count()) return false;
     const VariantDesc& d = variant_desc(v);
     if (lds_bytes(d) > (size_t)kMaxLdsBytes) return false;
+    if (d.kind == 1) {
+        // bf16 matrix cores: bf16 tensors, weights already rounded to bf16, and a
+        // shared operand only for column tiles made of exactly two row blocks
+        if (xdt != NM_BF16 || wp->value_dtype != NM_BF16) return false;
+        if (d.share != 1 && d.share != wp->rbpt) return false;
+    }
     return find_prepack(wp, d) != nullptr;
 }
 
@@ -154,12 +166,12 @@ void fill_params(ConvParams& p, const VariantDesc& d, const Prepack& pp, const n
 // Deterministic default when the shape has not been tuned: a small model of
 // "rounds of workgroups x work per workgroup", preferring tiles that fill the
 // 256 CUs and reuse the staged strip across many row blocks.
-int heuristic_variant(const nm_packed* wp, int P)
+int heuristic_variant(const nm_packed* wp, int P, nm_dtype_t xdt)
 {
     int best = -1;
     double best_cost = 0;
     for (int v = 0; v < variant_count(); ++v) {
-        if (!variant_legal(v, wp)) continue;
+        if (!variant_legal(v, wp, xdt)) continue;
         const VariantDesc& d = variant_desc(v);
         const int rb_per_wg = (4 / d.WP) * d.NJ;
         const long n_pt = (P + d.BP - 1) / d.BP;
@@ -170,7 +182,8 @@ int heuristic_variant(const nm_packed* wp, int P)
         const long rounds = (n_wg + (long)kNumCU * occ - 1) / ((long)kNumCU * occ);
         const double mfma = (double)d.BP * rb_per_wg;            // per chunk step, relative
         const double stage = (double)d.BP * 2.0;                 // staging cost per chunk, relative
-        const double cost = (double)rounds * occ * (mfma + stage);
+        // the bf16 matrix-core kernel contracts several times faster where it applies
+        const double cost = (double)rounds * occ * (mfma + stage) * (d.kind == 1 ? 0.3 : 1.0);
         if (best < 0 || cost < best_cost * 0.999) {
             best = v;
             best_cost = cost;
@@ -322,30 +335,43 @@ int nm_prune(const float* w, int cout, int kh, int kw, int cin, int n, int m, in
     const bool vec_ok = cin % 4 == 0;
     for (int v = 0; v < variant_count(); ++v) {
         const VariantDesc& d = variant_desc(v);
-        if ((d.vec != 0) != vec_ok) continue;
+        if (d.kind == 1) {
+            if (value_dtype != NM_BF16 || cin % 8 != 0) continue;
+        } else if ((d.vec != 0) != vec_ok) {
+            continue;
+        }
         if (find_prepack(wp, d)) continue;
         const ChunkGeom g = make_chunk_geom(cin, wp->K, d.CK, d.vec);
-        const int need = (max_kept_per_chunk(wp, g) + 3) / 4;
-        // smallest instantiated SPC >= need for this (CK, vec)
+        const int per_step = d.kind == 1 ? 32 : 4;   // kept columns per k-step
+        const int need = (max_kept_per_chunk(wp, g) + per_step - 1) / per_step;
+        // smallest instantiated SPC >= need for this (kind, CK, mode)
         int pick = 0;
         for (int u = 0; u < variant_count(); ++u) {
             const VariantDesc& e = variant_desc(u);
-            if (e.CK == d.CK && e.vec == d.vec && e.SPC >= need && (pick == 0 || e.SPC < pick))
+            if (e.kind == d.kind && e.CK == d.CK && e.vec == d.vec && e.SPC >= need &&
+                (pick == 0 || e.SPC < pick))
                 pick = e.SPC;
         }
         if (pick == 0 || pick != d.SPC) continue;
         Prepack pp;
+        pp.kind = d.kind;
         pp.geom = g;
         pp.SPC = d.SPC;
-        const size_t rows_bytes = (size_t)wp->n_tiles * g.nchunks * 4 * pp.SPC * sizeof(uint32_t);
-        const size_t wf_bytes = (size_t)wp->n_rowblocks * g.nchunks * 64 * pp.SPC * sizeof(float);
-        if (wf_bytes >= 0x80000000ull) continue;   // operand streams are addressed through a 2 GiB window
+        size_t rows_bytes, wf_bytes;
+        if (d.kind == 1) {
+            rows_bytes = (size_t)wp->n_tiles * g.nchunks * pp.SPC * 4 * 8 * sizeof(uint32_t);
+            wf_bytes = (size_t)wp->n_rowblocks * g.nchunks * pp.SPC * 64 * 8 * sizeof(uint16_t);
+        } else {
+            rows_bytes = (size_t)wp->n_tiles * g.nchunks * 4 * pp.SPC * sizeof(uint32_t);
+            wf_bytes = (size_t)wp->n_rowblocks * g.nchunks * 64 * pp.SPC * sizeof(float);
+        }
+        if (wf_bytes >= 0x80000000ull || rows_bytes >= 0x80000000ull) continue;   // 2 GiB buffer windows
         pp.rows_bytes = rows_bytes;
         pp.wfrag_bytes = wf_bytes;
         NM_TRY_HIP(hipMalloc(&pp.d_rows, rows_bytes), NM_ERR_ALLOC);
         wp->prepacks.push_back(pp);   // owned by the handle from here on
         Prepack& ref = wp->prepacks.back();
-        NM_TRY_HIP(hipMalloc(&ref.d_wfrag, wf_bytes), NM_ERR_ALLOC);
+        NM_TRY_HIP(hipMalloc(reinterpret_cast<void**>(&ref.d_wfrag), wf_bytes), NM_ERR_ALLOC);
         NM_TRY_HIP(hipMemsetAsync(ref.d_rows, 0, rows_bytes, s), NM_ERR_HIP);
         NM_TRY_HIP(hipMemsetAsync(ref.d_wfrag, 0, wf_bytes, s), NM_ERR_HIP);
         rc = run_build_prepack(wp, ref, s);
@@ -459,7 +485,7 @@ int nm_variant_legal(int variant, const nm_packed_t* wp, nm_dtype_t xdt, nm_dtyp
         return NM_ERR_ARG;
     }
     if (xdt != ydt) return 0;
-    return variant_legal(variant, wp) ? 1 : 0;
+    return variant_legal(variant, wp, xdt) ? 1 : 0;
 }
 
 int nm_conv2d(const void* x, nm_dtype_t xdt, int b, int h, int w, int cin, const nm_packed_t* wp,
@@ -482,14 +508,14 @@ int nm_conv2d(const void* x, nm_dtype_t xdt, int b, int h, int w, int cin, const
             if (it != g_cache.end()) v = it->second.variant;
         }
     }
-    if (v >= 0 && !variant_legal(v, wp)) {
+    if (v >= 0 && !variant_legal(v, wp, xdt)) {
         if (g_forced >= 0) {
             set_error("variant %d (%s) cannot run this layer", v, nm_variant_name(v));
             return NM_ERR_UNSUPPORTED;
         }
         v = -1;   // stale cache entry: fall back to the default
     }
-    if (v < 0) v = heuristic_variant(wp, g.P);
+    if (v < 0) v = heuristic_variant(wp, g.P, xdt);
     if (v < 0) {
         set_error("no kernel variant can run this layer");
         return NM_ERR_UNSUPPORTED;
@@ -524,7 +550,7 @@ int nm_autotune(nm_dtype_t xdt, int b, int h, int w, int cin, const nm_packed_t*
     {
         std::lock_guard<std::mutex> lk(g_mu);
         auto it = g_cache.find(key);
-        if (it != g_cache.end() && variant_legal(it->second.variant, wp)) {
+        if (it != g_cache.end() && variant_legal(it->second.variant, wp, xdt)) {
             if (chosen) *chosen = it->second.variant;
             if (best_ms) *best_ms = it->second.ms;
             return NM_OK;
@@ -574,7 +600,7 @@ int nm_autotune(nm_dtype_t xdt, int b, int h, int w, int cin, const nm_packed_t*
     float best = 0.f;
     int turn = 0;
     for (int v = 0; v < variant_count(); ++v) {
-        if (!variant_legal(v, wp)) continue;
+        if (!variant_legal(v, wp, xdt)) continue;
         const VariantDesc& d = variant_desc(v);
         ConvParams p;
         auto launch_next = [&]() {

@@ -7,17 +7,23 @@ namespace {
 typedef int (*LaunchFn)(const ConvParams&, hipStream_t);
 struct Entry {
     VariantDesc d;
-    LaunchFn ff;   // fp32 in, fp32 out
+    LaunchFn ff;   // fp32 in, fp32 out (fp32 MFMA kernel only)
     LaunchFn bb;   // bf16 in, bf16 out
 };
 
 #define NM_ENTRY(NB, WP, NJ, CK, SPC, VEC)                                                     \
-    {{"NB" #NB "_WP" #WP "_NJ" #NJ "_CK" #CK "_SPC" #SPC "_V" #VEC, 16 * NB * WP, NB, WP, NJ, CK, SPC, VEC}, \
+    {{"NB" #NB "_WP" #WP "_NJ" #NJ "_CK" #CK "_SPC" #SPC "_V" #VEC, 16 * NB * WP, NB, WP, NJ, CK, SPC, VEC, 0, 1}, \
      &launch_t<NB, WP, NJ, CK, SPC, (VEC) != 0, float, float>,                                 \
      &launch_t<NB, WP, NJ, CK, SPC, (VEC) != 0, bf16_t, bf16_t>},
 #define NM_SHAPE_ENTRIES(NB, WP, NJ) NM_VEC_CHUNKS(NM_ENTRY, NB, WP, NJ)
 
-const Entry kEntries[] = {NM_SHAPES(NM_SHAPE_ENTRIES) NM_SCALAR_VARIANTS(NM_ENTRY)};
+#define NM_ENTRY16(NB, WP, NJ, SH, CK, SPC)                                                     \
+    {{"B16_NB" #NB "_WP" #WP "_NJ" #NJ "_SH" #SH "_CK" #CK "_SPC" #SPC, 16 * NB * WP, NB, WP, NJ, CK, SPC, 1, 1, SH}, \
+     nullptr, &launch16_t<NB, WP, NJ, CK, SPC, SH>},
+#define NM_SHAPE_ENTRIES16(NB, WP, NJ, SH) NM16_CHUNKS(NM_ENTRY16, NB, WP, NJ, SH)
+
+const Entry kEntries[] = {NM_SHAPES(NM_SHAPE_ENTRIES) NM_SCALAR_VARIANTS(NM_ENTRY)
+                          NM16_SHAPES(NM_SHAPE_ENTRIES16)};
 constexpr int kCount = (int)(sizeof(kEntries) / sizeof(kEntries[0]));
 }  // namespace
 
@@ -30,7 +36,7 @@ int launch_conv(int v, nm_dtype_t xdt, nm_dtype_t ydt, const ConvParams& p, hipS
         set_error("variant %d out of range", v);
         return NM_ERR_UNSUPPORTED;
     }
-    if (xdt == NM_F32 && ydt == NM_F32) return kEntries[v].ff(p, s);
+    if (xdt == NM_F32 && ydt == NM_F32 && kEntries[v].ff) return kEntries[v].ff(p, s);
     if (xdt == NM_BF16 && ydt == NM_BF16) return kEntries[v].bb(p, s);
     set_error("unsupported dtype pair: input and output must both be fp32 or both bf16");
     return NM_ERR_UNSUPPORTED;

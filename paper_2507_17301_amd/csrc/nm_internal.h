@@ -61,10 +61,17 @@ inline ChunkGeom make_chunk_geom(int cin, int K, int CK, int vec)
 // tile; the i-th kept column of the chunk is quarter i % 4 of step i / 4, and
 // unused slots carry weight 0 and row 0.
 struct Prepack {
+    int kind = 0;                     // 0: tables of the fp32 MFMA kernel, 1: of the bf16 MFMA kernel
     ChunkGeom geom{};
     int SPC = 0;                      // k-steps per chunk (1, 2, 4 or 8)
-    uint32_t* d_rows = nullptr;       // [n_tiles][nchunks][4][SPC]  LDS row (k - k0) that quarter q reads in step s
-    float* d_wfrag = nullptr;         // [n_rowblocks][nchunks][64][SPC]  MFMA A-operand lane values
+    // kind 0: a k-step is 4 kept columns
+    //   d_rows  [n_tiles][nchunks][4][SPC] u32        LDS row (k - k0) that quarter q reads in step s
+    //   d_wfrag [n_rowblocks][nchunks][64][SPC] fp32  MFMA A-operand lane values
+    // kind 1: a k-step is 32 kept columns
+    //   d_rows  [n_tiles][nchunks][SPC][4][8] u32     byte offset (k - k0) * 2 of the 8 columns of quarter q
+    //   d_wfrag [n_rowblocks][nchunks][SPC][64][8] bf16  MFMA A-operand lane values
+    uint32_t* d_rows = nullptr;
+    float* d_wfrag = nullptr;
     size_t rows_bytes = 0, wfrag_bytes = 0;
     uint32_t* d_ktab = nullptr;       // scalar mode only: [nchunks*CK] (kh | kw << 8 | ci << 16) per im2col row
 };
@@ -130,6 +137,8 @@ struct VariantDesc {
     int CK;    // K rows per LDS chunk
     int SPC;   // k-steps per chunk
     int vec;   // chunk mode: 1 = 16-byte channel loads, 0 = element-wise on flat k
+    int kind;  // 0 = fp32 MFMA kernel (fp32 or bf16 I/O), 1 = bf16 MFMA kernel (bf16 I/O, bf16 weights)
+    int share; // kind 1: row blocks fed from one gathered operand
 };
 
 int variant_count();
@@ -139,7 +148,7 @@ int launch_conv(int v, nm_dtype_t xdt, nm_dtype_t ydt, const ConvParams& p, hipS
 
 // prune-side kernels (nm_prune_kernels.hip)
 int run_prune(const float* d_w, nm_packed* wp, hipStream_t s);
-int run_build_prepack(nm_packed* wp, Prepack& pp, hipStream_t s);
+int run_build_prepack(nm_packed* wp, Prepack& pp, hipStream_t s);   // either kind
 int run_build_mask(const nm_packed* wp, uint8_t* d_mask, hipStream_t s);
 int run_fill_random(void* d, size_t n_elems, nm_dtype_t dt, uint32_t seed, hipStream_t s);
 

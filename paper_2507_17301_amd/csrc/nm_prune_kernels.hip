@@ -153,6 +153,58 @@ __global__ __launch_bounds__(256) void build_prepack_kernel(
     }
 }
 
+// The same for the bf16 MFMA kernel: a k-step is 32 kept columns, column i of a
+// chunk is element i % 8 of quarter (i % 32) / 8 of step i / 32.  Outputs
+// (zero-initialised by the caller):
+//   rows [j][c][s][q][8] u32     byte offset (k - k0) * 2 of the column inside the strip's pixel row
+//   wfrag[rb][c][s][lane][8]     bf16 weight for MFMA A-operand lane (q*16 + t), element e
+__global__ __launch_bounds__(256) void build_prepack16_kernel(
+    const int32_t* __restrict__ idx, const float* __restrict__ vals, int kprime, int T, int rbpt,
+    int cin, int CK, int ncpt, int nchunks, int SPC,
+    uint32_t* __restrict__ rows, unsigned short* __restrict__ wfrag, int* __restrict__ err)
+{
+    extern __shared__ int sm_int[];
+    int* cnt = sm_int;
+    int* first = sm_int + nchunks;
+    const int j = blockIdx.x;
+    const int32_t* idxj = idx + (size_t)j * kprime;
+    for (int c = threadIdx.x; c < nchunks; c += blockDim.x) cnt[c] = 0;
+    __syncthreads();
+    for (int kk = threadIdx.x; kk < kprime; kk += blockDim.x) {
+        int c, r;
+        chunk_of(idxj[kk], cin, CK, 1, ncpt, &c, &r);
+        atomicAdd(&cnt[c], 1);
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        int run = 0;
+        for (int c = 0; c < nchunks; ++c) {
+            first[c] = run;
+            run += cnt[c];
+            if (cnt[c] > 32 * SPC) err[0] = 1;
+        }
+    }
+    __syncthreads();
+    for (int kk = threadIdx.x; kk < kprime; kk += blockDim.x) {
+        int c, r;
+        chunk_of(idxj[kk], cin, CK, 1, ncpt, &c, &r);
+        const int i = kk - first[c];
+        const int step = i >> 5, q = (i & 31) >> 3, e = i & 7;
+        if (step >= SPC) continue;
+        rows[((((size_t)j * nchunks + c) * SPC + step) * 4 + q) * 8 + e] = (uint32_t)r * 2u;
+        for (int sub = 0; sub < rbpt; ++sub) {
+            const size_t rb = (size_t)j * rbpt + sub;
+            for (int t = 0; t < 16; ++t) {
+                const int tt = sub * 16 + t;
+                const float v = tt < T ? vals[((size_t)j * kprime + kk) * T + tt] : 0.f;
+                // the values are already bf16-representable (rounded at pack time): keep the top half
+                wfrag[((((rb * nchunks + c) * SPC + step) * 64) + q * 16 + t) * 8 + e] =
+                    (unsigned short)(__float_as_uint(v) >> 16);
+            }
+        }
+    }
+}
+
 __global__ void build_mask_kernel(const int32_t* __restrict__ idx, int cout, int K, int kprime,
                                   int T, int n_tiles, unsigned char* __restrict__ mask)
 {
@@ -227,9 +279,14 @@ int run_build_prepack(nm_packed* wp, Prepack& pp, hipStream_t s)
     NM_HIP_CHECK(hipMalloc(&d_err, sizeof(int)));
     NM_HIP_CHECK(hipMemsetAsync(d_err, 0, sizeof(int), s));
     const size_t lds = (size_t)2 * g.nchunks * sizeof(int);
-    hipLaunchKernelGGL(build_prepack_kernel, dim3(wp->n_tiles), dim3(256), lds, s, wp->d_idx,
-                       wp->d_vals, wp->kprime, wp->tile, wp->rbpt, wp->cin, g.CK, g.vec, g.ncpt,
-                       g.nchunks, pp.SPC, pp.d_rows, pp.d_wfrag, d_err);
+    if (pp.kind == 0)
+        hipLaunchKernelGGL(build_prepack_kernel, dim3(wp->n_tiles), dim3(256), lds, s, wp->d_idx,
+                           wp->d_vals, wp->kprime, wp->tile, wp->rbpt, wp->cin, g.CK, g.vec, g.ncpt,
+                           g.nchunks, pp.SPC, pp.d_rows, pp.d_wfrag, d_err);
+    else
+        hipLaunchKernelGGL(build_prepack16_kernel, dim3(wp->n_tiles), dim3(256), lds, s, wp->d_idx,
+                           wp->d_vals, wp->kprime, wp->tile, wp->rbpt, wp->cin, g.CK, g.ncpt, g.nchunks,
+                           pp.SPC, pp.d_rows, reinterpret_cast<unsigned short*>(pp.d_wfrag), d_err);
     hipError_t e = hipGetLastError();
     int h_err = 0;
     if (e == hipSuccess) e = hipMemcpyAsync(&h_err, d_err, sizeof(int), hipMemcpyDeviceToHost, s);

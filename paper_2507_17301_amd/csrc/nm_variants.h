@@ -23,3 +23,16 @@
     Y(NB, WP, NJ, 64, 2, 1) Y(NB, WP, NJ, 64, 4, 1) Y(NB, WP, NJ, 64, 8, 1)
 
 #define NM_SCALAR_VARIANTS(Y) Y(4, 4, 4, 32, 8, 0) Y(4, 2, 2, 32, 8, 0) Y(4, 1, 1, 32, 8, 0)
+
+// bf16 matrix-core kernel (bf16 activations, bf16-rounded weights):
+//   SHARE row blocks of one column tile are fed from the same gathered operand (2 for T = 32)
+//   a k-step is 32 kept columns; CK channels per chunk hold SPC k-steps
+// X(NBLK, WP, NJ, SHARE)
+#define NM16_SHAPES(X)                                                              \
+    X(8, 1, 2, 1) X(8, 1, 1, 1) X(4, 1, 2, 1) X(4, 1, 1, 1) X(4, 2, 2, 1) X(2, 1, 2, 1) \
+    X(2, 1, 1, 1) X(5, 1, 1, 1) X(6, 1, 1, 1) X(12, 1, 1, 1) X(16, 1, 1, 1)            \
+    X(8, 1, 2, 2) X(4, 1, 2, 2) X(4, 2, 2, 2) X(2, 1, 2, 2) X(4, 1, 4, 2)
+// Y(NBLK, WP, NJ, SHARE, CK, SPC)
+#define NM16_CHUNKS(Y, NB, WP, NJ, SH)                                              \
+    Y(NB, WP, NJ, SH, 32, 1) Y(NB, WP, NJ, SH, 64, 1) Y(NB, WP, NJ, SH, 128, 1)     \
+    Y(NB, WP, NJ, SH, 64, 2) Y(NB, WP, NJ, SH, 128, 2) Y(NB, WP, NJ, SH, 256, 1)

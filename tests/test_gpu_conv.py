@@ -109,6 +109,35 @@ def test_every_variant_other_sparsities(n, m, tile):
     assert ran >= 9
 
 
+@pytest.mark.parametrize("n,m,tile,cin", [(2, 4, 16, 64), (2, 8, 32, 128), (1, 4, 32, 64), (4, 8, 8, 64),
+                                            (1, 1, 16, 32), (2, 4, 16, 40)])
+def test_every_variant_bf16(n, m, tile, cin):
+    """bf16 tensors: every legal variant, i.e. the fp32-MFMA kernels on bf16 data and
+    the bf16 matrix-core kernels (T = 32 also with the shared operand), forced in turn."""
+    layer = L("variants_bf16", 11, 9, cin, 80, 3, 3, 1, 1, 1, n, m, tile)
+    x, w, bias = wl.make_tensors(layer, 3, 9, weight_sigma=0.1)
+    ref = oracle_conv(layer, x, w, bias, relu=True, bf16=True)
+    import torch
+    wp = nm.nm_prune(w, n, m, tile, nm.NM_BF16)
+    xd = torch.from_numpy(x).cuda().to(torch.bfloat16)
+    bd = torch.from_numpy(bias).cuda()
+    ran = ran16 = 0
+    try:
+        for v in range(nm.nm_variant_count()):
+            if not nm.nm_variant_legal(v, wp, nm.NM_BF16, nm.NM_BF16):
+                continue
+            say(f"forced bf16 variant {v} {nm.nm_variant_name(v)} {n}:{m} T={tile} cin={cin}")
+            nm.nm_force_variant(v)
+            y = nm.nm_conv2d(xd, wp, bd, 1, 1, 1, True)
+            torch.cuda.synchronize()
+            assert norm_err(y.float().cpu().numpy(), ref) <= BF16_TOL, nm.nm_variant_name(v)
+            ran += 1
+            ran16 += nm.nm_variant_name(v).startswith("B16")
+    finally:
+        nm.nm_force_variant(-1)
+    assert ran >= 9 and ran16 >= 5
+
+
 def test_illegal_forced_variant_is_an_error_not_a_fallback():
     layer = L("flat_only", 6, 6, 6, 16, 3, 3, 1, 1, 1, 1, 2, 16)
     x, w, bias = wl.make_tensors(layer, 1, 3)
