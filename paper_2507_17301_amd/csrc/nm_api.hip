@@ -141,6 +141,16 @@ int conv_geometry(int b, int h, int w, const nm_packed* wp, int sh, int sw, int 
     return NM_OK;
 }
 
+// x / d for x < 2^31 as umulhi(2 x, mul) >> shift: shift = ceil(log2 d) and
+// mul = floor(2^(31 + shift) / d) + 1, which fits 32 bits and is exact on that range.
+void magic_div(unsigned d, unsigned* mul, unsigned* shift)
+{
+    unsigned s = 0;
+    while ((1ull << s) < d) ++s;
+    *mul = (unsigned)(((1ull << (31 + s)) / d) + 1);
+    *shift = s;
+}
+
 void fill_params(ConvParams& p, const VariantDesc& d, const Prepack& pp, const nm_packed* wp,
                  const void* x, void* y, const float* bias, int b, int h, int w, const Geometry& g,
                  int sh, int sw, int ph, int pw, int dh, int dw, int relu, size_t es)
@@ -160,6 +170,8 @@ void fill_params(ConvParams& p, const VariantDesc& d, const Prepack& pp, const n
     p.n_cblocks = (wp->n_rowblocks + rb_per_wg - 1) / rb_per_wg;
     p.n_wg = p.n_ptiles * p.n_cblocks;
     p.wg_per_xcd = (p.n_wg + 7) / 8;
+    magic_div((unsigned)(g.Ho * g.Wo), &p.howo_mul, &p.howo_shift);
+    magic_div((unsigned)g.Wo, &p.wo_mul, &p.wo_shift);
     p.x_bytes = (unsigned)((size_t)b * h * w * wp->cin * es);
 }
 

@@ -74,19 +74,15 @@ __global__ __launch_bounds__(256) void nm_conv_bf16_kernel(const ConvParams p)
     for (int it = 0; it < NIT; ++it) {
         const int pl = pl0 + it * PSTEP;
         const int pp = p0 + pl;
-        if (pp < p.P && pl < BP) {
-            const int b = pp / HoWo;
-            const int rem = pp - b * HoWo;
-            const int ho = rem / p.Wo;
-            const int wo = rem - ho * p.Wo;
-            hi0[it] = ho * p.sh - p.ph;
-            wi0[it] = wo * p.sw - p.pw;
-            base[it] = (unsigned)(((b * p.H + hi0[it]) * p.W + wi0[it]) * p.Cin + oct * 8) * 2;
-        } else {
-            hi0[it] = -(1 << 28);
-            wi0[it] = 0;
-            base[it] = 0;
-        }
+        const bool live = (pp < p.P) & (pl < BP);
+        const int b = (int)fdiv((unsigned)pp, p.howo_mul, p.howo_shift);
+        const int rem = pp - b * HoWo;
+        const int ho = (int)fdiv((unsigned)rem, p.wo_mul, p.wo_shift);
+        const int wo = rem - ho * p.Wo;
+        const int h0 = ho * p.sh - p.ph, w0 = wo * p.sw - p.pw;
+        hi0[it] = live ? h0 : -(1 << 28);   // a dead pixel has every tap outside the image
+        wi0[it] = w0;
+        base[it] = (unsigned)(((b * p.H + h0) * p.W + w0) * p.Cin + oct * 8) * 2;
     }
     u4v st[NIT];
     int f_c = 0, f_kh = 0, f_kw = 0, f_ci0 = 0;

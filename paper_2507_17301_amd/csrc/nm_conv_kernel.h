@@ -108,6 +108,13 @@ __device__ inline void load_words(unsigned (&dst)[SPC], __amdgpu_buffer_rsrc_t r
     }
 }
 
+// x / d for a divisor d fixed at launch and x < 2^31: umulhi(2 x, mul) >> shift
+// with shift = ceil(log2 d) and mul = floor(2^(31 + shift) / d) + 1.
+__device__ inline unsigned fdiv(unsigned x, unsigned mul, unsigned shift)
+{
+    return __umulhi(x << 1, mul) >> shift;
+}
+
 template <int NBLK, int WP, int NJ, int CK, int SPC, bool VEC, typename TIN, typename TOUT>
 __global__ __launch_bounds__(256) void nm_conv_kernel(const ConvParams p)
 {
@@ -170,19 +177,15 @@ __global__ __launch_bounds__(256) void nm_conv_kernel(const ConvParams p)
     for (int it = 0; it < NIT; ++it) {
         const int pl = pl0 + it * PSTEP;
         const int pp = p0 + pl;
-        if (pp < p.P && pl < BP) {
-            const int b = pp / HoWo;
-            const int rem = pp - b * HoWo;
-            const int ho = rem / p.Wo;
-            const int wo = rem - ho * p.Wo;
-            hi0[it] = ho * p.sh - p.ph;
-            wi0[it] = wo * p.sw - p.pw;
-            base[it] = (unsigned)(((b * p.H + hi0[it]) * p.W + wi0[it]) * p.Cin + (VEC ? quad * 4 : 0)) * ES;
-        } else {
-            hi0[it] = -(1 << 28);   // every tap lands outside the image
-            wi0[it] = 0;
-            base[it] = 0;
-        }
+        const bool live = (pp < p.P) & (pl < BP);
+        const int b = (int)fdiv((unsigned)pp, p.howo_mul, p.howo_shift);
+        const int rem = pp - b * HoWo;
+        const int ho = (int)fdiv((unsigned)rem, p.wo_mul, p.wo_shift);
+        const int wo = rem - ho * p.Wo;
+        const int h0 = ho * p.sh - p.ph, w0 = wo * p.sw - p.pw;
+        hi0[it] = live ? h0 : -(1 << 28);   // a dead pixel has every tap outside the image
+        wi0[it] = w0;
+        base[it] = (unsigned)(((b * p.H + h0) * p.W + w0) * p.Cin + (VEC ? quad * 4 : 0)) * ES;
     }
 
     f4 st[VEC ? NIT : 1];

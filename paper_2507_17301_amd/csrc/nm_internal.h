@@ -124,6 +124,8 @@ struct ConvParams {
     int tile, rbpt, n_rowblocks;
     int n_ptiles, n_cblocks, n_wg;   // pixel tiles, row-block groups, product
     int wg_per_xcd;
+    // launch-time divisors as multiply-shift pairs (x / d = umulhi(x, mul) >> shift, mul == 0: d == 1)
+    unsigned howo_mul, howo_shift, wo_mul, wo_shift;
     unsigned x_bytes;  // size of x in bytes (< 2 GiB), the range of the buffer descriptor
     unsigned wfrag_bytes, rows_bytes;
 };
