@@ -50,6 +50,14 @@ def _shapes16():
             for m in re.findall(r"X\((\d+),\s*(\d+),\s*(\d+),\s*(\d+)\)", body)]
 
 
+def _shapes_sp():
+    """(NBLK, WP, NJ) of NMSP_SHAPES in nm_variants.h."""
+    text = open(os.path.join(CSRC, "nm_variants.h")).read()
+    body = text[text.index("#define NMSP_SHAPES(X)"):]
+    body = body[:body.index("// Y(")]
+    return [tuple(int(v) for v in m) for m in re.findall(r"X\((\d+),\s*(\d+),\s*(\d+)\)", body)]
+
+
 def _jobs():
     jobs = []
     for src in ("nm_api.hip", "nm_prune_kernels.hip", "nm_conv_registry.hip"):
@@ -64,6 +72,10 @@ def _jobs():
         jobs.append((inst16, os.path.join(OBJDIR, f"nm_conv16_inst_{nb}_{wp}_{nj}_{sh}.o"),
                      [f"-DNM_INST_NBLK={nb}", f"-DNM_INST_WP={wp}", f"-DNM_INST_NJ={nj}",
                       f"-DNM_INST_SHARE={sh}"]))
+    instsp = os.path.join(CSRC, "nm_conv_sp16_inst.hip")
+    for nb, wp, nj in _shapes_sp():
+        jobs.append((instsp, os.path.join(OBJDIR, f"nm_conv_sp16_inst_{nb}_{wp}_{nj}.o"),
+                     [f"-DNM_INST_NBLK={nb}", f"-DNM_INST_WP={wp}", f"-DNM_INST_NJ={nj}"]))
     return jobs
 
 

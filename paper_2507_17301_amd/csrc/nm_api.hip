@@ -53,10 +53,10 @@ ShapeKey make_key(nm_dtype_t xdt, nm_dtype_t ydt, int b, int h, int w, const nm_
 
 size_t lds_bytes(const VariantDesc& d)
 {
-    if (d.kind == 1) {
+    if (d.kind >= 1) {
         const int opr = d.CK / 8, pstep = 256 / opr, nit = (d.BP * opr + 255) / 256;
         const int rows = nit * pstep > d.BP ? nit * pstep : d.BP;
-        return (size_t)2 * rows * (d.CK * 2 + 4);
+        return (size_t)2 * rows * (d.CK * 2 + (d.kind == 1 ? 4 : 16));
     }
     return (size_t)2 * d.CK * strip_stride(d.BP, d.CK, d.vec != 0) * sizeof(float);
 }
@@ -75,7 +75,7 @@ bool variant_legal(int v, const nm_packed* wp, nm_dtype_t xdt)
     if (v < 0 || v >= variant_count()) return false;
     const VariantDesc& d = variant_desc(v);
     if (lds_bytes(d) > (size_t)kMaxLdsBytes) return false;
-    if (d.kind == 1) {
+    if (d.kind >= 1) {
         // bf16 matrix cores: bf16 tensors, weights already rounded to bf16, and a
         // shared operand only for column tiles made of exactly two row blocks
         if (xdt != NM_BF16 || wp->value_dtype != NM_BF16) return false;
@@ -195,7 +195,8 @@ int heuristic_variant(const nm_packed* wp, int P, nm_dtype_t xdt)
         const double mfma = (double)d.BP * rb_per_wg;            // per chunk step, relative
         const double stage = (double)d.BP * 2.0;                 // staging cost per chunk, relative
         // the bf16 matrix-core kernel contracts several times faster where it applies
-        const double cost = (double)rounds * occ * (mfma + stage) * (d.kind == 1 ? 0.3 : 1.0);
+        const double speed[4] = {1.0, 0.3, 0.1, 0.2};             // relative cost of a unit of contraction
+        const double cost = (double)rounds * occ * (mfma + stage) * speed[d.kind];
         if (best < 0 || cost < best_cost * 0.999) {
             best = v;
             best_cost = cost;
@@ -347,30 +348,41 @@ int nm_prune(const float* w, int cout, int kh, int kw, int cin, int n, int m, in
     const bool vec_ok = cin % 4 == 0;
     for (int v = 0; v < variant_count(); ++v) {
         const VariantDesc& d = variant_desc(v);
-        if (d.kind == 1) {
+        if (d.kind >= 2) {
+            // gather-free bf16 kernel: whole 64-channel k-steps of one tap per chunk; the
+            // sparse operand holds at most 2 kept columns per aligned group of 4
+            if (value_dtype != NM_BF16 || cin % d.CK != 0) continue;
+            if (d.kind == 2 && !(n <= 2 && m % 4 == 0)) continue;
+        } else if (d.kind == 1) {
             if (value_dtype != NM_BF16 || cin % 8 != 0) continue;
         } else if ((d.vec != 0) != vec_ok) {
             continue;
         }
         if (find_prepack(wp, d)) continue;
         const ChunkGeom g = make_chunk_geom(cin, wp->K, d.CK, d.vec);
-        const int per_step = d.kind == 1 ? 32 : 4;   // kept columns per k-step
-        const int need = (max_kept_per_chunk(wp, g) + per_step - 1) / per_step;
-        // smallest instantiated SPC >= need for this (kind, CK, mode)
-        int pick = 0;
-        for (int u = 0; u < variant_count(); ++u) {
-            const VariantDesc& e = variant_desc(u);
-            if (e.kind == d.kind && e.CK == d.CK && e.vec == d.vec && e.SPC >= need &&
-                (pick == 0 || e.SPC < pick))
-                pick = e.SPC;
+        if (d.kind < 2) {
+            const int per_step = d.kind == 1 ? 32 : 4;   // kept columns per k-step
+            const int need = (max_kept_per_chunk(wp, g) + per_step - 1) / per_step;
+            // smallest instantiated SPC >= need for this (kind, CK, mode)
+            int pick = 0;
+            for (int u = 0; u < variant_count(); ++u) {
+                const VariantDesc& e = variant_desc(u);
+                if (e.kind == d.kind && e.CK == d.CK && e.vec == d.vec && e.SPC >= need &&
+                    (pick == 0 || e.SPC < pick))
+                    pick = e.SPC;
+            }
+            if (pick == 0 || pick != d.SPC) continue;
         }
-        if (pick == 0 || pick != d.SPC) continue;
         Prepack pp;
         pp.kind = d.kind;
         pp.geom = g;
         pp.SPC = d.SPC;
         size_t rows_bytes, wf_bytes;
-        if (d.kind == 1) {
+        if (d.kind >= 2) {
+            rows_bytes = (size_t)wp->n_tiles * g.nchunks * 4 * pp.SPC * sizeof(uint32_t);
+            wf_bytes = (size_t)wp->n_rowblocks * g.nchunks * pp.SPC * (d.kind == 2 ? 1 : 2) * 64 * 8 *
+                       sizeof(uint16_t);
+        } else if (d.kind == 1) {
             rows_bytes = (size_t)wp->n_tiles * g.nchunks * pp.SPC * 4 * 8 * sizeof(uint32_t);
             wf_bytes = (size_t)wp->n_rowblocks * g.nchunks * pp.SPC * 64 * 8 * sizeof(uint16_t);
         } else {

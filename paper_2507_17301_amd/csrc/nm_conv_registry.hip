@@ -22,8 +22,14 @@ struct Entry {
      nullptr, &launch16_t<NB, WP, NJ, CK, SPC, SH>},
 #define NM_SHAPE_ENTRIES16(NB, WP, NJ, SH) NM16_CHUNKS(NM_ENTRY16, NB, WP, NJ, SH)
 
+// kind 2: sparse matrix instruction, kind 3: dense instruction on zero-filled weights
+#define NM_ENTRYSP(NB, WP, NJ, CK, SP)                                                          \
+    {{"SP" #SP "_NB" #NB "_WP" #WP "_NJ" #NJ "_CK" #CK, 16 * NB * WP, NB, WP, NJ, CK, CK / 64, 1, (SP) ? 2 : 3, 1}, \
+     nullptr, &launch_sp16_t<NB, WP, NJ, CK, (SP) != 0>},
+#define NM_SHAPE_ENTRIESSP(NB, WP, NJ) NMSP_CHUNKS(NM_ENTRYSP, NB, WP, NJ)
+
 const Entry kEntries[] = {NM_SHAPES(NM_SHAPE_ENTRIES) NM_SCALAR_VARIANTS(NM_ENTRY)
-                          NM16_SHAPES(NM_SHAPE_ENTRIES16)};
+                          NM16_SHAPES(NM_SHAPE_ENTRIES16) NMSP_SHAPES(NM_SHAPE_ENTRIESSP)};
 constexpr int kCount = (int)(sizeof(kEntries) / sizeof(kEntries[0]));
 }  // namespace
 

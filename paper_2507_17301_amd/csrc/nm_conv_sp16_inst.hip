@@ -1,0 +1,10 @@
+// Explicit instantiations of the gather-free bf16 kernel.  Compiled once per
+// shape (-DNM_INST_NBLK=.. -DNM_INST_WP=.. -DNM_INST_NJ=..).
+#include "nm_conv_sp16_kernel.h"
+#include "nm_variants.h"
+
+namespace nm {
+#define NM_INSTSP(NB, WP, NJ, CK, SP) \
+    template int launch_sp16_t<NB, WP, NJ, CK, (SP) != 0>(const ConvParams&, hipStream_t);
+NMSP_CHUNKS(NM_INSTSP, NM_INST_NBLK, NM_INST_WP, NM_INST_NJ)
+}  // namespace nm

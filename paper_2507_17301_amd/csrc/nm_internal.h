@@ -61,7 +61,7 @@ inline ChunkGeom make_chunk_geom(int cin, int K, int CK, int vec)
 // tile; the i-th kept column of the chunk is quarter i % 4 of step i / 4, and
 // unused slots carry weight 0 and row 0.
 struct Prepack {
-    int kind = 0;                     // 0: tables of the fp32 MFMA kernel, 1: of the bf16 MFMA kernel
+    int kind = 0;                     // 0: fp32 MFMA kernel, 1: bf16 MFMA gather kernel, 2/3: gather-free bf16 kernel
     ChunkGeom geom{};
     int SPC = 0;                      // k-steps per chunk (1, 2, 4 or 8)
     // kind 0: a k-step is 4 kept columns
@@ -70,6 +70,10 @@ struct Prepack {
     // kind 1: a k-step is 32 kept columns
     //   d_rows  [n_tiles][nchunks][SPC][4][8] u32     byte offset (k - k0) * 2 of the 8 columns of quarter q
     //   d_wfrag [n_rowblocks][nchunks][SPC][64][8] bf16  MFMA A-operand lane values
+    // kind 2 (sparse matrix instruction) and 3 (dense instruction, zero-filled weights):
+    //   a k-step is 64 consecutive channels of one tap; SPC = CK / 64
+    //   d_rows  [n_tiles][nchunks][4][SPC] u32        kind 2: index operand of lane group q in k-step s
+    //   d_wfrag [n_rowblocks][nchunks][SPC][AH][64][8] bf16   A-operand lane values, AH = 1 (kind 2) or 2 (kind 3)
     uint32_t* d_rows = nullptr;
     float* d_wfrag = nullptr;
     size_t rows_bytes = 0, wfrag_bytes = 0;
@@ -139,7 +143,8 @@ struct VariantDesc {
     int CK;    // K rows per LDS chunk
     int SPC;   // k-steps per chunk
     int vec;   // chunk mode: 1 = 16-byte channel loads, 0 = element-wise on flat k
-    int kind;  // 0 = fp32 MFMA kernel (fp32 or bf16 I/O), 1 = bf16 MFMA kernel (bf16 I/O, bf16 weights)
+    int kind;  // 0 = fp32 MFMA kernel (fp32 or bf16 I/O), 1 = bf16 MFMA gather kernel (bf16 I/O, bf16 weights),
+               // 2 = bf16 sparse-matrix-instruction kernel, 3 = bf16 dense kernel on zero-filled weights
     int share; // kind 1: row blocks fed from one gathered operand
 };
 

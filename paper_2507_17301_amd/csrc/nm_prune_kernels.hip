@@ -205,6 +205,88 @@ __global__ __launch_bounds__(256) void build_prepack16_kernel(
     }
 }
 
+// Operand tables of the gather-free bf16 kernel.  One thread per (row block,
+// chunk, k-step, half, lane) writes that lane's 8 A-operand values.
+//   sparse: element ea of lane i + 16 qa belongs to the aligned group of 4
+//     columns that starts at channel 16 (2 (qa % 2) + ea / 4) + 8 (qa / 2) +
+//     4 ((ea % 4) / 2) of the k-step; its two slots take the group's kept
+//     columns in ascending order, a group with fewer than two is padded with a
+//     zero weight at a free position (positions stay ascending); the 2-bit
+//     positions go to field ea of the lane group's index operand.
+//   dense: element e of lane i + 16 q, half h is channel 16 q + 8 h + e of the
+//     k-step, its weight or 0.
+__device__ inline int lower_bound_idx(const int32_t* a, int n, int key)
+{
+    int lo = 0, hi = n;
+    while (lo < hi) {
+        const int mid = (lo + hi) >> 1;
+        if (a[mid] < key) lo = mid + 1; else hi = mid;
+    }
+    return lo;
+}
+
+__global__ __launch_bounds__(256) void build_prepack_sp16_kernel(
+    const int32_t* __restrict__ idx, const float* __restrict__ vals, int kprime, int T, int rbpt,
+    int n_rowblocks, int cin, int CK, int ncpt, int nchunks, int sparse,
+    uint32_t* __restrict__ rows, unsigned short* __restrict__ wfrag, int* __restrict__ err)
+{
+    const int KS = CK / 64, AH = sparse ? 1 : 2;
+    const size_t total = (size_t)n_rowblocks * nchunks * KS * AH * 64;
+    for (size_t id = (size_t)blockIdx.x * blockDim.x + threadIdx.x; id < total;
+         id += (size_t)gridDim.x * blockDim.x) {
+        const int lane = (int)(id % 64);
+        size_t r = id / 64;
+        const int h = (int)(r % AH); r /= AH;
+        const int s = (int)(r % KS); r /= KS;
+        const int c = (int)(r % nchunks);
+        const int rb = (int)(r / nchunks);
+        const int i = lane & 15, qa = lane >> 4;
+        const int j = rb / rbpt, sub = rb - j * rbpt;
+        const int t = sub * 16 + i;                       // row inside the column tile
+        const int32_t* idxj = idx + (size_t)j * kprime;
+        const int tap = c / ncpt, ci0 = (c - tap * ncpt) * CK;
+        const int kstep0 = tap * cin + ci0 + s * 64;      // flat k of the k-step's first channel
+        unsigned short out[8];
+        if (sparse) {
+            unsigned fields = 0;
+            for (int pair = 0; pair < 4; ++pair) {        // elements 2 pair, 2 pair + 1 share a group
+                const int ea = 2 * pair;
+                const int k0 = kstep0 + 16 * (2 * (qa % 2) + ea / 4) + 8 * (qa / 2) + 4 * ((ea % 4) / 2);
+                const int lb = lower_bound_idx(idxj, kprime, k0);
+                int cnt = 0, pos[2] = {0, 0}, kk[2] = {-1, -1};
+                for (int u = lb; u < kprime && idxj[u] < k0 + 4; ++u) {
+                    if (cnt < 2) { pos[cnt] = idxj[u] - k0; kk[cnt] = u; }
+                    ++cnt;
+                }
+                if (cnt > 2) err[0] = 1;
+                if (cnt == 0) {
+                    pos[0] = 0; pos[1] = 1;
+                } else if (cnt == 1) {
+                    if (pos[0] == 3) { pos[1] = 3; kk[1] = kk[0]; pos[0] = 0; kk[0] = -1; }
+                    else pos[1] = 3;
+                }
+                for (int e = 0; e < 2; ++e) {
+                    float v = 0.f;
+                    if (kk[e] >= 0 && t < T) v = vals[((size_t)j * kprime + kk[e]) * T + t];
+                    out[ea + e] = (unsigned short)(__float_as_uint(v) >> 16);   // already bf16-representable
+                }
+                fields |= (unsigned)(pos[0] | (pos[1] << 2)) << (4 * pair);
+            }
+            if (i == 0 && sub == 0) rows[(((size_t)j * nchunks + c) * 4 + qa) * KS + s] = fields;
+        } else {
+            for (int e = 0; e < 8; ++e) {
+                const int k = kstep0 + 16 * qa + 8 * h + e;
+                const int lb = lower_bound_idx(idxj, kprime, k);
+                float v = 0.f;
+                if (lb < kprime && idxj[lb] == k && t < T) v = vals[((size_t)j * kprime + lb) * T + t];
+                out[e] = (unsigned short)(__float_as_uint(v) >> 16);
+            }
+        }
+        unsigned short* dst = wfrag + id * 8;
+        for (int e = 0; e < 8; ++e) dst[e] = out[e];
+    }
+}
+
 __global__ void build_mask_kernel(const int32_t* __restrict__ idx, int cout, int K, int kprime,
                                   int T, int n_tiles, unsigned char* __restrict__ mask)
 {
@@ -283,7 +365,13 @@ int run_build_prepack(nm_packed* wp, Prepack& pp, hipStream_t s)
         hipLaunchKernelGGL(build_prepack_kernel, dim3(wp->n_tiles), dim3(256), lds, s, wp->d_idx,
                            wp->d_vals, wp->kprime, wp->tile, wp->rbpt, wp->cin, g.CK, g.vec, g.ncpt,
                            g.nchunks, pp.SPC, pp.d_rows, pp.d_wfrag, d_err);
-    else
+    else if (pp.kind >= 2) {
+        const size_t total = (size_t)wp->n_rowblocks * g.nchunks * pp.SPC * (pp.kind == 2 ? 1 : 2) * 64;
+        hipLaunchKernelGGL(build_prepack_sp16_kernel, dim3(grid_for(total, 256)), dim3(256), 0, s,
+                           wp->d_idx, wp->d_vals, wp->kprime, wp->tile, wp->rbpt, wp->n_rowblocks, wp->cin,
+                           g.CK, g.ncpt, g.nchunks, pp.kind == 2 ? 1 : 0, pp.d_rows,
+                           reinterpret_cast<unsigned short*>(pp.d_wfrag), d_err);
+    } else
         hipLaunchKernelGGL(build_prepack16_kernel, dim3(wp->n_tiles), dim3(256), lds, s, wp->d_idx,
                            wp->d_vals, wp->kprime, wp->tile, wp->rbpt, wp->cin, g.CK, g.ncpt, g.nchunks,
                            pp.SPC, pp.d_rows, reinterpret_cast<unsigned short*>(pp.d_wfrag), d_err);

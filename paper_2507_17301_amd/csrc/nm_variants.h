@@ -36,3 +36,15 @@
 #define NM16_CHUNKS(Y, NB, WP, NJ, SH)                                              \
     Y(NB, WP, NJ, SH, 32, 1) Y(NB, WP, NJ, SH, 64, 1) Y(NB, WP, NJ, SH, 128, 1)     \
     Y(NB, WP, NJ, SH, 64, 2) Y(NB, WP, NJ, SH, 128, 2) Y(NB, WP, NJ, SH, 256, 1)
+
+// bf16 kernels that contract the dense strip without a gather: the sparse
+// matrix instruction (SP = 1: N <= 2 kept of every aligned 4 columns) or the
+// dense one on zero-filled weights (SP = 0).  A chunk is CK channels of one tap.
+// X(NBLK, WP, NJ)
+#define NMSP_SHAPES(X)                                                          \
+    X(4, 1, 2) X(4, 1, 4) X(2, 1, 2) X(2, 1, 4) X(4, 2, 2) X(4, 2, 4) X(8, 1, 2) \
+    X(8, 1, 1) X(4, 1, 1) X(2, 1, 1) X(2, 2, 2) X(6, 1, 2) X(3, 1, 2) X(2, 2, 4)
+// Y(NBLK, WP, NJ, CK, SP)
+#define NMSP_CHUNKS(Y, NB, WP, NJ)                                   \
+    Y(NB, WP, NJ, 64, 1) Y(NB, WP, NJ, 128, 1) Y(NB, WP, NJ, 256, 1) \
+    Y(NB, WP, NJ, 64, 0) Y(NB, WP, NJ, 128, 0) Y(NB, WP, NJ, 256, 0)

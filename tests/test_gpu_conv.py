@@ -110,10 +110,14 @@ def test_every_variant_other_sparsities(n, m, tile):
 
 
 @pytest.mark.parametrize("n,m,tile,cin", [(2, 4, 16, 64), (2, 8, 32, 128), (1, 4, 32, 64), (4, 8, 8, 64),
-                                            (1, 1, 16, 32), (2, 4, 16, 40)])
+                                            (1, 1, 16, 32), (2, 4, 16, 40), (2, 4, 16, 256), (1, 8, 16, 128),
+                                            (1, 1, 16, 64)])
 def test_every_variant_bf16(n, m, tile, cin):
-    """bf16 tensors: every legal variant, i.e. the fp32-MFMA kernels on bf16 data and
-    the bf16 matrix-core kernels (T = 32 also with the shared operand), forced in turn."""
+    """bf16 tensors: every legal variant, i.e. the fp32-MFMA kernels on bf16 data, the
+    bf16 matrix-core gather kernels (T = 32 also with the shared operand) and, where
+    the channel count is a multiple of 64, the gather-free kernels (sparse matrix
+    instruction for N <= 2 of M % 4 == 0, dense instruction on zero-filled weights
+    for everything), forced in turn."""
     layer = L("variants_bf16", 11, 9, cin, 80, 3, 3, 1, 1, 1, n, m, tile)
     x, w, bias = wl.make_tensors(layer, 3, 9, weight_sigma=0.1)
     ref = oracle_conv(layer, x, w, bias, relu=True, bf16=True)
@@ -121,7 +125,7 @@ def test_every_variant_bf16(n, m, tile, cin):
     wp = nm.nm_prune(w, n, m, tile, nm.NM_BF16)
     xd = torch.from_numpy(x).cuda().to(torch.bfloat16)
     bd = torch.from_numpy(bias).cuda()
-    ran = ran16 = 0
+    ran = ran16 = ran_sp = ran_dn = 0
     try:
         for v in range(nm.nm_variant_count()):
             if not nm.nm_variant_legal(v, wp, nm.NM_BF16, nm.NM_BF16):
@@ -133,9 +137,16 @@ def test_every_variant_bf16(n, m, tile, cin):
             assert norm_err(y.float().cpu().numpy(), ref) <= BF16_TOL, nm.nm_variant_name(v)
             ran += 1
             ran16 += nm.nm_variant_name(v).startswith("B16")
+            ran_sp += nm.nm_variant_name(v).startswith("SP1")
+            ran_dn += nm.nm_variant_name(v).startswith("SP0")
     finally:
         nm.nm_force_variant(-1)
     assert ran >= 9 and ran16 >= 5
+    if cin % 64 == 0:
+        assert ran_dn >= 14
+        assert (ran_sp >= 14) == (n <= 2 and m % 4 == 0)
+    else:
+        assert ran_sp == 0 and ran_dn == 0
 
 
 def test_illegal_forced_variant_is_an_error_not_a_fallback():
