@@ -53,10 +53,13 @@ ShapeKey make_key(nm_dtype_t xdt, nm_dtype_t ydt, int b, int h, int w, const nm_
 
 size_t lds_bytes(const VariantDesc& d)
 {
-    if (d.kind >= 1) {
+    if (d.kind >= 2)   // three stages of the strip [BP][CK] bf16 plus each wave's operands
+        return (size_t)3 * (d.BP * d.CK * 2 +
+                            4 * d.NJ * (d.CK / 64) * (d.kind == 2 ? 1024 + 256 : 2048));
+    if (d.kind == 1) {
         const int opr = d.CK / 8, pstep = 256 / opr, nit = (d.BP * opr + 255) / 256;
         const int rows = nit * pstep > d.BP ? nit * pstep : d.BP;
-        return (size_t)2 * rows * (d.CK * 2 + (d.kind == 1 ? 4 : 16));
+        return (size_t)2 * rows * (d.CK * 2 + 4);
     }
     return (size_t)2 * d.CK * strip_stride(d.BP, d.CK, d.vec != 0) * sizeof(float);
 }

@@ -37,28 +37,45 @@ namespace nm {
 typedef __bf16 bf8x __attribute__((ext_vector_type(8)));
 typedef __bf16 bf16x __attribute__((ext_vector_type(16)));
 
-// LDS row stride (bytes): CK channels plus 16, so that rows stay 16-byte
-// aligned and the 16 pixels that a lane group reads with one 16-byte access
-// start in 16 different bank quads.
-constexpr int strip_sp16_stride(int CK) { return CK * 2 + 16; }
-constexpr int strip_sp16_rows(int BP, int CK)
+// The strip goes from global memory straight into LDS (buffer loads with the
+// LDS modifier, 16 bytes per lane): lane L of a wave-wide load writes the 16-byte
+// granule L of a 1 KB window, so a stage is the plain [pixel][CK channels] array
+// and the lane decides which (pixel, octet) it fetches.  To keep the 16-byte
+// operand reads of 16 pixels conflict-free without padding, octet g of pixel
+// row r is stored at granule position g ^ swz(r) of the row.
+// Out-of-image taps are fetched with an out-of-range offset, which writes zeros.
+// The weights and index words of a chunk travel the same way into a per-wave
+// part of the stage.  Three stages form a ring: while chunk c is contracted,
+// the loads of chunks c + 1 and c + 2 are in flight; no global load returns
+// into registers inside the loop.
+constexpr int kSp16Stages = 3;
+// one stage: the strip [BP][CK] bf16, then per wave the weights (and index words) of its row blocks
+constexpr int sp16_stage_bytes(int BP, int CK, int NJ, bool sparse)
 {
-    const int opr = CK / 8, pstep = 256 / opr, nit = (BP * opr + 255) / 256;
-    return nit * pstep > BP ? nit * pstep : BP;
+    return BP * CK * 2 + 4 * NJ * (CK / 64) * ((sparse ? 1 : 2) * 1024 + (sparse ? 256 : 0));
 }
+__device__ inline int sp16_swz(int row, int CK) { return CK == 64 ? ((row >> 1) & 7) : (row & 15); }
+
+// s_waitcnt with only the vector-memory counter set (gfx9 encoding: vmcnt in
+// bits 3:0 and 15:14, the other counters at their maxima).
+#define NM_WAIT_VMCNT(n) __builtin_amdgcn_s_waitcnt(((n) & 15) | (((n) >> 4) << 14) | 0x0f70)
+
+typedef __attribute__((address_space(3))) void* lds_ptr_t;
 
 template <int NBLK, int WP, int NJ, int CK, bool SPARSE>
 __global__ __launch_bounds__(256) void nm_conv_sp16_kernel(const ConvParams p)
 {
     constexpr int BPW = 16 * NBLK;
     constexpr int BP = BPW * WP;
-    constexpr int S = strip_sp16_stride(CK);
     constexpr int WC = 4 / WP;
     constexpr int KS = CK / 64;                  // k-steps (64 channels) per chunk
     constexpr int AH = SPARSE ? 1 : 2;           // 16-byte A operands per k-step and row block
+    constexpr int RB = CK * 2;                   // bytes per pixel row of a stage
+    const int D = p.nchunks < kSp16Stages ? p.nchunks : kSp16Stages;   // stages in use (and allocated)
+    constexpr int STAGE = sp16_stage_bytes(BP, CK, NJ, SPARSE);
     static_assert(CK % 64 == 0, "a chunk is a whole number of 64-channel k-steps");
 
-    extern __shared__ char lds8[];               // [2][ROWS][S]
+    extern __shared__ __attribute__((aligned(16))) char lds8[];   // [D][BP][RB]
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -80,19 +97,19 @@ __global__ __launch_bounds__(256) void nm_conv_sp16_kernel(const ConvParams p)
     const __amdgpu_buffer_rsrc_t wr = make_rsrc(p.wfrag, p.wfrag_bytes);
     const __amdgpu_buffer_rsrc_t rr = make_rsrc(p.rows, p.rows_bytes);
 
-    // ---- staging: item = (pixel, 8-channel octet), 16 bytes ----------------
-    constexpr int OPR = CK / 8;
-    constexpr int PSTEP = 256 / OPR;
-    constexpr int NIT = (BP * OPR + 255) / 256;
-    constexpr int ROWS = strip_sp16_rows(BP, CK);
-    const int oct = tid % OPR;
-    const int pl0 = tid / OPR;
+    // ---- staging: wave-wide loads of 64 granules; load i of the stage covers
+    // granules 64 i .. 64 i + 63 and is issued by wave i % 4 -------------------
+    constexpr int OPR = CK / 8;                  // granules (octets) per pixel row
+    constexpr int NW = BP * OPR / 64;            // wave-wide loads per stage
+    constexpr int NIT = (NW + 3) / 4;            // per wave
     int hi0[NIT], wi0[NIT];
     unsigned base[NIT], voff[NIT];
     const int HoWo = p.Ho * p.Wo;
 #pragma unroll
     for (int it = 0; it < NIT; ++it) {
-        const int pl = pl0 + it * PSTEP;
+        const int G = (wave + 4 * it) * 64 + lane;            // granule of the stage this lane fills
+        const int pl = G / OPR;
+        const int oct = (G % OPR) ^ sp16_swz(pl, CK);         // the octet that belongs at that position
         const int pp = p0 + pl;
         const bool live = (pp < p.P) & (pl < BP);
         const int b = (int)fdiv((unsigned)pp, p.howo_mul, p.howo_shift);
@@ -104,8 +121,8 @@ __global__ __launch_bounds__(256) void nm_conv_sp16_kernel(const ConvParams p)
         wi0[it] = w0;
         base[it] = (unsigned)(((b * p.H + h0) * p.W + w0) * p.Cin + oct * 8) * 2;
     }
-    u4v st[NIT];
     int f_c = 0, f_kh = 0, f_kw = 0, f_ci0 = 0;
+    bool f_live = true;                          // false once the iterator has run past the last chunk
     auto retap = [&]() {
         const int dhh = f_kh * p.dh, dww = f_kw * p.dw;
         const unsigned tapoff = (unsigned)((dhh * p.W + dww) * p.Cin) * 2;
@@ -116,38 +133,43 @@ __global__ __launch_bounds__(256) void nm_conv_sp16_kernel(const ConvParams p)
             voff[it] = inb ? base[it] + tapoff : kOOB;
         }
     };
-    auto fetch_item = [&](int it) {
-        st[it] = __builtin_amdgcn_raw_buffer_load_b128(xr, voff[it] + (unsigned)(f_ci0 * 2), 0, 0);
+    // one wave-wide load of the current fetch chunk into stage `stage`
+    auto fetch_item = [&](int it, int stage) {
+        if (NW % 4 != 0 && wave + 4 * it >= NW) return;       // wave-uniform
+        const unsigned off = f_live ? voff[it] + (unsigned)(f_ci0 * 2) : kOOB;
+        char* dst = lds8 + stage * STAGE + (wave + 4 * it) * 1024;
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(xr, (lds_ptr_t)dst, 16, off, 0, 0, 0);
     };
     auto fetch_advance = [&]() {
-        const int adv = f_c + 1 < p.nchunks ? 1 : 0;
-        f_c += adv;
+        const bool adv = f_c + 1 < p.nchunks;
+        f_live = f_live & adv;
+        f_c += adv ? 1 : 0;
         const int nci = f_ci0 + CK;
-        const int wrap = (adv && nci >= p.Cin) ? 1 : 0;
+        const bool wrap = adv & (nci >= p.Cin);
         f_ci0 = wrap ? 0 : (adv ? nci : f_ci0);
         if (wrap) {
             const int nkw = f_kw + 1;
-            const int wrap2 = nkw == p.Kw ? 1 : 0;
+            const bool wrap2 = nkw == p.Kw;
             f_kw = wrap2 ? 0 : nkw;
-            f_kh += wrap2;
+            f_kh += wrap2 ? 1 : 0;
             retap();
         }
-    };
-    auto stash_item = [&](int it, char* dst) {
-        *reinterpret_cast<u4v*>(dst + (pl0 + it * PSTEP) * S + oct * 16) = st[it];
     };
 
     // ---- operand streams ------------------------------------------------------
     // weights: [row block][chunk][k-step][AH][lane] x 16 bytes (8 bf16)
     // index operands (sparse): [column tile][chunk][lane group][k-step] x 4 bytes
-    struct Ops {
-        u4v a[KS][AH];
-        unsigned idx[KS];
-    };
+    // Both take the same road as the strip: each wave loads the operands of its
+    // own row blocks into a private part of the stage (lane L's 16 bytes, or 4
+    // for the index word, land at position L) and reads them back when the
+    // chunk's turn comes.
     constexpr unsigned WCH = KS * AH * 1024;     // weight bytes per (row block, chunk)
     constexpr unsigned ICH = KS * 16;            // index bytes per (tile, chunk)
+    constexpr int AW = NJ * KS * (AH * 1024 + (SPARSE ? 256 : 0));   // operand bytes per wave and stage
+    constexpr int NOPS = NJ * KS * (AH + (SPARSE ? 1 : 0));          // operand loads per wave and stage
+    constexpr int NL = NIT + NOPS;                                   // loads per wave and stage
+    static_assert(NL <= 63, "a stage's loads must fit the memory counter");
     const unsigned wvoff = (unsigned)lane * 16;
-    const unsigned ivoff = (unsigned)q * KS * 4;
     unsigned wsoff[NJ], isoff[NJ];
 #pragma unroll
     for (int jj = 0; jj < NJ; ++jj) {
@@ -156,26 +178,27 @@ __global__ __launch_bounds__(256) void nm_conv_sp16_kernel(const ConvParams p)
         wsoff[jj] = (unsigned)rb * p.nchunks * WCH;
         isoff[jj] = (unsigned)(rb / p.rbpt) * p.nchunks * ICH;
     }
-    auto load_ops = [&](Ops& o, int jj, int c) {
+    int o_c = 0;                                 // chunk whose operands the next fetch_ops brings in
+    auto fetch_ops = [&](int stage) {
+        char* dst = lds8 + stage * STAGE + BP * RB + wave * AW;
+        const int c = o_c < p.nchunks ? o_c : p.nchunks - 1;   // past the end: any valid chunk, never used
 #pragma unroll
-        for (int s = 0; s < KS; ++s)
+        for (int jj = 0; jj < NJ; ++jj)
 #pragma unroll
-            for (int h = 0; h < AH; ++h)
-                o.a[s][h] = __builtin_amdgcn_raw_buffer_load_b128(
-                    wr, wvoff, wsoff[jj] + (unsigned)c * WCH + (unsigned)(s * AH + h) * 1024, 0);
-        if constexpr (SPARSE) {
-            const unsigned so = isoff[jj] + (unsigned)c * ICH;
-            if constexpr (KS == 1) {
-                o.idx[0] = __builtin_amdgcn_raw_buffer_load_b32(rr, ivoff, so, 0);
-            } else if constexpr (KS == 2) {
-                const u2v t = __builtin_amdgcn_raw_buffer_load_b64(rr, ivoff, so, 0);
-                o.idx[0] = t.x; o.idx[1] = t.y;
-            } else {
-                static_assert(KS == 4, "index operands are fetched 1, 2 or 4 at a time");
-                const u4v t = __builtin_amdgcn_raw_buffer_load_b128(rr, ivoff, so, 0);
-                o.idx[0] = t.x; o.idx[1] = t.y; o.idx[2] = t.z; o.idx[3] = t.w;
+            for (int s = 0; s < KS; ++s) {
+#pragma unroll
+                for (int h = 0; h < AH; ++h) {
+                    const unsigned vo = wvoff + wsoff[jj] + (unsigned)c * WCH + (unsigned)(s * AH + h) * 1024;
+                    char* d = dst + ((jj * KS + s) * AH + h) * 1024;
+                    __builtin_amdgcn_raw_ptr_buffer_load_lds(wr, (lds_ptr_t)d, 16, vo, 0, 0, 0);
+                }
+                if constexpr (SPARSE) {
+                    const unsigned vo = (unsigned)(q * KS + s) * 4 + isoff[jj] + (unsigned)c * ICH;
+                    char* d = dst + NJ * KS * AH * 1024 + (jj * KS + s) * 256;
+                    __builtin_amdgcn_raw_ptr_buffer_load_lds(rr, (lds_ptr_t)d, 4, vo, 0, 0, 0);
+                }
             }
-        }
+        ++o_c;
     };
 
     f4 acc[NJ][NBLK];
@@ -184,55 +207,122 @@ __global__ __launch_bounds__(256) void nm_conv_sp16_kernel(const ConvParams p)
 #pragma unroll
         for (int b = 0; b < NBLK; ++b) acc[jj][b] = f4{0.f, 0.f, 0.f, 0.f};
 
-    Ops opsA[NJ], opsB[NJ];
+    // this lane's operand granules inside block 0 of a stage: k-step s, half h
+    unsigned roff[KS][2];
 #pragma unroll
-    for (int jj = 0; jj < NJ; ++jj) load_ops(opsA[jj], jj, 0);
+    for (int s = 0; s < KS; ++s)
+#pragma unroll
+        for (int h = 0; h < 2; ++h)
+            roff[s][h] = (unsigned)((wpix + n) * RB + (((s * 8 + q * 2 + h) ^ sp16_swz(n, CK)) * 16));
+
+    // The memory counter retires loads in order, so "at most one stage's loads
+    // outstanding" means that the stage before it has landed.
+    //   prologue:    stage(0) stage(1)
+    //   iteration c: wait, barrier | issue stage(c + 2) | contract chunk c
+    auto fetch_stage = [&](int stage) {
+#pragma unroll
+        for (int it = 0; it < NIT; ++it) fetch_item(it, stage);
+        fetch_advance();
+        fetch_ops(stage);
+    };
     retap();
+    fetch_stage(0);
+    if (p.nchunks > 1) fetch_stage(1);
+
+    // bias of this lane's rows, fetched now so that its latency hides behind the loop
+    const bool fast = (p.tile % 4 == 0) && (p.Cout % 4 == 0);
+    f4 bb[NJ];
 #pragma unroll
-    for (int it = 0; it < NIT; ++it) fetch_item(it);
-    fetch_advance();
-#pragma unroll
-    for (int it = 0; it < NIT; ++it) stash_item(it, lds8);
-#pragma unroll
-    for (int it = 0; it < NIT; ++it) fetch_item(it);
-    fetch_advance();
-    __syncthreads();
+    for (int jj = 0; jj < NJ; ++jj) {
+        bb[jj] = f4{0.f, 0.f, 0.f, 0.f};
+        const int rb = rb0 + jj;
+        const int j = rb / p.rbpt;
+        const int rit = (rb - j * p.rbpt) * 16 + q * 4;
+        const int co = j * p.tile + rit;
+        if (fast && p.bias && rb < p.n_rowblocks && rit < p.tile && co < p.Cout)
+            bb[jj] = *reinterpret_cast<const f4*>(p.bias + co);
+    }
 
     constexpr int NM = KS * NBLK;                // B operands (LDS reads) per chunk for this wavefront
-    constexpr int NTASK = 2 * NIT + NJ + 1;
-    // this lane's 32 bytes inside block 0, k-step 0
-    const unsigned lanepix = (unsigned)((wpix + n) * S + q * 32);
+    static_assert((NBLK - 1) * 16 * RB < 65536, "block offsets must fit the LDS instruction's immediate");
+    static_assert(AW < 65536, "operand offsets must fit the LDS instruction's immediate");
+    const unsigned lds0 = (unsigned)(uintptr_t)(__attribute__((address_space(3))) char*)lds8;
+    const unsigned aoff = (unsigned)(BP * RB + wave * AW) + wvoff;            // this lane's weights in a stage
+    const unsigned ioff = (unsigned)(BP * RB + wave * AW + NJ * KS * AH * 1024) + (unsigned)lane * 4;
+    // a wave whose last strip load does not exist has one load less per stage
+    const bool short_wave = (NW % 4 != 0) && (wave + 4 * (NIT - 1) >= NW);
+    int rstage = 0, wstage = D - 1;              // stage read by this chunk / filled for chunk c + 2
 
-    // One chunk: the strip of the next chunk goes from registers to the other
-    // LDS buffer, the fetch two chunks ahead and the operands of the next chunk
-    // are issued, all dealt out behind the matrix instructions of this chunk.
-    auto chunk = [&](int c, const int parity, Ops (&cur)[NJ], Ops (&nxt)[NJ]) {
-        const int cn = c + 1 < p.nchunks ? c + 1 : c;
-        char* const wbuf = lds8 + (parity ^ 1) * (ROWS * S);
-        const char* const rbase = lds8 + parity * (ROWS * S) + lanepix;
-        auto task = [&](int i) {
-            if (i < NJ) {
-                load_ops(nxt[i], i, cn);
-            } else if (i < NJ + NIT) {
-                stash_item(i - NJ, wbuf);
-            } else if (i < NJ + 2 * NIT) {
-                fetch_item(i - NJ - NIT);
-            } else {
-                fetch_advance();
-            }
-        };
+    // All LDS reads are inline assembly with hand-placed waits: the compiler,
+    // which cannot tell the stages of the ring apart, would otherwise make
+    // every LDS read wait for the loads just issued into the other stages.
+    auto chunk = [&](int c) {
+        // all of this wave's loads for chunk c have landed once at most the next
+        // stage's loads (if there is a next chunk) are outstanding
+        if (c + 1 < p.nchunks) {
+            if (short_wave) NM_WAIT_VMCNT(NL - 1); else NM_WAIT_VMCNT(NL);
+        } else {
+            NM_WAIT_VMCNT(0);
+        }
+        // A bare barrier: the fences of __syncthreads() would wait for every load
+        // into LDS that is in flight, i.e. for the stages being filled ahead.  What
+        // must be ordered is ordered by hand: this wave's loads for chunk c have
+        // landed (the wait above), and its LDS reads of chunk c - 1 have returned
+        // (each was waited for before the matrix instruction that used it).
+        __builtin_amdgcn_s_barrier();
+        if (c + 2 < p.nchunks) fetch_stage(wstage);
+
+        const unsigned sbase = lds0 + (unsigned)(rstage * STAGE);
+        u4v a[NJ][KS][AH];
+        unsigned idx[NJ][KS];
+        {
+            const unsigned aa = sbase + aoff, ia = sbase + ioff;
+#pragma unroll
+            for (int jj = 0; jj < NJ; ++jj)
+#pragma unroll
+                for (int s = 0; s < KS; ++s) {
+#pragma unroll
+                    for (int h = 0; h < AH; ++h)
+                        asm volatile("ds_read_b128 %0, %1 offset:%2"
+                                     : "=v"(a[jj][s][h]) : "v"(aa), "n"(((jj * KS + s) * AH + h) * 1024) : "memory");
+                    if constexpr (SPARSE)
+                        asm volatile("ds_read_b32 %0, %1 offset:%2"
+                                     : "=v"(idx[jj][s]) : "v"(ia), "n"((jj * KS + s) * 256) : "memory");
+                }
+        }
+        unsigned raddr[KS][2];
+#pragma unroll
+        for (int s = 0; s < KS; ++s)
+#pragma unroll
+            for (int h = 0; h < 2; ++h) raddr[s][h] = sbase + roff[s][h];
         auto read_b = [&](int m, u4v (&dst)[2]) {
             const int s = m / NBLK, b = m % NBLK;
-            const char* a = rbase + b * 16 * S + s * 128;
-            dst[0] = *reinterpret_cast<const u4v*>(a);
-            dst[1] = *reinterpret_cast<const u4v*>(a + 16);
+            asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(dst[0]) : "v"(raddr[s][0]), "n"(b * 16 * RB) : "memory");
+            asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(dst[1]) : "v"(raddr[s][1]), "n"(b * 16 * RB) : "memory");
         };
         u4v ring[2][2];
         read_b(0, ring[0]);
 #pragma unroll
         for (int m = 0; m < NM; ++m) {
             const int s = m / NBLK, b = m % NBLK;
-            if (m + 1 < NM) read_b(m + 1, ring[(m + 1) & 1]);
+            if (m + 1 < NM) {
+                read_b(m + 1, ring[(m + 1) & 1]);
+                asm volatile("s_waitcnt lgkmcnt(2)" : "+v"(ring[m & 1][0]), "+v"(ring[m & 1][1]));
+            } else {
+                asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(ring[m & 1][0]), "+v"(ring[m & 1][1]));
+            }
+            if (m == 0) {
+                // the operands were requested before the first strip read, so the wait
+                // above covers them too; tell the compiler that they are defined here
+#pragma unroll
+                for (int jj = 0; jj < NJ; ++jj)
+#pragma unroll
+                    for (int s2 = 0; s2 < KS; ++s2) {
+#pragma unroll
+                        for (int h = 0; h < AH; ++h) asm volatile("" : "+v"(a[jj][s2][h]));
+                        if constexpr (SPARSE) asm volatile("" : "+v"(idx[jj][s2]));
+                    }
+            }
             const u4v(&bo)[2] = ring[m & 1];
 #pragma unroll
             for (int jj = 0; jj < NJ; ++jj) {
@@ -241,32 +331,25 @@ __global__ __launch_bounds__(256) void nm_conv_sp16_kernel(const ConvParams p)
                                                              __builtin_bit_cast(bf8x, bo[1]), 0, 1, 2, 3, 4,
                                                              5, 6, 7, 8, 9, 10, 11, 12, 13, 14, 15);
                     acc[jj][b] = __builtin_amdgcn_smfmac_f32_16x16x64_bf16(
-                        __builtin_bit_cast(bf8x, cur[jj].a[s][0]), bv, acc[jj][b], (int)cur[jj].idx[s], 0, 0);
+                        __builtin_bit_cast(bf8x, a[jj][s][0]), bv, acc[jj][b], (int)idx[jj][s], 0, 0);
                 } else {
 #pragma unroll
                     for (int h = 0; h < 2; ++h)
                         acc[jj][b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
-                            __builtin_bit_cast(bf8x, cur[jj].a[s][h]), __builtin_bit_cast(bf8x, bo[h]),
+                            __builtin_bit_cast(bf8x, a[jj][s][h]), __builtin_bit_cast(bf8x, bo[h]),
                             acc[jj][b], 0, 0, 0);
                 }
             }
-#pragma unroll
-            for (int i = m * NTASK / NM; i < (m + 1) * NTASK / NM; ++i) task(i);
             __builtin_amdgcn_sched_barrier(0);
         }
-        __syncthreads();
+        rstage = rstage + 1 == D ? 0 : rstage + 1;
+        wstage = wstage + 1 == D ? 0 : wstage + 1;
     };
 
-    int c = 0;
-    for (; c + 1 < p.nchunks; c += 2) {
-        chunk(c, 0, opsA, opsB);
-        chunk(c + 1, 1, opsB, opsA);
-    }
-    if (c < p.nchunks) chunk(c, 0, opsA, opsB);
+    for (int c = 0; c < p.nchunks; ++c) chunk(c);
 
     // ---- epilogue: bias, ReLU, round to bf16, NHWC store ------------------------
     bf16_t* __restrict__ y = reinterpret_cast<bf16_t*>(p.y);
-    const bool fast = (p.tile % 4 == 0) && (p.Cout % 4 == 0);
 #pragma unroll
     for (int jj = 0; jj < NJ; ++jj) {
         const int rb = rb0 + jj;
@@ -277,13 +360,11 @@ __global__ __launch_bounds__(256) void nm_conv_sp16_kernel(const ConvParams p)
         const int co = j * p.tile + rit;
         if (fast) {
             if (rit >= p.tile || co >= p.Cout) continue;
-            f4 bb = {0.f, 0.f, 0.f, 0.f};
-            if (p.bias) bb = *reinterpret_cast<const f4*>(p.bias + co);
 #pragma unroll
             for (int b = 0; b < NBLK; ++b) {
                 const int pp = p0 + wpix + b * 16 + n;
                 if (pp >= p.P) continue;
-                f4 v = acc[jj][b] + bb;
+                f4 v = acc[jj][b] + bb[jj];
                 if (p.relu) {
                     v.x = fmaxf(v.x, 0.f); v.y = fmaxf(v.y, 0.f);
                     v.z = fmaxf(v.z, 0.f); v.w = fmaxf(v.w, 0.f);
@@ -311,15 +392,18 @@ template <int NBLK, int WP, int NJ, int CK, bool SPARSE>
 int launch_sp16_t(const ConvParams& p, hipStream_t s)
 {
     auto kern = nm_conv_sp16_kernel<NBLK, WP, NJ, CK, SPARSE>;
-    constexpr size_t lds = (size_t)2 * strip_sp16_rows(16 * NBLK * WP, CK) * strip_sp16_stride(CK);
-    if (lds > 64 * 1024) {
+    constexpr size_t stage = sp16_stage_bytes(16 * NBLK * WP, CK, NJ, SPARSE);
+    if (kSp16Stages * stage > 64 * 1024) {
         static hipError_t once = hipFuncSetAttribute(
-            reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+            reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
+            (int)(kSp16Stages * stage));
         if (once != hipSuccess) {
-            set_error("hipFuncSetAttribute(LDS %zu) failed: %s", lds, hipGetErrorString(once));
+            set_error("hipFuncSetAttribute(LDS %zu) failed: %s", kSp16Stages * stage, hipGetErrorString(once));
             return NM_ERR_HIP;
         }
     }
+    // short K loops use (and allocate) fewer stages, which leaves room for more workgroups per CU
+    const size_t lds = stage * (size_t)(p.nchunks < kSp16Stages ? p.nchunks : kSp16Stages);
     hipLaunchKernelGGL(kern, dim3(p.wg_per_xcd * 8), dim3(256), lds, s, p);
     NM_HIP_CHECK(hipGetLastError());
     return NM_OK;
