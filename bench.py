@@ -37,7 +37,12 @@ def main():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--dtype", choices=["f32", "bf16"], default="f32")
-    ap.add_argument("--batch", type=int, default=64)
+    ap.add_argument("--batch", type=int, default=None, help="default: the workload's own batch")
+    ap.add_argument("--workload", default="resnet50",
+                    choices=["resnet50", "resnet18", "resnet101", "sweep", "single"],
+                    help="resnet50 (default, the headline: 53 layers 2:4 T16 batch 64) | resnet18 (batch 32) | "
+                         "resnet101 (mixed sparsity, T32, batch 256, bf16) | sweep (15 N:M x T cells of one "
+                         "3x3 layer + its dense form, batch 32) | single (one 3x3 layer, batch 1)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-tune", action="store_true", help="use the untuned default variant")
     ap.add_argument("--no-graph", action="store_true",
@@ -63,8 +68,21 @@ def main():
     dev = torch.device("cuda:0")
     nm.lib()
 
-    B = args.batch
-    layers = wl.resnet50_stack(2, 4, 16)
+    if args.workload == "resnet50":
+        layers, B, wname, seed0 = wl.resnet50_stack(2, 4, 16), 64, "resnet50_conv_stack_53layers_2of4_T16", 4000
+    elif args.workload == "resnet18":
+        layers, B, wname, seed0 = wl.resnet18_stack(2, 4, 16), 32, "resnet18_conv_stack_20layers_2of4_T16", 3000
+    elif args.workload == "resnet101":
+        layers, B, wname, seed0 = wl.resnet101_stack(32), 256, "resnet101_conv_stack_104layers_mixed_T32", 5000
+        if "--dtype" not in sys.argv:
+            args.dtype = "bf16"
+    elif args.workload == "sweep":
+        cells = wl.sweep_config2()
+        layers, B, wname, seed0 = cells + [wl.dense_form(cells[1], "cfg2_dense_T16")], 32, "sweep_3x3_256ch_14x14_15cells_plus_dense", 0
+    else:
+        layers, B, wname, seed0 = [wl.single_conv_config1()], 1, "single_3x3_64ch_56x56_2of4_T16", 0
+    if args.batch is not None:
+        B = args.batch
     bf16 = args.dtype == "bf16"
     tdt = torch.bfloat16 if bf16 else torch.float32
     ndt = nm.NM_BF16 if bf16 else nm.NM_F32
@@ -79,7 +97,7 @@ def main():
     packed, xs, ys, biases, variants = [], [], [], [], []
     prune_s = 0.0
     for i, l in enumerate(layers):
-        _, w, bias = wl.make_tensors(l, B, 4000 + i, with_input=False)
+        _, w, bias = wl.make_tensors(l, B, seed0 + i, with_input=False)
         tp = time.time()
         wp = nm.nm_prune(w, l.n, l.m, l.tile, ndt)
         prune_s += time.time() - tp
@@ -185,34 +203,48 @@ def main():
     log(f"sum of kernel times {kern_ms:.3f} ms, step {ms_step:.3f} ms (host {ms_step_host:.3f} ms), "
         f"sum of per-layer lower bounds {tmin_ms:.3f} ms -> {tmin_ms / kern_ms * 100:.1f}% of binding roofline")
 
-    roofline = {
-        # the convolution kernel, all 53 launches of a step taken together:
-        # flops actually contracted (2*P*K'*Cout per launch) over their summed duration
-        "bound": "mfma", "achieved": eff / kern_ms / 1e9, "peak": PEAK_TFLOPS[args.dtype],
-        "unit": "TFLOP/s", "frac": eff / kern_ms / 1e9 / PEAK_TFLOPS[args.dtype],
+    # The convolution kernel, all launches of a step taken together.  fp32 is bound by the
+    # fp32 matrix cores (2*P*K'*Cout flops per launch over the summed durations); with bf16
+    # tensors nearly every layer sits below the ridge, so the bound is HBM (algorithmic bytes
+    # per launch over the summed durations).
+    if bf16:
+        roofline = {"bound": "hbm", "achieved": byts / kern_ms / 1e6, "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                    "frac": byts / kern_ms / 1e6 / PEAK_HBM_GBS}
+    else:
+        roofline = {"bound": "mfma", "achieved": eff / kern_ms / 1e9, "peak": PEAK_TFLOPS["f32"],
+                    "unit": "TFLOP/s", "frac": eff / kern_ms / 1e9 / PEAK_TFLOPS["f32"]}
+    roofline.update({
         # HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled by what the same
-        # counters read for the 1 GiB device copy above (profiles/nm_conv_kernel_resnet50_b64_f32.txt);
-        # measured for the default workload only
-        "traffic": 111.7e6 if (args.dtype == "f32" and B == 64) else None,
-        "kernel": "nm_conv_kernel", "launches_per_step": len(layers),
+        # counters read for the 1 GiB device copy above (profiles/); measured for the default workload only
+        "traffic": 111.7e6 if (args.workload == "resnet50" and args.dtype == "f32" and B == 64) else None,
+        "kernel": "nm_conv_sp16_kernel" if bf16 else "nm_conv_kernel", "launches_per_step": len(layers),
         "avg_launch_ms": kern_ms / len(layers),
         "frac_of_binding_roofline_per_layer": tmin_ms / kern_ms,
+        "effective_tflops": eff / kern_ms / 1e9,
         "algorithmic_gbytes_per_step": byts / 1e9, "achieved_gbs": byts / kern_ms / 1e6,
-    }
+    })
+
+    if args.workload == "sweep":
+        # sparse-over-dense speedup per cell: the dense form of the same layer through the same kernel family
+        t_dense = per_layer[-1]["ms"]
+        for r in per_layer[:-1]:
+            r["speedup_over_dense"] = t_dense / r["ms"]
+            log(f"{r['layer']:>18s}  {r['ms'] * 1e3:7.1f} us   x{r['speedup_over_dense']:.2f} over dense ({t_dense * 1e3:.1f} us)")
 
     cpu = None
     if not args.no_cpu_baseline:
-        cpu = cpu_baseline(layers, B, bf16)
+        cpu = cpu_baseline(layers, B, bf16, seed0)
 
     out = {
-        "metric": "dense-equiv GFLOP/s, ResNet-50 conv stack 2:4 @batch 64",
+        "metric": ("dense-equiv GFLOP/s, ResNet-50 conv stack 2:4 @batch 64" if args.workload == "resnet50" and B == 64
+                   else f"dense-equiv GFLOP/s, {wname} @batch {B}"),
         "value": dense / ms_step / 1e6, "unit": "GFLOP/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms_step, "ms_per_img": ms_step / B,
         "effective_gflops": eff / ms_step / 1e6,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": args.dtype, "data": "synthetic",
-        "config": {"workload": f"resnet50_conv_stack_53layers_2of4_T16_batch{B}_{args.dtype}",
+        "config": {"workload": f"{wname}_batch{B}_{args.dtype}",
                    "batch": B, "layers": len(layers), "tuned": not args.no_tune,
                    "launch": "hip_graph_replay" if graph is not None else "one_launch_per_layer"},
         "setup": {"prune_pack_s": prune_s, "autotune_s": tune_s},
@@ -224,7 +256,7 @@ def main():
     print(json.dumps(out), flush=True)
 
 
-def cpu_baseline(layers, B, bf16):
+def cpu_baseline(layers, B, bf16, seed0):
     """The CPU oracle, as it stands, on the first images of the same workload."""
     import numpy as np
     import oracle
@@ -233,7 +265,7 @@ def cpu_baseline(layers, B, bf16):
     cores = min(16, os.cpu_count() or 1)
     prepared = []
     for i, l in enumerate(layers):
-        _, w, bias = wl.make_tensors(l, 1, 4000 + i, with_input=False)
+        _, w, bias = wl.make_tensors(l, 1, seed0 + i, with_input=False)
         _, _, wz = oracle.prune(w, l.n, l.m, l.tile)
         if bf16:
             wz = oracle.round_bf16(wz)

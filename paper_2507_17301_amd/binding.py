@@ -15,6 +15,7 @@ import numpy as np
 
 NM_F32, NM_BF16 = 0, 1
 NM_OK = 0
+NM_ERR_ARG, NM_ERR_SHAPE, NM_ERR_UNSUPPORTED, NM_ERR_ALLOC, NM_ERR_HIP, NM_ERR_IO = -1, -2, -3, -4, -5, -6
 _STATUS = {0: "NM_OK", -1: "NM_ERR_ARG", -2: "NM_ERR_SHAPE", -3: "NM_ERR_UNSUPPORTED",
            -4: "NM_ERR_ALLOC", -5: "NM_ERR_HIP", -6: "NM_ERR_IO"}
 

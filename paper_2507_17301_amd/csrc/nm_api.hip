@@ -53,6 +53,8 @@ ShapeKey make_key(nm_dtype_t xdt, nm_dtype_t ydt, int b, int h, int w, const nm_
 
 size_t lds_bytes(const VariantDesc& d)
 {
+    if (d.kind == 4)   // the strip [BP][64 SPC] bf16 plus the dense weights of the workgroup's row blocks
+        return (size_t)d.BP * d.SPC * 128 + (size_t)(4 / d.WP) * d.NJ * d.SPC * 2048;
     if (d.kind >= 2)   // three stages of the strip [BP][CK] bf16 plus each wave's operands
         return (size_t)3 * (d.BP * d.CK * 2 +
                             4 * d.NJ * (d.CK / 64) * (d.kind == 2 ? 1024 + 256 : 2048));
@@ -64,16 +66,30 @@ size_t lds_bytes(const VariantDesc& d)
     return (size_t)2 * d.CK * strip_stride(d.BP, d.CK, d.vec != 0) * sizeof(float);
 }
 
-const Prepack* find_prepack(const nm_packed* wp, const VariantDesc& d)
+// The part of the convolution arguments that decides whether the kernel-row-run
+// kernel applies and which of its two operand tables it needs.
+struct RunArgs {
+    int w, sw, pw, dw;
+};
+
+// k-steps the kernel-row-run kernel needs for this layer when runs start `par` elements early
+int run_ksteps(const nm_packed* wp, int par)
+{
+    const int gr = (par + wp->kw * wp->cin + 7) / 8;
+    return (wp->kh * gr + 7) / 8;
+}
+
+const Prepack* find_prepack(const nm_packed* wp, const VariantDesc& d, int par = -1)
 {
     for (const Prepack& pp : wp->prepacks)
         if (pp.kind == d.kind && pp.geom.CK == d.CK && pp.geom.vec == d.vec && pp.SPC == d.SPC &&
-            (d.vec || pp.d_ktab))
+            (d.vec || pp.d_ktab) && (d.kind != 4 || par < 0 || pp.par == par))
             return &pp;
     return nullptr;
 }
 
-bool variant_legal(int v, const nm_packed* wp, nm_dtype_t xdt)
+// With `ra` the answer is for that convolution; without, "for some convolution".
+bool variant_legal(int v, const nm_packed* wp, nm_dtype_t xdt, const RunArgs* ra = nullptr)
 {
     if (v < 0 || v >= variant_count()) return false;
     const VariantDesc& d = variant_desc(v);
@@ -83,6 +99,11 @@ bool variant_legal(int v, const nm_packed* wp, nm_dtype_t xdt)
         // shared operand only for column tiles made of exactly two row blocks
         if (xdt != NM_BF16 || wp->value_dtype != NM_BF16) return false;
         if (d.share != 1 && d.share != wp->rbpt) return false;
+    }
+    if (d.kind == 4 && ra) {
+        // a kernel row must be one contiguous, 4-byte aligned run of every pixel
+        if (ra->dw != 1 || (ra->sw * wp->cin) % 2 != 0 || (ra->w * wp->cin) % 2 != 0) return false;
+        return find_prepack(wp, d, (ra->pw * wp->cin) % 2) != nullptr;
     }
     return find_prepack(wp, d) != nullptr;
 }
@@ -175,18 +196,21 @@ void fill_params(ConvParams& p, const VariantDesc& d, const Prepack& pp, const n
     p.wg_per_xcd = (p.n_wg + 7) / 8;
     magic_div((unsigned)(g.Ho * g.Wo), &p.howo_mul, &p.howo_shift);
     magic_div((unsigned)g.Wo, &p.wo_mul, &p.wo_shift);
+    p.x_elems = (unsigned)((size_t)b * h * w * wp->cin);
     p.x_bytes = (unsigned)((size_t)b * h * w * wp->cin * es);
+    p.run_d = pp.par;
+    p.run_gr = (pp.par + wp->kw * wp->cin + 7) / 8;
 }
 
 // Deterministic default when the shape has not been tuned: a small model of
 // "rounds of workgroups x work per workgroup", preferring tiles that fill the
 // 256 CUs and reuse the staged strip across many row blocks.
-int heuristic_variant(const nm_packed* wp, int P, nm_dtype_t xdt)
+int heuristic_variant(const nm_packed* wp, int P, nm_dtype_t xdt, const RunArgs* ra)
 {
     int best = -1;
     double best_cost = 0;
     for (int v = 0; v < variant_count(); ++v) {
-        if (!variant_legal(v, wp, xdt)) continue;
+        if (!variant_legal(v, wp, xdt, ra)) continue;
         const VariantDesc& d = variant_desc(v);
         const int rb_per_wg = (4 / d.WP) * d.NJ;
         const long n_pt = (P + d.BP - 1) / d.BP;
@@ -198,7 +222,7 @@ int heuristic_variant(const nm_packed* wp, int P, nm_dtype_t xdt)
         const double mfma = (double)d.BP * rb_per_wg;            // per chunk step, relative
         const double stage = (double)d.BP * 2.0;                 // staging cost per chunk, relative
         // the bf16 matrix-core kernel contracts several times faster where it applies
-        const double speed[4] = {1.0, 0.3, 0.1, 0.2};             // relative cost of a unit of contraction
+        const double speed[5] = {1.0, 0.3, 0.1, 0.2, 0.1};        // relative cost of a unit of contraction
         const double cost = (double)rounds * occ * (mfma + stage) * speed[d.kind];
         if (best < 0 || cost < best_cost * 0.999) {
             best = v;
@@ -351,6 +375,26 @@ int nm_prune(const float* w, int cout, int kh, int kw, int cin, int n, int m, in
     const bool vec_ok = cin % 4 == 0;
     for (int v = 0; v < variant_count(); ++v) {
         const VariantDesc& d = variant_desc(v);
+        if (d.kind == 4) {
+            // kernel-row runs: only where channel runs are too short for the other bf16 kernels
+            if (value_dtype != NM_BF16 || cin % 8 == 0) continue;
+            for (int par = 0; par < 2; ++par) {
+                if (run_ksteps(wp, par) != d.SPC || find_prepack(wp, d, par)) continue;
+                Prepack pp;
+                pp.kind = 4;
+                pp.geom.vec = 1; pp.geom.CK = d.CK; pp.geom.ncpt = 1; pp.geom.nchunks = 1;
+                pp.SPC = d.SPC;
+                pp.par = par;
+                pp.rows_bytes = 0;
+                pp.wfrag_bytes = (size_t)wp->n_rowblocks * pp.SPC * 2 * 64 * 8 * sizeof(uint16_t);
+                wp->prepacks.push_back(pp);
+                Prepack& ref = wp->prepacks.back();
+                NM_TRY_HIP(hipMalloc(reinterpret_cast<void**>(&ref.d_wfrag), ref.wfrag_bytes), NM_ERR_ALLOC);
+                rc = run_build_prepack(wp, ref, s);
+                if (rc != NM_OK) return fail(rc);
+            }
+            continue;
+        }
         if (d.kind >= 2) {
             // gather-free bf16 kernel: whole 64-channel k-steps of one tap per chunk; the
             // sparse operand holds at most 2 kept columns per aligned group of 4
@@ -535,21 +579,22 @@ int nm_conv2d(const void* x, nm_dtype_t xdt, int b, int h, int w, int cin, const
             if (it != g_cache.end()) v = it->second.variant;
         }
     }
-    if (v >= 0 && !variant_legal(v, wp, xdt)) {
+    const RunArgs ra = {w, sw, pw, dw};
+    if (v >= 0 && !variant_legal(v, wp, xdt, &ra)) {
         if (g_forced >= 0) {
             set_error("variant %d (%s) cannot run this layer", v, nm_variant_name(v));
             return NM_ERR_UNSUPPORTED;
         }
         v = -1;   // stale cache entry: fall back to the default
     }
-    if (v < 0) v = heuristic_variant(wp, g.P, xdt);
+    if (v < 0) v = heuristic_variant(wp, g.P, xdt, &ra);
     if (v < 0) {
         set_error("no kernel variant can run this layer");
         return NM_ERR_UNSUPPORTED;
     }
     const VariantDesc& d = variant_desc(v);
     ConvParams p;
-    fill_params(p, d, *find_prepack(wp, d), wp, x, y, bias, b, h, w, g, sh, sw, ph, pw, dh, dw, relu,
+    fill_params(p, d, *find_prepack(wp, d, (pw * wp->cin) % 2), wp, x, y, bias, b, h, w, g, sh, sw, ph, pw, dh, dw, relu,
                 xdt == NM_F32 ? 4 : 2);
     return launch_conv(v, xdt, ydt, p, (hipStream_t)stream);
 }
@@ -574,10 +619,11 @@ int nm_autotune(nm_dtype_t xdt, int b, int h, int w, int cin, const nm_packed_t*
     int rc = conv_geometry(b, h, w, wp, sh, sw, ph, pw, dh, dw, xdt == NM_F32 ? 4 : 2, &g);
     if (rc != NM_OK) return rc;
     const ShapeKey key = make_key(xdt, ydt, b, h, w, wp, sh, sw, ph, pw, dh, dw);
+    const RunArgs ra = {w, sw, pw, dw};
     {
         std::lock_guard<std::mutex> lk(g_mu);
         auto it = g_cache.find(key);
-        if (it != g_cache.end() && variant_legal(it->second.variant, wp, xdt)) {
+        if (it != g_cache.end() && variant_legal(it->second.variant, wp, xdt, &ra)) {
             if (chosen) *chosen = it->second.variant;
             if (best_ms) *best_ms = it->second.ms;
             return NM_OK;
@@ -627,12 +673,12 @@ int nm_autotune(nm_dtype_t xdt, int b, int h, int w, int cin, const nm_packed_t*
     float best = 0.f;
     int turn = 0;
     for (int v = 0; v < variant_count(); ++v) {
-        if (!variant_legal(v, wp, xdt)) continue;
+        if (!variant_legal(v, wp, xdt, &ra)) continue;
         const VariantDesc& d = variant_desc(v);
         ConvParams p;
         auto launch_next = [&]() {
             char* set = dpool + (xbytes + ybytes) * (turn++ % nbuf);
-            fill_params(p, d, *find_prepack(wp, d), wp, set, set + xbytes, dbias, b, h, w, g, sh, sw, ph, pw,
+            fill_params(p, d, *find_prepack(wp, d, (pw * wp->cin) % 2), wp, set, set + xbytes, dbias, b, h, w, g, sh, sw, ph, pw,
                         dh, dw, relu, es);
             return launch_conv(v, xdt, ydt, p, s);
         };

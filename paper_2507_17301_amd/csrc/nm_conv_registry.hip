@@ -28,8 +28,15 @@ struct Entry {
      nullptr, &launch_sp16_t<NB, WP, NJ, CK, (SP) != 0>},
 #define NM_SHAPE_ENTRIESSP(NB, WP, NJ) NMSP_CHUNKS(NM_ENTRYSP, NB, WP, NJ)
 
+// kind 4: contiguous kernel-row runs
+#define NM_ENTRYRUN(NB, WP, NJ, KS)                                                             \
+    {{"RUN_NB" #NB "_WP" #WP "_NJ" #NJ "_KS" #KS, 16 * NB * WP, NB, WP, NJ, 64 * KS, KS, 1, 4, 1}, \
+     nullptr, &launch_run16_t<NB, WP, NJ, KS>},
+#define NM_SHAPE_ENTRIESRUN(NB, WP, NJ) NMRUN_CHUNKS(NM_ENTRYRUN, NB, WP, NJ)
+
 const Entry kEntries[] = {NM_SHAPES(NM_SHAPE_ENTRIES) NM_SCALAR_VARIANTS(NM_ENTRY)
-                          NM16_SHAPES(NM_SHAPE_ENTRIES16) NMSP_SHAPES(NM_SHAPE_ENTRIESSP)};
+                          NM16_SHAPES(NM_SHAPE_ENTRIES16) NMSP_SHAPES(NM_SHAPE_ENTRIESSP)
+                          NMRUN_SHAPES(NM_SHAPE_ENTRIESRUN)};
 constexpr int kCount = (int)(sizeof(kEntries) / sizeof(kEntries[0]));
 }  // namespace
 

@@ -1,0 +1,241 @@
+// bf16 convolution for layers with very few input channels (the 7x7 first
+// layer of the ResNets: Cin = 3, paper section 4.1.2 keeps it dense).
+//
+// With Cin this small the im2col row of a pixel is not made of channel runs
+// worth fetching, but for a fixed kernel row kh the Kw * Cin values
+// x[b][hi][wi0 .. wi0 + Kw - 1][0 .. Cin - 1] are one contiguous run in NHWC.
+// The strip therefore holds, per pixel, Kh runs of GR 16-byte granules (the run
+// starts d = 0 or 1 elements early so that it is 4-byte aligned, and is padded
+// to whole granules), padded to KS 64-element k-steps; the weights are laid
+// out to match, zero in every padding slot.  K grows from Kh*Kw*Cin to
+// KS*64 (147 -> 192 for the 7x7x3 layer), which the bf16 matrix cores absorb
+// easily; in exchange the whole strip arrives through 16-byte loads straight
+// into LDS and the contraction is the dense one of the gather-free kernel.
+//
+// A run may hang over the left or right image border (there the neighbouring
+// image row would be read) or over the ends of the tensor.  Those granules --
+// a few per image row -- are instead assembled element by element with guarded
+// loads by the thread that owns them and written over the granule before the
+// workgroup starts contracting.
+//
+// One chunk only: the whole (padded) K of a pixel tile is resident at once.
+#pragma once
+
+#include "nm_conv_sp16_kernel.h"
+
+namespace nm {
+
+// granule position swizzle for rows of 8 * KS granules (see the gather-free kernel)
+__device__ inline int run16_swz(int row, int KS) { return (KS & 1) ? ((row & 7) ^ ((row >> 3) & 1)) : (row & 15); }
+
+// strip [BP][KS*64] bf16, then the dense weights of the workgroup's row blocks: one copy per
+// group of waves that work on the same row blocks (WC = 4 / WP groups)
+constexpr int run16_lds_bytes(int BP, int WP, int NJ, int KS) { return BP * KS * 128 + (4 / WP) * NJ * KS * 2048; }
+
+template <int NBLK, int WP, int NJ, int KS>
+__global__ __launch_bounds__(256) void nm_conv_run16_kernel(const ConvParams p)
+{
+    constexpr int BPW = 16 * NBLK;
+    constexpr int BP = BPW * WP;
+    constexpr int WC = 4 / WP;
+    constexpr int GPR = 8 * KS;                  // granules per pixel row of the strip
+    constexpr int RB = GPR * 16;                 // bytes per pixel row
+    constexpr int AW = NJ * KS * 2048;           // weight bytes per group of waves sharing row blocks
+
+    extern __shared__ __attribute__((aligned(16))) char lds8[];   // [BP][RB] strip, then [WC][AW] weights
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int q = lane >> 4;
+    const int n = lane & 15;
+
+    const int bid = blockIdx.x;
+    const int logical = (bid & 7) * p.wg_per_xcd + (bid >> 3);
+    if (logical >= p.n_wg) return;
+    const int cblock = logical % p.n_cblocks;
+    const int ptile = logical / p.n_cblocks;
+    const int p0 = ptile * BP;
+    const int wpx = wave % WP, wcx = wave / WP;
+    const int rb0 = (cblock * WC + wcx) * NJ;
+    const int wpix = wpx * BPW;
+
+    const __amdgpu_buffer_rsrc_t xr = make_rsrc(p.x, p.x_bytes);
+    const __amdgpu_buffer_rsrc_t wr = make_rsrc(p.wfrag, p.wfrag_bytes);
+
+    // ---- weights of this wave's row blocks: [row block][k-step][half][lane] x 16 bytes.
+    // The WP waves that share the row blocks split the loads between them.
+#pragma unroll
+    for (int li = 0; li < NJ * KS * 2; ++li) {
+        if (WP > 1 && li % WP != wpx) continue;              // wave-uniform
+        const int jj = li / (KS * 2), sh = li % (KS * 2);
+        int rb = rb0 + jj;
+        if (rb >= p.n_rowblocks) rb = p.n_rowblocks - 1;
+        const unsigned vo = (unsigned)lane * 16 + ((unsigned)rb * KS * 2 + sh) * 1024;
+        char* d = lds8 + BP * RB + wcx * AW + li * 1024;
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(wr, (lds_ptr_t)d, 16, vo, 0, 0, 0);
+    }
+
+    // ---- strip: wave-wide loads of 64 granules; load i is issued by wave i % 4
+    constexpr int NW = BP * GPR / 64;
+    constexpr int NIT = (NW + 3) / 4;
+    const int HoWo = p.Ho * p.Wo;
+    const int GR = p.run_gr, dsh = p.run_d;
+    const int KwC = p.Kw * p.Cin;
+    u4v fix[NIT];
+    bool need[NIT];
+#pragma unroll
+    for (int it = 0; it < NIT; ++it) {
+        need[it] = false;
+        fix[it] = u4v{0u, 0u, 0u, 0u};
+        if (NW % 4 != 0 && wave + 4 * it >= NW) continue;     // wave-uniform
+        const int G = (wave + 4 * it) * 64 + lane;            // granule slot of the strip this lane fills
+        const int pl = G / GPR;
+        const int g = (G % GPR) ^ run16_swz(pl, KS);          // the granule that belongs at that slot
+        const int kh = g / GR, gi = g - kh * GR;
+        const int pp = p0 + pl;
+        const int b = (int)fdiv((unsigned)pp, p.howo_mul, p.howo_shift);
+        const int rem = pp - b * HoWo;
+        const int ho = (int)fdiv((unsigned)rem, p.wo_mul, p.wo_shift);
+        const int wo = rem - ho * p.Wo;
+        const int hi = ho * p.sh - p.ph + kh * p.dh;
+        const int wi0 = wo * p.sw - p.pw;
+        const bool rowok = (pp < p.P) & (kh < p.Kh) & ((unsigned)hi < (unsigned)p.H);
+        // first element of the granule in the tensor, and which of its 8 elements are real taps
+        const int e0 = gi * 8 - dsh;                          // position in the run of element 0
+        const long long start = ((long long)(b * p.H + hi) * p.W + wi0) * p.Cin + e0;
+        // columns the real taps of this granule touch: elements max(e0,0) .. min(e0+7, KwC-1)
+        const int lo = e0 > 0 ? e0 : 0, hi_e = e0 + 7 < KwC - 1 ? e0 + 7 : KwC - 1;
+        const bool any = lo <= hi_e;
+        const int wlo = wi0 + lo / p.Cin, whi = wi0 + hi_e / p.Cin;
+        const bool inside = (wlo >= 0) & (whi < p.W) & (start >= 0) & (start + 8 <= (long long)p.x_elems);
+        const bool dma = rowok & any & inside;
+        need[it] = rowok & any & !inside;
+        const unsigned off = dma ? (unsigned)start * 2u : kOOB;
+        char* dst = lds8 + (wave + 4 * it) * 1024;
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(xr, (lds_ptr_t)dst, 16, off, 0, 0, 0);
+        if (need[it]) {
+            // border granule: element by element, zero where the column is outside the image
+            unsigned short v[8];
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const int er = e0 + e;
+                const int wi = wi0 + (er >= 0 ? er / p.Cin : -1);
+                const bool ok = (er >= 0) & (er < KwC) & ((unsigned)wi < (unsigned)p.W);
+                v[e] = __builtin_amdgcn_raw_buffer_load_b16(xr, ok ? (unsigned)(start + e) * 2u : kOOB, 0, 0);
+            }
+            fix[it] = u4v{(unsigned)v[0] | ((unsigned)v[1] << 16), (unsigned)v[2] | ((unsigned)v[3] << 16),
+                          (unsigned)v[4] | ((unsigned)v[5] << 16), (unsigned)v[6] | ((unsigned)v[7] << 16)};
+        }
+    }
+
+    // bias of this lane's rows
+    const bool fast = (p.tile % 4 == 0) && (p.Cout % 4 == 0);
+    f4 bb[NJ];
+#pragma unroll
+    for (int jj = 0; jj < NJ; ++jj) {
+        bb[jj] = f4{0.f, 0.f, 0.f, 0.f};
+        const int rb = rb0 + jj;
+        const int j = rb / p.rbpt;
+        const int rit = (rb - j * p.rbpt) * 16 + q * 4;
+        const int co = j * p.tile + rit;
+        if (fast && p.bias && rb < p.n_rowblocks && rit < p.tile && co < p.Cout)
+            bb[jj] = *reinterpret_cast<const f4*>(p.bias + co);
+    }
+
+    // all loads of this thread have landed; then the border granules go over the zeros
+    NM_WAIT_VMCNT(0);
+#pragma unroll
+    for (int it = 0; it < NIT; ++it)
+        if (need[it]) *reinterpret_cast<u4v*>(lds8 + (wave + 4 * it) * 1024 + lane * 16) = fix[it];
+    __syncthreads();
+
+    f4 acc[NJ][NBLK];
+#pragma unroll
+    for (int jj = 0; jj < NJ; ++jj)
+#pragma unroll
+        for (int b = 0; b < NBLK; ++b) acc[jj][b] = f4{0.f, 0.f, 0.f, 0.f};
+
+    const char* const abase = lds8 + BP * RB + wcx * AW + lane * 16;
+    const int sw = run16_swz(n, KS);             // rows of block b are 16 b + n: same swizzle for every block
+#pragma unroll
+    for (int s = 0; s < KS; ++s) {
+        u4v a[NJ][2];
+#pragma unroll
+        for (int jj = 0; jj < NJ; ++jj)
+#pragma unroll
+            for (int h = 0; h < 2; ++h)
+                a[jj][h] = *reinterpret_cast<const u4v*>(abase + ((jj * KS + s) * 2 + h) * 1024);
+#pragma unroll
+        for (int b = 0; b < NBLK; ++b) {
+            const char* row = lds8 + (wpix + b * 16 + n) * RB;
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                const u4v bo = *reinterpret_cast<const u4v*>(row + (((s * 8 + q * 2 + h) ^ sw) * 16));
+#pragma unroll
+                for (int jj = 0; jj < NJ; ++jj)
+                    acc[jj][b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
+                        __builtin_bit_cast(bf8x, a[jj][h]), __builtin_bit_cast(bf8x, bo), acc[jj][b], 0, 0, 0);
+            }
+        }
+    }
+
+    // ---- epilogue: bias, ReLU, round to bf16, NHWC store ------------------------
+    bf16_t* __restrict__ y = reinterpret_cast<bf16_t*>(p.y);
+#pragma unroll
+    for (int jj = 0; jj < NJ; ++jj) {
+        const int rb = rb0 + jj;
+        if (rb >= p.n_rowblocks) continue;
+        const int j = rb / p.rbpt;
+        const int sub = rb - j * p.rbpt;
+        const int rit = sub * 16 + q * 4;
+        const int co = j * p.tile + rit;
+        if (fast) {
+            if (rit >= p.tile || co >= p.Cout) continue;
+#pragma unroll
+            for (int b = 0; b < NBLK; ++b) {
+                const int pp = p0 + wpix + b * 16 + n;
+                if (pp >= p.P) continue;
+                f4 v = acc[jj][b] + bb[jj];
+                if (p.relu) {
+                    v.x = fmaxf(v.x, 0.f); v.y = fmaxf(v.y, 0.f);
+                    v.z = fmaxf(v.z, 0.f); v.w = fmaxf(v.w, 0.f);
+                }
+                store4(y + (size_t)pp * p.Cout + co, v);
+            }
+        } else {
+#pragma unroll
+            for (int b = 0; b < NBLK; ++b) {
+                const int pp = p0 + wpix + b * 16 + n;
+                if (pp >= p.P) continue;
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    if (rit + r >= p.tile || co + r >= p.Cout) continue;
+                    float v = acc[jj][b][r] + (p.bias ? p.bias[co + r] : 0.f);
+                    if (p.relu) v = fmaxf(v, 0.f);
+                    store1(y + (size_t)pp * p.Cout + co + r, v);
+                }
+            }
+        }
+    }
+}
+
+template <int NBLK, int WP, int NJ, int KS>
+int launch_run16_t(const ConvParams& p, hipStream_t s)
+{
+    auto kern = nm_conv_run16_kernel<NBLK, WP, NJ, KS>;
+    constexpr size_t lds = run16_lds_bytes(16 * NBLK * WP, WP, NJ, KS);
+    if (lds > 64 * 1024) {
+        static hipError_t once = hipFuncSetAttribute(
+            reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (once != hipSuccess) {
+            set_error("hipFuncSetAttribute(LDS %zu) failed: %s", lds, hipGetErrorString(once));
+            return NM_ERR_HIP;
+        }
+    }
+    hipLaunchKernelGGL(kern, dim3(p.wg_per_xcd * 8), dim3(256), lds, s, p);
+    NM_HIP_CHECK(hipGetLastError());
+    return NM_OK;
+}
+
+}  // namespace nm

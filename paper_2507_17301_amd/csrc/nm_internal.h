@@ -74,6 +74,10 @@ struct Prepack {
     //   a k-step is 64 consecutive channels of one tap; SPC = CK / 64
     //   d_rows  [n_tiles][nchunks][4][SPC] u32        kind 2: index operand of lane group q in k-step s
     //   d_wfrag [n_rowblocks][nchunks][SPC][AH][64][8] bf16   A-operand lane values, AH = 1 (kind 2) or 2 (kind 3)
+    // kind 4 (contiguous kernel-row runs, layers with very few input channels): one chunk of SPC
+    //   64-element k-steps; per pixel Kh runs of GR granules, each starting `par` elements early
+    //   d_wfrag [n_rowblocks][SPC][2][64][8] bf16   A-operand lane values, zero in padding slots
+    int par = 0;                      // kind 4: 0 or 1 elements of lead-in per run (alignment of the run start)
     uint32_t* d_rows = nullptr;
     float* d_wfrag = nullptr;
     size_t rows_bytes = 0, wfrag_bytes = 0;
@@ -130,6 +134,8 @@ struct ConvParams {
     int wg_per_xcd;
     // launch-time divisors as multiply-shift pairs (x / d = umulhi(x, mul) >> shift, mul == 0: d == 1)
     unsigned howo_mul, howo_shift, wo_mul, wo_shift;
+    int run_gr, run_d; // kind 4: granules per kernel-row run, lead-in elements of a run
+    unsigned x_elems;  // elements of x
     unsigned x_bytes;  // size of x in bytes (< 2 GiB), the range of the buffer descriptor
     unsigned wfrag_bytes, rows_bytes;
 };
@@ -144,7 +150,8 @@ struct VariantDesc {
     int SPC;   // k-steps per chunk
     int vec;   // chunk mode: 1 = 16-byte channel loads, 0 = element-wise on flat k
     int kind;  // 0 = fp32 MFMA kernel (fp32 or bf16 I/O), 1 = bf16 MFMA gather kernel (bf16 I/O, bf16 weights),
-               // 2 = bf16 sparse-matrix-instruction kernel, 3 = bf16 dense kernel on zero-filled weights
+               // 2 = bf16 sparse-matrix-instruction kernel, 3 = bf16 dense kernel on zero-filled weights,
+               // 4 = bf16 dense kernel on contiguous kernel-row runs (very few input channels)
     int share; // kind 1: row blocks fed from one gathered operand
 };
 
@@ -155,7 +162,7 @@ int launch_conv(int v, nm_dtype_t xdt, nm_dtype_t ydt, const ConvParams& p, hipS
 
 // prune-side kernels (nm_prune_kernels.hip)
 int run_prune(const float* d_w, nm_packed* wp, hipStream_t s);
-int run_build_prepack(nm_packed* wp, Prepack& pp, hipStream_t s);   // either kind
+int run_build_prepack(nm_packed* wp, Prepack& pp, hipStream_t s);   // any kind
 int run_build_mask(const nm_packed* wp, uint8_t* d_mask, hipStream_t s);
 int run_fill_random(void* d, size_t n_elems, nm_dtype_t dt, uint32_t seed, hipStream_t s);
 

@@ -12,4 +12,6 @@ template <int NBLK, int WP, int NJ, int CK, int SPC, int SHARE>
 int launch16_t(const ConvParams& p, hipStream_t s);
 template <int NBLK, int WP, int NJ, int CK, bool SPARSE>
 int launch_sp16_t(const ConvParams& p, hipStream_t s);
+template <int NBLK, int WP, int NJ, int KS>
+int launch_run16_t(const ConvParams& p, hipStream_t s);
 }  // namespace nm

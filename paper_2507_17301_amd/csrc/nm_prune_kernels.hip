@@ -287,6 +287,41 @@ __global__ __launch_bounds__(256) void build_prepack_sp16_kernel(
     }
 }
 
+// Operand table of the kernel-row-run kernel: element E = 64 s + 16 q + 8 h + e of
+// a pixel's padded K axis is position E % (8 GR) - par of the run of kernel row
+// E / (8 GR); positions outside [0, Kw*Cin) and rows >= Kh are padding (weight 0).
+__global__ __launch_bounds__(256) void build_prepack_run16_kernel(
+    const int32_t* __restrict__ idx, const float* __restrict__ vals, int kprime, int T, int rbpt,
+    int n_rowblocks, int Kh, int KwC, int KS, int GR, int par, unsigned short* __restrict__ wfrag)
+{
+    const size_t total = (size_t)n_rowblocks * KS * 2 * 64;
+    for (size_t id = (size_t)blockIdx.x * blockDim.x + threadIdx.x; id < total;
+         id += (size_t)gridDim.x * blockDim.x) {
+        const int lane = (int)(id % 64);
+        size_t r = id / 64;
+        const int h = (int)(r % 2); r /= 2;
+        const int s = (int)(r % KS);
+        const int rb = (int)(r / KS);
+        const int i = lane & 15, q = lane >> 4;
+        const int j = rb / rbpt, sub = rb - j * rbpt;
+        const int t = sub * 16 + i;
+        const int32_t* idxj = idx + (size_t)j * kprime;
+        unsigned short* dst = wfrag + id * 8;
+        for (int e = 0; e < 8; ++e) {
+            const int E = 64 * s + 16 * q + 8 * h + e;
+            const int kh = E / (8 * GR);
+            const int pos = E - kh * 8 * GR - par;
+            float v = 0.f;
+            if (kh < Kh && pos >= 0 && pos < KwC && t < T) {
+                const int k = kh * KwC + pos;
+                const int lb = lower_bound_idx(idxj, kprime, k);
+                if (lb < kprime && idxj[lb] == k) v = vals[((size_t)j * kprime + lb) * T + t];
+            }
+            dst[e] = (unsigned short)(__float_as_uint(v) >> 16);
+        }
+    }
+}
+
 __global__ void build_mask_kernel(const int32_t* __restrict__ idx, int cout, int K, int kprime,
                                   int T, int n_tiles, unsigned char* __restrict__ mask)
 {
@@ -365,7 +400,13 @@ int run_build_prepack(nm_packed* wp, Prepack& pp, hipStream_t s)
         hipLaunchKernelGGL(build_prepack_kernel, dim3(wp->n_tiles), dim3(256), lds, s, wp->d_idx,
                            wp->d_vals, wp->kprime, wp->tile, wp->rbpt, wp->cin, g.CK, g.vec, g.ncpt,
                            g.nchunks, pp.SPC, pp.d_rows, pp.d_wfrag, d_err);
-    else if (pp.kind >= 2) {
+    else if (pp.kind == 4) {
+        const int KwC = wp->kw * wp->cin, GR = (pp.par + KwC + 7) / 8;
+        const size_t total = (size_t)wp->n_rowblocks * pp.SPC * 2 * 64;
+        hipLaunchKernelGGL(build_prepack_run16_kernel, dim3(grid_for(total, 256)), dim3(256), 0, s,
+                           wp->d_idx, wp->d_vals, wp->kprime, wp->tile, wp->rbpt, wp->n_rowblocks, wp->kh,
+                           KwC, pp.SPC, GR, pp.par, reinterpret_cast<unsigned short*>(pp.d_wfrag));
+    } else if (pp.kind >= 2) {
         const size_t total = (size_t)wp->n_rowblocks * g.nchunks * pp.SPC * (pp.kind == 2 ? 1 : 2) * 64;
         hipLaunchKernelGGL(build_prepack_sp16_kernel, dim3(grid_for(total, 256)), dim3(256), 0, s,
                            wp->d_idx, wp->d_vals, wp->kprime, wp->tile, wp->rbpt, wp->n_rowblocks, wp->cin,

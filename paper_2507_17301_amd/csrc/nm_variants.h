@@ -48,3 +48,11 @@
 #define NMSP_CHUNKS(Y, NB, WP, NJ)                                   \
     Y(NB, WP, NJ, 64, 1) Y(NB, WP, NJ, 128, 1) Y(NB, WP, NJ, 256, 1) \
     Y(NB, WP, NJ, 64, 0) Y(NB, WP, NJ, 128, 0) Y(NB, WP, NJ, 256, 0)
+
+// bf16 kernel for layers with very few input channels (contiguous kernel-row
+// runs, one chunk of KS 64-element k-steps).
+// X(NBLK, WP, NJ)
+#define NMRUN_SHAPES(X) \
+    X(4, 1, 1) X(8, 1, 1) X(2, 1, 1) X(2, 2, 2) X(4, 2, 2) X(2, 4, 4) X(4, 4, 4) X(1, 4, 4) X(3, 4, 4) X(7, 1, 1)
+// Y(NBLK, WP, NJ, KS)
+#define NMRUN_CHUNKS(Y, NB, WP, NJ) Y(NB, WP, NJ, 1) Y(NB, WP, NJ, 2) Y(NB, WP, NJ, 3) Y(NB, WP, NJ, 4)

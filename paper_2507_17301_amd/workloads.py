@@ -79,6 +79,12 @@ def _dense(layer: ConvLayer) -> ConvLayer:
     return replace(layer, n=1, m=1)
 
 
+def dense_form(layer: ConvLayer, name: str = "dense") -> ConvLayer:
+    """The same convolution with nothing pruned (N = M = 1): the reference of the
+    sparse-over-dense speedup."""
+    return replace(layer, name=name, n=1, m=1)
+
+
 # --------------------------------------------------------------------------
 # layer tables
 # --------------------------------------------------------------------------

@@ -149,6 +149,60 @@ def test_every_variant_bf16(n, m, tile, cin):
         assert ran_sp == 0 and ran_dn == 0
 
 
+# name, H, W, Cin, Cout, Kh, Kw, stride, pad, dil, n, m, tile  | batch | the kernel-row-run kernel applies
+FEW_CHANNELS = [
+    (L("stem_7x7_s2", 30, 30, 3, 64, 7, 7, 2, 3, 1, 1, 1, 16), 3, True),      # runs start one element early
+    (L("c3_3x3_s2", 17, 18, 3, 40, 3, 3, 2, 1, 1, 1, 1, 16), 2, True),
+    (L("c3_5x5_s2_p2", 16, 16, 3, 32, 5, 5, 2, 2, 1, 1, 1, 16), 3, True),     # even padding: no lead-in
+    (L("c4_3x3_s1_2of4", 9, 10, 4, 48, 3, 3, 1, 1, 1, 2, 4, 16), 2, True),    # pruned, stride 1
+    (L("c2_7x7_s1", 12, 12, 2, 16, 7, 7, 1, 3, 1, 1, 1, 16), 2, True),
+    (L("c1_3x3_s2", 10, 12, 1, 20, 3, 3, 2, 1, 1, 1, 1, 16), 2, True),
+    (L("c3_3x3_pad0_T32", 11, 12, 3, 70, 3, 3, 2, 0, 1, 1, 1, 32), 2, True),
+    (L("c3_odd_width", 15, 15, 3, 32, 3, 3, 2, 1, 1, 1, 1, 16), 2, False),    # W*Cin odd: rows not 4-byte aligned
+    (L("c3_s1", 12, 12, 3, 32, 3, 3, 1, 1, 1, 1, 1, 16), 2, False),           # stride*Cin odd
+    (L("c4_dil2", 12, 12, 4, 32, 3, 3, 1, 2, 2, 1, 1, 16), 2, False),         # dilated columns are not one run
+]
+
+
+@pytest.mark.parametrize("layer,batch,applies", FEW_CHANNELS, ids=[g[0].name for g in FEW_CHANNELS])
+def test_few_input_channels_bf16(layer, batch, applies):
+    """Layers with very few input channels in bf16: the kernel that fetches whole kernel
+    rows as contiguous runs, every shape of it forced in turn, where the geometry allows
+    it; an error (never a wrong answer) where it does not; and the default choice."""
+    import torch
+    x, w, bias = wl.make_tensors(layer, batch, 31, weight_sigma=0.2)
+    ref = oracle_conv(layer, x, w, bias, relu=True, bf16=True)
+    wp = nm.nm_prune(w, layer.n, layer.m, layer.tile, nm.NM_BF16)
+    xd = torch.from_numpy(x).cuda().to(torch.bfloat16)
+    bd = torch.from_numpy(bias).cuda()
+    ran = refused = 0
+    try:
+        for v in range(nm.nm_variant_count()):
+            name = nm.nm_variant_name(v)
+            if not name.startswith("RUN") or not nm.nm_variant_legal(v, wp, nm.NM_BF16, nm.NM_BF16):
+                continue
+            say(f"forced {name} on {layer.name}")
+            nm.nm_force_variant(v)
+            try:
+                y = nm.nm_conv2d(xd, wp, bd, layer.stride, layer.pad, layer.dil, True)
+            except nm.NMError as e:
+                assert e.code == nm.NM_ERR_UNSUPPORTED
+                refused += 1
+                continue
+            torch.cuda.synchronize()
+            assert norm_err(y.float().cpu().numpy(), ref) <= BF16_TOL, name
+            ran += 1
+    finally:
+        nm.nm_force_variant(-1)
+    if applies:
+        assert ran >= 5 and refused == 0
+    else:
+        assert ran == 0
+    y = nm.nm_conv2d(xd, wp, bd, layer.stride, layer.pad, layer.dil, True)
+    torch.cuda.synchronize()
+    assert norm_err(y.float().cpu().numpy(), ref) <= BF16_TOL
+
+
 def test_illegal_forced_variant_is_an_error_not_a_fallback():
     layer = L("flat_only", 6, 6, 6, 16, 3, 3, 1, 1, 1, 1, 2, 16)
     x, w, bias = wl.make_tensors(layer, 1, 3)
