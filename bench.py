@@ -1,6 +1,7 @@
 #!/usr/bin/env python3
 """Benchmark: ResNet-50 convolution stack, column-wise 2:4 (T = 16), batch 64,
-on one MI355X.
+on one MI355X (the default; --workload selects the other workloads, which are
+reported the same way but are not the headline).
 
 A step is one pass of the hot path over one batch: all 53 convolutions
 (fused im2col+pack, kept-column contraction, bias + ReLU) launched back to back
@@ -216,7 +217,8 @@ def main():
     roofline.update({
         # HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled by what the same
         # counters read for the 1 GiB device copy above (profiles/); measured for the default workload only
-        "traffic": 111.7e6 if (args.workload == "resnet50" and args.dtype == "f32" and B == 64) else None,
+        "traffic": ({"f32": 111.3e6, "bf16": 56.3e6}[args.dtype]
+                    if (args.workload == "resnet50" and B == 64) else None),
         "kernel": "nm_conv_sp16_kernel" if bf16 else "nm_conv_kernel", "launches_per_step": len(layers),
         "avg_launch_ms": kern_ms / len(layers),
         "frac_of_binding_roofline_per_layer": tmin_ms / kern_ms,

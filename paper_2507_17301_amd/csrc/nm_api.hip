@@ -51,13 +51,17 @@ ShapeKey make_key(nm_dtype_t xdt, nm_dtype_t ydt, int b, int h, int w, const nm_
     return k;
 }
 
-size_t lds_bytes(const VariantDesc& d)
+// LDS footprint of variant d on the layer wp (the ring of the gather-free bf16
+// kernel is only as deep as the layer's K loop is long).
+size_t lds_bytes(const VariantDesc& d, const nm_packed* wp)
 {
     if (d.kind == 4)   // the strip [BP][64 SPC] bf16 plus the dense weights of the workgroup's row blocks
         return (size_t)d.BP * d.SPC * 128 + (size_t)(4 / d.WP) * d.NJ * d.SPC * 2048;
-    if (d.kind >= 2)   // three stages of the strip [BP][CK] bf16 plus each wave's operands
-        return (size_t)3 * (d.BP * d.CK * 2 +
-                            4 * d.NJ * (d.CK / 64) * (d.kind == 2 ? 1024 + 256 : 2048));
+    if (d.kind >= 2) {   // up to three stages of the strip [BP][CK] bf16 plus each wave's operands
+        const int nchunks = wp->kh * wp->kw * ((wp->cin + d.CK - 1) / d.CK);
+        return (size_t)std::min(3, nchunks) *
+               (d.BP * d.CK * 2 + 4 * d.NJ * (d.CK / 64) * (d.kind == 2 ? 1024 + 256 : 2048));
+    }
     if (d.kind == 1) {
         const int opr = d.CK / 8, pstep = 256 / opr, nit = (d.BP * opr + 255) / 256;
         const int rows = nit * pstep > d.BP ? nit * pstep : d.BP;
@@ -93,7 +97,7 @@ bool variant_legal(int v, const nm_packed* wp, nm_dtype_t xdt, const RunArgs* ra
 {
     if (v < 0 || v >= variant_count()) return false;
     const VariantDesc& d = variant_desc(v);
-    if (lds_bytes(d) > (size_t)kMaxLdsBytes) return false;
+    if (lds_bytes(d, wp) > (size_t)kMaxLdsBytes) return false;
     if (d.kind >= 1) {
         // bf16 matrix cores: bf16 tensors, weights already rounded to bf16, and a
         // shared operand only for column tiles made of exactly two row blocks
@@ -216,7 +220,7 @@ int heuristic_variant(const nm_packed* wp, int P, nm_dtype_t xdt, const RunArgs*
         const long n_pt = (P + d.BP - 1) / d.BP;
         const long n_cb = (wp->n_rowblocks + rb_per_wg - 1) / rb_per_wg;
         const long n_wg = n_pt * n_cb;
-        int occ = (int)std::min<size_t>(2, kMaxLdsBytes / lds_bytes(d));
+        int occ = (int)std::min<size_t>(2, kMaxLdsBytes / lds_bytes(d, wp));
         if (occ < 1) occ = 1;
         const long rounds = (n_wg + (long)kNumCU * occ - 1) / ((long)kNumCU * occ);
         const double mfma = (double)d.BP * rb_per_wg;            // per chunk step, relative

@@ -393,17 +393,22 @@ int launch_sp16_t(const ConvParams& p, hipStream_t s)
 {
     auto kern = nm_conv_sp16_kernel<NBLK, WP, NJ, CK, SPARSE>;
     constexpr size_t stage = sp16_stage_bytes(16 * NBLK * WP, CK, NJ, SPARSE);
-    if (kSp16Stages * stage > 64 * 1024) {
+    // the most this kernel may ever be launched with: the full ring, or what the CU has
+    constexpr size_t most = kSp16Stages * stage < 160 * 1024 ? kSp16Stages * stage : 160 * 1024;
+    if (most > 64 * 1024) {
         static hipError_t once = hipFuncSetAttribute(
-            reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
-            (int)(kSp16Stages * stage));
+            reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)most);
         if (once != hipSuccess) {
-            set_error("hipFuncSetAttribute(LDS %zu) failed: %s", kSp16Stages * stage, hipGetErrorString(once));
+            set_error("hipFuncSetAttribute(LDS %zu) failed: %s", most, hipGetErrorString(once));
             return NM_ERR_HIP;
         }
     }
     // short K loops use (and allocate) fewer stages, which leaves room for more workgroups per CU
     const size_t lds = stage * (size_t)(p.nchunks < kSp16Stages ? p.nchunks : kSp16Stages);
+    if (lds > most) {
+        set_error("internal: LDS %zu bytes exceed the CU's 160 KB", lds);
+        return NM_ERR_UNSUPPORTED;
+    }
     hipLaunchKernelGGL(kern, dim3(p.wg_per_xcd * 8), dim3(256), lds, s, p);
     NM_HIP_CHECK(hipGetLastError());
     return NM_OK;

@@ -109,16 +109,17 @@ def test_every_variant_other_sparsities(n, m, tile):
     assert ran >= 9
 
 
-@pytest.mark.parametrize("n,m,tile,cin", [(2, 4, 16, 64), (2, 8, 32, 128), (1, 4, 32, 64), (4, 8, 8, 64),
-                                            (1, 1, 16, 32), (2, 4, 16, 40), (2, 4, 16, 256), (1, 8, 16, 128),
-                                            (1, 1, 16, 64)])
-def test_every_variant_bf16(n, m, tile, cin):
+@pytest.mark.parametrize("n,m,tile,cin,ksize", [
+    (2, 4, 16, 64, 3), (2, 8, 32, 128, 3), (1, 4, 32, 64, 3), (4, 8, 8, 64, 3), (1, 1, 16, 32, 3),
+    (2, 4, 16, 40, 3), (2, 4, 16, 256, 3), (1, 8, 16, 128, 3), (1, 1, 16, 64, 3), (6, 8, 32, 64, 3),
+    (2, 4, 16, 256, 1), (1, 4, 32, 512, 1)])   # 1x1: K loops of one or two chunks, which need less LDS
+def test_every_variant_bf16(n, m, tile, cin, ksize):
     """bf16 tensors: every legal variant, i.e. the fp32-MFMA kernels on bf16 data, the
     bf16 matrix-core gather kernels (T = 32 also with the shared operand) and, where
     the channel count is a multiple of 64, the gather-free kernels (sparse matrix
     instruction for N <= 2 of M % 4 == 0, dense instruction on zero-filled weights
     for everything), forced in turn."""
-    layer = L("variants_bf16", 11, 9, cin, 80, 3, 3, 1, 1, 1, n, m, tile)
+    layer = L("variants_bf16", 11, 9, cin, 80, ksize, ksize, 1, ksize // 2, 1, n, m, tile)
     x, w, bias = wl.make_tensors(layer, 3, 9, weight_sigma=0.1)
     ref = oracle_conv(layer, x, w, bias, relu=True, bf16=True)
     import torch
@@ -130,9 +131,9 @@ def test_every_variant_bf16(n, m, tile, cin):
         for v in range(nm.nm_variant_count()):
             if not nm.nm_variant_legal(v, wp, nm.NM_BF16, nm.NM_BF16):
                 continue
-            say(f"forced bf16 variant {v} {nm.nm_variant_name(v)} {n}:{m} T={tile} cin={cin}")
+            say(f"forced bf16 variant {v} {nm.nm_variant_name(v)} {n}:{m} T={tile} cin={cin} k={ksize}")
             nm.nm_force_variant(v)
-            y = nm.nm_conv2d(xd, wp, bd, 1, 1, 1, True)
+            y = nm.nm_conv2d(xd, wp, bd, layer.stride, layer.pad, layer.dil, True)
             torch.cuda.synchronize()
             assert norm_err(y.float().cpu().numpy(), ref) <= BF16_TOL, nm.nm_variant_name(v)
             ran += 1
@@ -157,6 +158,7 @@ FEW_CHANNELS = [
     (L("c4_3x3_s1_2of4", 9, 10, 4, 48, 3, 3, 1, 1, 1, 2, 4, 16), 2, True),    # pruned, stride 1
     (L("c2_7x7_s1", 12, 12, 2, 16, 7, 7, 1, 3, 1, 1, 1, 16), 2, True),
     (L("c1_3x3_s2", 10, 12, 1, 20, 3, 3, 2, 1, 1, 1, 1, 16), 2, True),
+    (L("c4_7x7_s1_four_ksteps", 10, 10, 4, 16, 7, 7, 1, 3, 1, 1, 1, 16), 2, True),
     (L("c3_3x3_pad0_T32", 11, 12, 3, 70, 3, 3, 2, 0, 1, 1, 1, 32), 2, True),
     (L("c3_odd_width", 15, 15, 3, 32, 3, 3, 2, 1, 1, 1, 1, 16), 2, False),    # W*Cin odd: rows not 4-byte aligned
     (L("c3_s1", 12, 12, 3, 32, 3, 3, 1, 1, 1, 1, 1, 16), 2, False),           # stride*Cin odd
