@@ -44,6 +44,11 @@ def main():
                     help="resnet50 (default, the headline: 53 layers 2:4 T16 batch 64) | resnet18 (batch 32) | "
                          "resnet101 (mixed sparsity, T32, batch 256, bf16) | sweep (15 N:M x T cells of one "
                          "3x3 layer + its dense form, batch 32) | single (one 3x3 layer, batch 1)")
+    ap.add_argument("--tile", type=int, default=None,
+                    help="experiment: tile size T of the ResNet workloads (1 = conventional row-wise N:M)")
+    ap.add_argument("--nm", default=None, help="experiment: N:M of the ResNet-18/50 workloads, e.g. 1:4")
+    ap.add_argument("--group", choices=["cin", "row"], default=None,
+                    help="experiment: one group per kernel tap (M = Cin) or per row (M = K), half the columns kept")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-tune", action="store_true", help="use the untuned default variant")
     ap.add_argument("--no-graph", action="store_true",
@@ -69,12 +74,17 @@ def main():
     dev = torch.device("cuda:0")
     nm.lib()
 
+    n_, m_ = (int(v) for v in args.nm.split(":")) if args.nm else (2, 4)
+    t_ = args.tile or 16
     if args.workload == "resnet50":
-        layers, B, wname, seed0 = wl.resnet50_stack(2, 4, 16), 64, "resnet50_conv_stack_53layers_2of4_T16", 4000
+        layers, B, seed0 = wl.resnet50_stack(n_, m_, t_), 64, 4000
+        wname = f"resnet50_conv_stack_53layers_{n_}of{m_}_T{t_}"
     elif args.workload == "resnet18":
-        layers, B, wname, seed0 = wl.resnet18_stack(2, 4, 16), 32, "resnet18_conv_stack_20layers_2of4_T16", 3000
+        layers, B, seed0 = wl.resnet18_stack(n_, m_, t_), 32, 3000
+        wname = f"resnet18_conv_stack_20layers_{n_}of{m_}_T{t_}"
     elif args.workload == "resnet101":
-        layers, B, wname, seed0 = wl.resnet101_stack(32), 256, "resnet101_conv_stack_104layers_mixed_T32", 5000
+        layers, B, seed0 = wl.resnet101_stack(args.tile or 32), 256, 5000
+        wname = f"resnet101_conv_stack_104layers_mixed_T{args.tile or 32}"
         if "--dtype" not in sys.argv:
             args.dtype = "bf16"
     elif args.workload == "sweep":
@@ -82,8 +92,12 @@ def main():
         layers, B, wname, seed0 = cells + [wl.dense_form(cells[1], "cfg2_dense_T16")], 32, "sweep_3x3_256ch_14x14_15cells_plus_dense", 0
     else:
         layers, B, wname, seed0 = [wl.single_conv_config1()], 1, "single_3x3_64ch_56x56_2of4_T16", 0
+    if args.group:
+        layers = wl.with_large_groups(layers, args.group)
+        wname += "_groups_per_" + args.group
     if args.batch is not None:
         B = args.batch
+    headline = (args.workload == "resnet50" and B == 64 and not args.group and (n_, m_, t_) == (2, 4, 16))
     bf16 = args.dtype == "bf16"
     tdt = torch.bfloat16 if bf16 else torch.float32
     ndt = nm.NM_BF16 if bf16 else nm.NM_F32
@@ -217,8 +231,7 @@ def main():
     roofline.update({
         # HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled by what the same
         # counters read for the 1 GiB device copy above (profiles/); measured for the default workload only
-        "traffic": ({"f32": 111.3e6, "bf16": 56.3e6}[args.dtype]
-                    if (args.workload == "resnet50" and B == 64) else None),
+        "traffic": {"f32": 111.3e6, "bf16": 56.3e6}[args.dtype] if headline else None,
         "kernel": "nm_conv_sp16_kernel" if bf16 else "nm_conv_kernel", "launches_per_step": len(layers),
         "avg_launch_ms": kern_ms / len(layers),
         "frac_of_binding_roofline_per_layer": tmin_ms / kern_ms,
@@ -238,7 +251,7 @@ def main():
         cpu = cpu_baseline(layers, B, bf16, seed0)
 
     out = {
-        "metric": ("dense-equiv GFLOP/s, ResNet-50 conv stack 2:4 @batch 64" if args.workload == "resnet50" and B == 64
+        "metric": ("dense-equiv GFLOP/s, ResNet-50 conv stack 2:4 @batch 64" if headline
                    else f"dense-equiv GFLOP/s, {wname} @batch {B}"),
         "value": dense / ms_step / 1e6, "unit": "GFLOP/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,

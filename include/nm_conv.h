@@ -126,6 +126,39 @@ int nm_conv2d(const void* x_dev, nm_dtype_t x_dtype, int b, int h, int w, int ci
               int relu, void* y_dev, nm_dtype_t y_dtype, void* hip_stream);
 
 /*
+ * nm_conv2d_res -- nm_conv2d with a residual input, for the convolution that
+ * closes a residual block (the networks of section 4 are ResNets):
+ *   y = relu?( conv(x, W_pruned) + bias + residual )
+ * The sum is formed in fp32 in the kernel's epilogue, so the block's skip
+ * connection costs one extra read of `residual` and no extra pass over y.
+ *   residual_dev  device pointer shaped and typed like y ([b][hout][wout][cout]
+ *                 of y_dtype), 16-byte aligned, only read, must not overlap y;
+ *                 NULL makes the call identical to nm_conv2d
+ * Everything else as for nm_conv2d (same variant choice, same tuning cache).
+ */
+int nm_conv2d_res(const void* x_dev, nm_dtype_t x_dtype, int b, int h, int w, int cin,
+                  const nm_packed_t* wp, const float* bias_dev, const void* residual_dev,
+                  int stride_h, int stride_w, int pad_h, int pad_w, int dil_h, int dil_w,
+                  int relu, void* y_dev, nm_dtype_t y_dtype, void* hip_stream);
+
+/*
+ * The two pooling layers a ResNet needs around its convolutions, so that a whole
+ * network can run on device tensors through this library (section 4 measures
+ * whole networks).  NHWC, fp32 or bf16 (same dtype in and out), enqueue-only.
+ *
+ * nm_maxpool2d: y[b][ho][wo][c] = max over the k x k window at stride `stride`
+ *   with `pad` rows/columns of padding that never win (windows lie inside the
+ *   padded image; hout = (h + 2*pad - k)/stride + 1, same for w).
+ * nm_avgpool_global: y[b][c] = mean over all h*w positions (fp32 sum).
+ * Errors: NM_ERR_ARG (null, sizes < 1, pad >= k, unknown dtype), NM_ERR_SHAPE
+ * (empty output), NM_ERR_HIP.
+ */
+int nm_maxpool2d(const void* x_dev, nm_dtype_t dtype, int b, int h, int w, int c,
+                 int k, int stride, int pad, void* y_dev, void* hip_stream);
+int nm_avgpool_global(const void* x_dev, nm_dtype_t dtype, int b, int h, int w, int c,
+                      void* y_dev, void* hip_stream);
+
+/*
  * nm_autotune -- per-layer choice of the fastest kernel variant (section 3.3:
  * every candidate is run on the target and the fastest kept).  Runs each legal
  * variant for this shape on library-allocated scratch tensors (pseudo-random

@@ -50,6 +50,12 @@ def _load():
         L.oracle_conv2d.restype = ci
         L.oracle_conv2d_points.argtypes = conv_common + [i32p, ctypes.c_long, fp]
         L.oracle_conv2d_points.restype = ci
+        L.oracle_conv2d_res.argtypes = (conv_common[:10] + [fp] + conv_common[10:] + [fp])
+        L.oracle_conv2d_res.restype = ci
+        L.oracle_maxpool2d.argtypes = [fp, ci, ci, ci, ci, ci, ci, ci, fp]
+        L.oracle_maxpool2d.restype = ci
+        L.oracle_avgpool_global.argtypes = [fp, ci, ci, ci, ci, ci, fp]
+        L.oracle_avgpool_global.restype = ci
         L.oracle_out_size.argtypes = [ci] * 10 + [ctypes.POINTER(ci), ctypes.POINTER(ci)]
         L.oracle_out_size.restype = ci
         _lib = L
@@ -160,6 +166,51 @@ def conv2d(x, w, bias=None, stride=1, pad=0, dil=1, relu=False, out_bf16=False,
                                int(nthreads))
     if rc != 0:
         raise ValueError("oracle_conv2d rejected its arguments")
+    return y
+
+
+def conv2d_res(x, w, residual, bias=None, stride=1, pad=0, dil=1, relu=False, out_bf16=False):
+    """relu?(conv(x, w) + bias + residual); residual is shaped like the output."""
+    args, keep, oshape = _conv_args(x, w, bias, stride, pad, dil, relu, out_bf16)
+    res = np.ascontiguousarray(residual, dtype=np.float32)
+    if res.shape != tuple(oshape):
+        raise ValueError("residual must be shaped like the output")
+    y = np.empty(oshape, dtype=np.float32)
+    fp = ctypes.POINTER(ctypes.c_float)
+    # argument order of the C function: ..., bias, residual, strides ...
+    head, tail = args[:10], args[10:]
+    rc = _load().oracle_conv2d_res(*head, res.ctypes.data_as(fp), *tail, y.ctypes.data_as(fp))
+    if rc != 0:
+        raise ValueError("oracle_conv2d_res rejected its arguments")
+    return y
+
+
+def maxpool2d(x, k, stride, pad):
+    """Max pooling of x [B,H,W,C] with a k x k window; padding never wins."""
+    x = np.ascontiguousarray(x, dtype=np.float32)
+    B, H, W, C = x.shape
+    if H + 2 * pad < k or W + 2 * pad < k:
+        raise ValueError("empty output")
+    Ho, Wo = (H + 2 * pad - k) // stride + 1, (W + 2 * pad - k) // stride + 1
+    y = np.empty((B, Ho, Wo, C), dtype=np.float32)
+    fp = ctypes.POINTER(ctypes.c_float)
+    rc = _load().oracle_maxpool2d(x.ctypes.data_as(fp), B, H, W, C, int(k), int(stride), int(pad),
+                                  y.ctypes.data_as(fp))
+    if rc != 0:
+        raise ValueError("oracle_maxpool2d rejected its arguments")
+    return y
+
+
+def avgpool_global(x, out_bf16=False):
+    """Mean over all positions: x [B,H,W,C] -> [B,C]."""
+    x = np.ascontiguousarray(x, dtype=np.float32)
+    B, H, W, C = x.shape
+    y = np.empty((B, C), dtype=np.float32)
+    fp = ctypes.POINTER(ctypes.c_float)
+    rc = _load().oracle_avgpool_global(x.ctypes.data_as(fp), B, H, W, C, int(bool(out_bf16)),
+                                       y.ctypes.data_as(fp))
+    if rc != 0:
+        raise ValueError("oracle_avgpool_global rejected its arguments")
     return y
 
 

@@ -165,6 +165,7 @@ typedef struct {
     const float* x;
     const float* w;
     const float* bias;
+    const float* res;        /* residual shaped like y, or NULL */
     float* y;
     int B, H, W, Cin, Cout, Kh, Kw;
     int sh, sw, ph, pw, dh, dw;
@@ -190,6 +191,8 @@ static float conv_point(const conv_job* J, int b, int ho, int wo, int co)
         }
     }
     if (J->bias) acc += (double)J->bias[co];
+    if (J->res)                                        /* skip connection, before the activation */
+        acc += (double)J->res[(((long)b * J->Ho + ho) * J->Wo + wo) * J->Cout + co];
     if (J->relu && acc < 0.0) acc = 0.0;
     float r = (float)acc;                              /* one rounding */
     if (J->out_bf16) r = round_to_bf16(r);
@@ -221,7 +224,7 @@ static int fill_job(conv_job* J, const float* x, int B, int H, int W, int Cin,
     const int eh = H + 2 * ph - dh * (Kh - 1) - 1;
     const int ew = W + 2 * pw - dw * (Kw - 1) - 1;
     if (eh < 0 || ew < 0) return ORACLE_ERR_ARG;
-    J->x = x; J->w = w; J->bias = bias; J->y = y;
+    J->x = x; J->w = w; J->bias = bias; J->res = NULL; J->y = y;
     J->B = B; J->H = H; J->W = W; J->Cin = Cin; J->Cout = Cout; J->Kh = Kh; J->Kw = Kw;
     J->sh = sh; J->sw = sw; J->ph = ph; J->pw = pw; J->dh = dh; J->dw = dw;
     J->Ho = eh / sh + 1;
@@ -266,6 +269,74 @@ int oracle_conv2d(const float* x, int B, int H, int W, int Cin,
     for (int t = 0; t < nthreads; ++t)
         if (pthread_create(&th[t], NULL, conv_rows, &jobs[t]) != 0) return ORACLE_ERR_ARG;
     for (int t = 0; t < nthreads; ++t) pthread_join(th[t], NULL);
+    return ORACLE_OK;
+}
+
+/*
+ * The convolution that closes a residual block:
+ *   y = relu?( conv(x, w) + bias + residual ), residual[B][Ho][Wo][Cout],
+ * the whole sum in double, one rounding.  Single-threaded.
+ */
+int oracle_conv2d_res(const float* x, int B, int H, int W, int Cin,
+                      const float* w, int Cout, int Kh, int Kw, const float* bias,
+                      const float* residual,
+                      int sh, int sw, int ph, int pw, int dh, int dw,
+                      int relu, int out_bf16, float* y)
+{
+    conv_job J;
+    int rc = fill_job(&J, x, B, H, W, Cin, w, Cout, Kh, Kw, bias,
+                      sh, sw, ph, pw, dh, dw, relu, out_bf16, y);
+    if (rc != ORACLE_OK) return rc;
+    J.res = residual;
+    J.row_begin = 0;
+    J.row_end = (long)B * J.Ho;
+    conv_rows(&J);
+    return ORACLE_OK;
+}
+
+/*
+ * Max pooling, NHWC, k x k window, padding never wins:
+ *   y[b][ho][wo][c] = max over the in-image positions of the window.
+ */
+int oracle_maxpool2d(const float* x, int B, int H, int W, int C, int k, int stride, int pad, float* y)
+{
+    if (!x || !y || B < 1 || H < 1 || W < 1 || C < 1 || k < 1 || stride < 1 || pad < 0 || pad >= k)
+        return ORACLE_ERR_ARG;
+    if (H + 2 * pad < k || W + 2 * pad < k) return ORACLE_ERR_ARG;
+    const int Ho = (H + 2 * pad - k) / stride + 1, Wo = (W + 2 * pad - k) / stride + 1;
+    for (int b = 0; b < B; ++b)
+        for (int ho = 0; ho < Ho; ++ho)
+            for (int wo = 0; wo < Wo; ++wo)
+                for (int c = 0; c < C; ++c) {
+                    int have = 0;
+                    float m = 0.f;
+                    for (int kh = 0; kh < k; ++kh) {
+                        const int hi = ho * stride - pad + kh;
+                        if (hi < 0 || hi >= H) continue;
+                        for (int kw = 0; kw < k; ++kw) {
+                            const int wi = wo * stride - pad + kw;
+                            if (wi < 0 || wi >= W) continue;
+                            const float v = x[(((long)b * H + hi) * W + wi) * C + c];
+                            if (!have || v > m) { m = v; have = 1; }
+                        }
+                    }
+                    y[(((long)b * Ho + ho) * Wo + wo) * C + c] = m;
+                }
+    return ORACLE_OK;
+}
+
+/* Global average pooling: y[b][c] = mean of x[b][.][.][c], summed in double, one rounding. */
+int oracle_avgpool_global(const float* x, int B, int H, int W, int C, int out_bf16, float* y)
+{
+    if (!x || !y || B < 1 || H < 1 || W < 1 || C < 1) return ORACLE_ERR_ARG;
+    for (int b = 0; b < B; ++b)
+        for (int c = 0; c < C; ++c) {
+            double s = 0.0;
+            for (long i = 0; i < (long)H * W; ++i) s += (double)x[((long)b * H * W + i) * C + c];
+            float r = (float)(s / (double)((long)H * W));
+            if (out_bf16) r = round_to_bf16(r);
+            y[(long)b * C + c] = r;
+        }
     return ORACLE_OK;
 }
 

@@ -52,6 +52,9 @@ def lib():
         L.nm_packed_values.argtypes = [vp, vp]
         L.nm_packed_mask.argtypes = [vp, vp]
         L.nm_conv2d.argtypes = [vp, ci, ci, ci, ci, ci, vp, vp, ci, ci, ci, ci, ci, ci, ci, vp, ci, vp]
+        L.nm_conv2d_res.argtypes = [vp, ci, ci, ci, ci, ci, vp, vp, vp, ci, ci, ci, ci, ci, ci, ci, vp, ci, vp]
+        L.nm_maxpool2d.argtypes = [vp, ci, ci, ci, ci, ci, ci, ci, ci, vp, vp]
+        L.nm_avgpool_global.argtypes = [vp, ci, ci, ci, ci, ci, vp, vp]
         L.nm_autotune.argtypes = [ci, ci, ci, ci, ci, vp, ci, ci, ci, ci, ci, ci, ci, ci, ci, vp,
                                   pi, ctypes.POINTER(cf)]
         L.nm_cache_save.argtypes = [ctypes.c_char_p]
@@ -59,7 +62,8 @@ def lib():
         L.nm_force_variant.argtypes = [ci]
         L.nm_variant_legal.argtypes = [ci, vp, ci, ci]
         for name in ("nm_prune", "nm_packed_free", "nm_packed_dims", "nm_packed_indices",
-                     "nm_packed_values", "nm_packed_mask", "nm_conv2d", "nm_autotune",
+                     "nm_packed_values", "nm_packed_mask", "nm_conv2d", "nm_conv2d_res", "nm_maxpool2d",
+                     "nm_avgpool_global", "nm_autotune",
                      "nm_cache_save", "nm_cache_load", "nm_cache_clear", "nm_cache_size",
                      "nm_force_variant", "nm_variant_legal"):
             getattr(L, name).restype = ci
@@ -189,6 +193,68 @@ def nm_conv2d(x, wp: Packed, bias=None, stride=1, pad=0, dil=1, relu=False, y=No
     _check(lib().nm_conv2d(x.data_ptr(), _dtype_code(x), b, h, w, cin, wp.handle, bptr,
                            sh, sw, ph, pw, dh, dw, int(bool(relu)), y.data_ptr(), _dtype_code(y),
                            _stream_ptr(stream)))
+    return y
+
+
+def nm_conv2d_res(x, wp: Packed, residual, bias=None, stride=1, pad=0, dil=1, relu=False, y=None,
+                  stream=None):
+    """nm_conv2d with a residual (device tensor shaped and typed like the output, or None)
+    added before the activation."""
+    import torch
+    if not x.is_cuda or not x.is_contiguous():
+        raise ValueError("x must be a contiguous device tensor")
+    b, h, w, cin = x.shape
+    sh, sw = _pair(stride)
+    ph, pw = _pair(pad)
+    dh, dw = _pair(dil)
+    shp = out_shape(x.shape, wp, stride, pad, dil)
+    if min(shp) < 1:
+        raise NMError(-2, "output would be empty")
+    if y is None:
+        y = torch.empty(shp, dtype=x.dtype, device=x.device)
+    rptr = None
+    if residual is not None:
+        if (tuple(residual.shape) != tuple(shp) or residual.dtype != y.dtype or not residual.is_cuda
+                or not residual.is_contiguous()):
+            raise ValueError("residual must be a contiguous device tensor shaped and typed like the output")
+        rptr = residual.data_ptr()
+    bptr = None
+    if bias is not None:
+        if bias.dtype != torch.float32 or not bias.is_cuda or not bias.is_contiguous():
+            raise ValueError("bias must be a contiguous fp32 device tensor")
+        bptr = bias.data_ptr()
+    _check(lib().nm_conv2d_res(x.data_ptr(), _dtype_code(x), b, h, w, cin, wp.handle, bptr, rptr,
+                               sh, sw, ph, pw, dh, dw, int(bool(relu)), y.data_ptr(), _dtype_code(y),
+                               _stream_ptr(stream)))
+    return y
+
+
+def nm_maxpool2d(x, k: int, stride: int, pad: int, y=None, stream=None):
+    """Max pooling of a contiguous NHWC device tensor (fp32 or bf16)."""
+    import torch
+    if not x.is_cuda or not x.is_contiguous():
+        raise ValueError("x must be a contiguous device tensor")
+    b, h, w, c = x.shape
+    ho, wo = (h + 2 * pad - k) // stride + 1, (w + 2 * pad - k) // stride + 1
+    if y is None:
+        if min(ho, wo) < 1:
+            raise NMError(-2, "output would be empty")
+        y = torch.empty((b, ho, wo, c), dtype=x.dtype, device=x.device)
+    _check(lib().nm_maxpool2d(x.data_ptr(), _dtype_code(x), b, h, w, c, k, stride, pad, y.data_ptr(),
+                              _stream_ptr(stream)))
+    return y
+
+
+def nm_avgpool_global(x, y=None, stream=None):
+    """Mean over all positions of a contiguous NHWC device tensor: [B,H,W,C] -> [B,C]."""
+    import torch
+    if not x.is_cuda or not x.is_contiguous():
+        raise ValueError("x must be a contiguous device tensor")
+    b, h, w, c = x.shape
+    if y is None:
+        y = torch.empty((b, c), dtype=x.dtype, device=x.device)
+    _check(lib().nm_avgpool_global(x.data_ptr(), _dtype_code(x), b, h, w, c, y.data_ptr(),
+                                   _stream_ptr(stream)))
     return y
 
 

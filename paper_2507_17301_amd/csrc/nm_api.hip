@@ -183,7 +183,7 @@ void fill_params(ConvParams& p, const VariantDesc& d, const Prepack& pp, const n
                  const void* x, void* y, const float* bias, int b, int h, int w, const Geometry& g,
                  int sh, int sw, int ph, int pw, int dh, int dw, int relu, size_t es)
 {
-    p.x = x; p.y = y; p.bias = bias;
+    p.x = x; p.y = y; p.bias = bias; p.res = nullptr;
     p.wfrag = pp.d_wfrag; p.rows = pp.d_rows; p.ktab = pp.d_ktab;
     p.wfrag_bytes = (unsigned)pp.wfrag_bytes; p.rows_bytes = (unsigned)pp.rows_bytes;
     p.B = b; p.H = h; p.W = w; p.Cin = wp->cin; p.Cout = wp->cout; p.Kh = wp->kh; p.Kw = wp->kw;
@@ -563,15 +563,27 @@ int nm_variant_legal(int variant, const nm_packed_t* wp, nm_dtype_t xdt, nm_dtyp
     return variant_legal(variant, wp, xdt) ? 1 : 0;
 }
 
-int nm_conv2d(const void* x, nm_dtype_t xdt, int b, int h, int w, int cin, const nm_packed_t* wp,
-              const float* bias, int sh, int sw, int ph, int pw, int dh, int dw, int relu, void* y,
-              nm_dtype_t ydt, void* stream)
+static int conv2d_impl(const void* x, nm_dtype_t xdt, int b, int h, int w, int cin, const nm_packed_t* wp,
+                       const float* bias, const void* res, int sh, int sw, int ph, int pw, int dh, int dw,
+                       int relu, void* y, nm_dtype_t ydt, void* stream)
 {
     int rc = check_conv_args(x, xdt, cin, wp, y, ydt);
     if (rc != NM_OK) return rc;
+    if (res && ((uintptr_t)res % (ydt == NM_F32 ? 16 : 8))) {
+        set_error("residual must be 16-byte aligned");
+        return NM_ERR_ARG;
+    }
     Geometry g;
     rc = conv_geometry(b, h, w, wp, sh, sw, ph, pw, dh, dw, xdt == NM_F32 ? 4 : 2, &g);
     if (rc != NM_OK) return rc;
+    if (res) {
+        const size_t ybytes = (size_t)g.P * wp->cout * (ydt == NM_F32 ? 4 : 2);
+        const uintptr_t r0 = (uintptr_t)res, y0 = (uintptr_t)y;
+        if (r0 < y0 + ybytes && y0 < r0 + ybytes) {
+            set_error("residual must not overlap y");
+            return NM_ERR_ARG;
+        }
+    }
 
     int v = -1;
     {
@@ -598,9 +610,57 @@ int nm_conv2d(const void* x, nm_dtype_t xdt, int b, int h, int w, int cin, const
     }
     const VariantDesc& d = variant_desc(v);
     ConvParams p;
-    fill_params(p, d, *find_prepack(wp, d, (pw * wp->cin) % 2), wp, x, y, bias, b, h, w, g, sh, sw, ph, pw, dh, dw, relu,
-                xdt == NM_F32 ? 4 : 2);
+    fill_params(p, d, *find_prepack(wp, d, (pw * wp->cin) % 2), wp, x, y, bias, b, h, w, g, sh, sw, ph, pw,
+                dh, dw, relu, xdt == NM_F32 ? 4 : 2);
+    p.res = res;
     return launch_conv(v, xdt, ydt, p, (hipStream_t)stream);
+}
+
+int nm_conv2d(const void* x, nm_dtype_t xdt, int b, int h, int w, int cin, const nm_packed_t* wp,
+              const float* bias, int sh, int sw, int ph, int pw, int dh, int dw, int relu, void* y,
+              nm_dtype_t ydt, void* stream)
+{
+    return conv2d_impl(x, xdt, b, h, w, cin, wp, bias, nullptr, sh, sw, ph, pw, dh, dw, relu, y, ydt, stream);
+}
+
+int nm_conv2d_res(const void* x, nm_dtype_t xdt, int b, int h, int w, int cin, const nm_packed_t* wp,
+                  const float* bias, const void* res, int sh, int sw, int ph, int pw, int dh, int dw,
+                  int relu, void* y, nm_dtype_t ydt, void* stream)
+{
+    return conv2d_impl(x, xdt, b, h, w, cin, wp, bias, res, sh, sw, ph, pw, dh, dw, relu, y, ydt, stream);
+}
+
+int nm_maxpool2d(const void* x, nm_dtype_t dt, int b, int h, int w, int c, int k, int stride, int pad,
+                 void* y, void* stream)
+{
+    if (!x || !y || b < 1 || h < 1 || w < 1 || c < 1 || k < 1 || stride < 1 || pad < 0 || pad >= k ||
+        (dt != NM_F32 && dt != NM_BF16)) {
+        set_error("bad max-pooling arguments");
+        return NM_ERR_ARG;
+    }
+    if (h + 2 * pad < k || w + 2 * pad < k) {
+        set_error("output would be empty: input %dx%d, window %d, pad %d", h, w, k, pad);
+        return NM_ERR_SHAPE;
+    }
+    const int ho = (h + 2 * pad - k) / stride + 1, wo = (w + 2 * pad - k) / stride + 1;
+    if (((uintptr_t)x % 16) || ((uintptr_t)y % 16)) {
+        set_error("x and y must be 16-byte aligned");
+        return NM_ERR_ARG;
+    }
+    return run_maxpool(x, dt, b, h, w, c, k, stride, pad, ho, wo, y, (hipStream_t)stream);
+}
+
+int nm_avgpool_global(const void* x, nm_dtype_t dt, int b, int h, int w, int c, void* y, void* stream)
+{
+    if (!x || !y || b < 1 || h < 1 || w < 1 || c < 1 || (dt != NM_F32 && dt != NM_BF16)) {
+        set_error("bad average-pooling arguments");
+        return NM_ERR_ARG;
+    }
+    if (b > 65535) {
+        set_error("batch %d exceeds 65535", b);
+        return NM_ERR_ARG;
+    }
+    return run_avgpool(x, dt, b, h * w, c, y, (hipStream_t)stream);
 }
 
 int nm_autotune(nm_dtype_t xdt, int b, int h, int w, int cin, const nm_packed_t* wp, int has_bias,

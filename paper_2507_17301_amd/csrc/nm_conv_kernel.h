@@ -55,6 +55,33 @@ __device__ inline void store4(bf16_t* p, f4 v)
 }
 __device__ inline void store1(float* p, float v) { *p = v; }
 __device__ inline void store1(bf16_t* p, float v) { p->v = to_bf16_bits(v); }
+__device__ inline f4 load4(const float* p) { return *reinterpret_cast<const f4*>(p); }
+__device__ inline f4 load4(const bf16_t* p)
+{
+    const uint2 u = *reinterpret_cast<const uint2*>(p);
+    return f4{__uint_as_float(u.x << 16), __uint_as_float(u.x & 0xffff0000u),
+              __uint_as_float(u.y << 16), __uint_as_float(u.y & 0xffff0000u)};
+}
+__device__ inline float load1(const float* p) { return *p; }
+__device__ inline float load1(const bf16_t* p) { return __uint_as_float((unsigned)p->v << 16); }
+
+// Tail of every epilogue: optional residual (a tensor shaped like the output,
+// added before the activation), ReLU, cast, store.
+template <typename TOUT> __device__ inline void emit4(const ConvParams& p, TOUT* y, size_t off, f4 v)
+{
+    if (p.res) v = v + load4(reinterpret_cast<const TOUT*>(p.res) + off);
+    if (p.relu) {
+        v.x = fmaxf(v.x, 0.f); v.y = fmaxf(v.y, 0.f);
+        v.z = fmaxf(v.z, 0.f); v.w = fmaxf(v.w, 0.f);
+    }
+    store4(y + off, v);
+}
+template <typename TOUT> __device__ inline void emit1(const ConvParams& p, TOUT* y, size_t off, float v)
+{
+    if (p.res) v += load1(reinterpret_cast<const TOUT*>(p.res) + off);
+    if (p.relu) v = fmaxf(v, 0.f);
+    store1(y + off, v);
+}
 
 // Buffer loads: an offset at or beyond the descriptor's size returns zeros, which
 // is how padding, ragged pixel tiles and partial chunks are filled without a branch.
@@ -413,11 +440,7 @@ __global__ __launch_bounds__(256) void nm_conv_kernel(const ConvParams p)
                 const int pp = p0 + wpix + pixel_of(b);
                 if (pp >= p.P) continue;
                 f4 v = acc[jj][b] + bb;
-                if (p.relu) {
-                    v.x = fmaxf(v.x, 0.f); v.y = fmaxf(v.y, 0.f);
-                    v.z = fmaxf(v.z, 0.f); v.w = fmaxf(v.w, 0.f);
-                }
-                store4(y + (size_t)pp * p.Cout + co, v);
+                emit4(p, y, (size_t)pp * p.Cout + co, v);
             }
         } else {
 #pragma unroll
@@ -428,8 +451,7 @@ __global__ __launch_bounds__(256) void nm_conv_kernel(const ConvParams p)
                 for (int r = 0; r < 4; ++r) {
                     if (rit + r >= p.tile || co + r >= p.Cout) continue;
                     float v = acc[jj][b][r] + (p.bias ? p.bias[co + r] : 0.f);
-                    if (p.relu) v = fmaxf(v, 0.f);
-                    store1(y + (size_t)pp * p.Cout + co + r, v);
+                    emit1(p, y, (size_t)pp * p.Cout + co + r, v);
                 }
             }
         }

@@ -365,11 +365,7 @@ __global__ __launch_bounds__(256) void nm_conv_sp16_kernel(const ConvParams p)
                 const int pp = p0 + wpix + b * 16 + n;
                 if (pp >= p.P) continue;
                 f4 v = acc[jj][b] + bb[jj];
-                if (p.relu) {
-                    v.x = fmaxf(v.x, 0.f); v.y = fmaxf(v.y, 0.f);
-                    v.z = fmaxf(v.z, 0.f); v.w = fmaxf(v.w, 0.f);
-                }
-                store4(y + (size_t)pp * p.Cout + co, v);
+                emit4(p, y, (size_t)pp * p.Cout + co, v);
             }
         } else {
 #pragma unroll
@@ -380,8 +376,7 @@ __global__ __launch_bounds__(256) void nm_conv_sp16_kernel(const ConvParams p)
                 for (int r = 0; r < 4; ++r) {
                     if (rit + r >= p.tile || co + r >= p.Cout) continue;
                     float v = acc[jj][b][r] + (p.bias ? p.bias[co + r] : 0.f);
-                    if (p.relu) v = fmaxf(v, 0.f);
-                    store1(y + (size_t)pp * p.Cout + co + r, v);
+                    emit1(p, y, (size_t)pp * p.Cout + co + r, v);
                 }
             }
         }

@@ -120,6 +120,7 @@ struct ConvParams {
     const void* x;
     void* y;
     const float* bias;
+    const void* res;        // residual tensor shaped and typed like y, added before the activation, or null
     const float* wfrag;
     const uint32_t* rows;
     const uint32_t* ktab;   // scalar mode: [nchunks*CK] (kh | kw << 8 | ci << 16) of each im2col row
@@ -165,5 +166,10 @@ int run_prune(const float* d_w, nm_packed* wp, hipStream_t s);
 int run_build_prepack(nm_packed* wp, Prepack& pp, hipStream_t s);   // any kind
 int run_build_mask(const nm_packed* wp, uint8_t* d_mask, hipStream_t s);
 int run_fill_random(void* d, size_t n_elems, nm_dtype_t dt, uint32_t seed, hipStream_t s);
+
+// pooling kernels (nm_pool_kernels.hip)
+int run_maxpool(const void* x, nm_dtype_t dt, int B, int H, int W, int C, int k, int stride, int pad,
+                int Ho, int Wo, void* y, hipStream_t s);
+int run_avgpool(const void* x, nm_dtype_t dt, int B, int HW, int C, void* y, hipStream_t s);
 
 }  // namespace nm

@@ -1,0 +1,101 @@
+// The pooling layers between the convolutions of a ResNet: 3x3/2 max pooling
+// after the first layer and global average pooling before the classifier.
+// Both are plain HBM-bound passes over NHWC tensors: one thread handles 4
+// consecutive channels (8 or 16 bytes) of one output position, so that a
+// wavefront reads and writes contiguous runs.
+#include "nm_conv_kernel.h"
+
+namespace nm {
+namespace {
+
+template <typename T>
+__global__ __launch_bounds__(256) void maxpool_kernel(const T* __restrict__ x, T* __restrict__ y, int B,
+                                                      int H, int W, int C, int k, int stride, int pad,
+                                                      int Ho, int Wo)
+{
+    const int C4 = (C + 3) / 4;
+    const size_t total = (size_t)B * Ho * Wo * C4;
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < total;
+         i += (size_t)gridDim.x * blockDim.x) {
+        const int c4 = (int)(i % C4);
+        size_t r = i / C4;
+        const int wo = (int)(r % Wo); r /= Wo;
+        const int ho = (int)(r % Ho);
+        const int b = (int)(r / Ho);
+        const int c0 = c4 * 4;
+        const bool vec = (C % 4 == 0);
+        f4 m = {-INFINITY, -INFINITY, -INFINITY, -INFINITY};
+        for (int kh = 0; kh < k; ++kh) {
+            const int hi = ho * stride - pad + kh;
+            if ((unsigned)hi >= (unsigned)H) continue;
+            for (int kw = 0; kw < k; ++kw) {
+                const int wi = wo * stride - pad + kw;
+                if ((unsigned)wi >= (unsigned)W) continue;
+                const T* px = x + ((size_t)(b * H + hi) * W + wi) * C + c0;
+                if (vec) {
+                    const f4 v = load4(px);
+                    m.x = fmaxf(m.x, v.x); m.y = fmaxf(m.y, v.y);
+                    m.z = fmaxf(m.z, v.z); m.w = fmaxf(m.w, v.w);
+                } else {
+                    for (int e = 0; e < 4 && c0 + e < C; ++e) m[e] = fmaxf(m[e], load1(px + e));
+                }
+            }
+        }
+        T* py = y + ((size_t)(b * Ho + ho) * Wo + wo) * C + c0;
+        if (vec) {
+            store4(py, m);
+        } else {
+            for (int e = 0; e < 4 && c0 + e < C; ++e) store1(py + e, m[e]);
+        }
+    }
+}
+
+// one workgroup per (image, 64-channel slab): 4 wavefronts split the positions,
+// lanes run along the channels; fp32 partial sums meet in LDS
+template <typename T>
+__global__ __launch_bounds__(256) void avgpool_kernel(const T* __restrict__ x, T* __restrict__ y, int HW, int C)
+{
+    __shared__ float part[4][64];
+    const int b = blockIdx.y;
+    const int c = blockIdx.x * 64 + (threadIdx.x & 63);
+    const int wv = threadIdx.x >> 6;
+    float s = 0.f;
+    if (c < C)
+        for (int i = wv; i < HW; i += 4) s += load1(x + ((size_t)b * HW + i) * C + c);
+    part[wv][threadIdx.x & 63] = s;
+    __syncthreads();
+    if (wv == 0 && c < C) {
+        const float t = ((part[0][threadIdx.x] + part[1][threadIdx.x]) + part[2][threadIdx.x]) + part[3][threadIdx.x];
+        store1(y + (size_t)b * C + c, t / (float)HW);
+    }
+}
+
+}  // namespace
+
+int run_maxpool(const void* x, nm_dtype_t dt, int B, int H, int W, int C, int k, int stride, int pad,
+                int Ho, int Wo, void* y, hipStream_t s)
+{
+    const size_t total = (size_t)B * Ho * Wo * ((C + 3) / 4);
+    const unsigned grid = (unsigned)std::min<size_t>((total + 255) / 256, 1u << 20);
+    if (dt == NM_F32)
+        hipLaunchKernelGGL(maxpool_kernel<float>, dim3(grid), dim3(256), 0, s, (const float*)x, (float*)y, B, H,
+                           W, C, k, stride, pad, Ho, Wo);
+    else
+        hipLaunchKernelGGL(maxpool_kernel<bf16_t>, dim3(grid), dim3(256), 0, s, (const bf16_t*)x, (bf16_t*)y, B,
+                           H, W, C, k, stride, pad, Ho, Wo);
+    NM_HIP_CHECK(hipGetLastError());
+    return NM_OK;
+}
+
+int run_avgpool(const void* x, nm_dtype_t dt, int B, int HW, int C, void* y, hipStream_t s)
+{
+    const dim3 grid((C + 63) / 64, B);
+    if (dt == NM_F32)
+        hipLaunchKernelGGL(avgpool_kernel<float>, grid, dim3(256), 0, s, (const float*)x, (float*)y, HW, C);
+    else
+        hipLaunchKernelGGL(avgpool_kernel<bf16_t>, grid, dim3(256), 0, s, (const bf16_t*)x, (bf16_t*)y, HW, C);
+    NM_HIP_CHECK(hipGetLastError());
+    return NM_OK;
+}
+
+}  // namespace nm

@@ -163,6 +163,20 @@ def resnet101_stack(tile: int = 32) -> List[ConvLayer]:
     return _bottleneck_stack((3, 4, 23, 3), [(1, 4), (2, 4), (2, 8), (4, 8)], tile)
 
 
+def with_large_groups(layers: List[ConvLayer], mode: str, keep: float = 0.5) -> List[ConvLayer]:
+    """The paper's adaptive setting (section 3.1): one group spans all input channels of a
+    kernel tap (mode "cin": M = Cin) or the whole row of the weight matrix (mode "row":
+    M = K), and N = keep * M columns survive.  Dense layers (N = M) stay dense."""
+    out = []
+    for l in layers:
+        if l.n == l.m:
+            out.append(l)
+            continue
+        m = l.Cin if mode == "cin" else l.K
+        out.append(replace(l, n=max(1, int(round(keep * m))), m=m))
+    return out
+
+
 def unique_shapes(layers: List[ConvLayer]) -> List[ConvLayer]:
     seen, out = set(), []
     for l in layers:

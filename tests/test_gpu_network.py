@@ -1,0 +1,128 @@
+"""Residual convolution and pooling on the GPU against the CPU oracle, through the C ABI."""
+import numpy as np
+import pytest
+
+import oracle
+from paper_2507_17301_amd import binding as nm
+from paper_2507_17301_amd import workloads as wl
+from gpu_util import FP32_TOL, BF16_TOL, say, norm_err
+
+pytestmark = pytest.mark.gpu
+
+L = wl.ConvLayer
+
+
+def _residual_case(layer, batch, bf16, seed, forced_prefixes=None):
+    import torch
+    x, w, bias = wl.make_tensors(layer, batch, seed, weight_sigma=0.1)
+    _, _, wz = oracle.prune(w, layer.n, layer.m, layer.tile)
+    rng = np.random.default_rng(seed + 1)
+    shape = (batch, layer.Ho, layer.Wo, layer.Cout)
+    res = rng.standard_normal(shape).astype(np.float32)
+    xo, ro = x, res
+    if bf16:
+        wz, xo, ro = oracle.round_bf16(wz), oracle.round_bf16(x), oracle.round_bf16(res)
+    ref = oracle.conv2d_res(xo, wz, ro, bias, layer.stride, layer.pad, layer.dil, True, out_bf16=bf16)
+    tdt = torch.bfloat16 if bf16 else torch.float32
+    ndt = nm.NM_BF16 if bf16 else nm.NM_F32
+    wp = nm.nm_prune(w, layer.n, layer.m, layer.tile, ndt)
+    xd = torch.from_numpy(x).cuda().to(tdt)
+    rd = torch.from_numpy(res).cuda().to(tdt)
+    bd = torch.from_numpy(bias).cuda()
+    tol = BF16_TOL if bf16 else FP32_TOL
+    y = nm.nm_conv2d_res(xd, wp, rd, bd, layer.stride, layer.pad, layer.dil, True)
+    torch.cuda.synchronize()
+    assert norm_err(y.float().cpu().numpy(), ref) <= tol
+    # residual = None is plain nm_conv2d
+    y0 = nm.nm_conv2d_res(xd, wp, None, bd, layer.stride, layer.pad, layer.dil, True)
+    y1 = nm.nm_conv2d(xd, wp, bd, layer.stride, layer.pad, layer.dil, True)
+    torch.cuda.synchronize()
+    assert torch.equal(y0, y1)
+    if forced_prefixes:
+        seen = set()
+        try:
+            for v in range(nm.nm_variant_count()):
+                name = nm.nm_variant_name(v)
+                fam = name.split("_")[0]
+                if fam not in forced_prefixes or fam in seen or not nm.nm_variant_legal(v, wp, ndt, ndt):
+                    continue
+                say(f"residual, forced {name} on {layer.name}")
+                nm.nm_force_variant(v)
+                try:
+                    y = nm.nm_conv2d_res(xd, wp, rd, bd, layer.stride, layer.pad, layer.dil, True)
+                except nm.NMError:
+                    continue
+                torch.cuda.synchronize()
+                assert norm_err(y.float().cpu().numpy(), ref) <= tol, name
+                seen.add(fam)
+        finally:
+            nm.nm_force_variant(-1)
+        assert seen == set(forced_prefixes)
+
+
+def test_residual_fp32():
+    _residual_case(L("res_3x3", 13, 11, 32, 48, 3, 3, 1, 1, 1, 2, 4, 16), 2, False, 50, {"NB4", "NB8"})
+    _residual_case(L("res_1x1_cout37", 9, 9, 16, 37, 1, 1, 1, 0, 1, 2, 4, 5), 2, False, 51)   # element-wise tail
+
+
+def test_residual_bf16_every_kernel_family():
+    # 64 channels, 2:4: fp32-MFMA kernel on bf16 data, gather kernel, sparse instruction, dense instruction
+    _residual_case(L("res16_3x3", 12, 10, 64, 80, 3, 3, 1, 1, 1, 2, 4, 16), 3, True, 52, {"NB4", "B16", "SP1", "SP0"})
+    _residual_case(L("res16_stem", 20, 20, 3, 32, 7, 7, 2, 3, 1, 1, 1, 16), 2, True, 53, {"RUN"})
+    _residual_case(L("res16_cout37", 9, 9, 64, 37, 1, 1, 1, 0, 1, 2, 4, 16), 2, True, 54)
+
+
+def test_residual_argument_errors():
+    import torch
+    layer = L("res_err", 6, 6, 16, 16, 3, 3, 1, 1, 1, 2, 4, 16)
+    x, w, bias = wl.make_tensors(layer, 1, 3)
+    wp = nm.nm_prune(w, 2, 4, 16)
+    xd = torch.from_numpy(x).cuda()
+    y = torch.empty((1, 6, 6, 16), device="cuda")
+    with pytest.raises(ValueError):
+        nm.nm_conv2d_res(xd, wp, torch.empty((1, 6, 6, 8), device="cuda"))
+    with pytest.raises(nm.NMError) as e:                       # residual overlapping the output
+        nm.nm_conv2d_res(xd, wp, y, None, 1, 1, 1, True, y=y)
+    assert e.value.code == nm.NM_ERR_ARG
+
+
+@pytest.mark.parametrize("k,stride,pad,H,W,C", [(3, 2, 1, 112, 112, 64), (3, 2, 1, 11, 9, 5), (2, 2, 0, 8, 8, 4),
+                                                 (3, 1, 1, 7, 6, 3), (5, 3, 2, 13, 12, 66)])
+@pytest.mark.parametrize("bf16", [False, True])
+def test_maxpool(k, stride, pad, H, W, C, bf16):
+    import torch
+    rng = np.random.default_rng(H + C)
+    x = rng.standard_normal((2, H, W, C)).astype(np.float32)
+    if bf16:
+        x = oracle.round_bf16(x)
+    ref = oracle.maxpool2d(x, k, stride, pad)
+    xd = torch.from_numpy(x).cuda().to(torch.bfloat16 if bf16 else torch.float32)
+    y = nm.nm_maxpool2d(xd, k, stride, pad)
+    torch.cuda.synchronize()
+    assert np.array_equal(y.float().cpu().numpy(), ref)        # a selection: bit-exact
+
+
+@pytest.mark.parametrize("H,W,C,B", [(7, 7, 2048, 3), (1, 1, 5, 2), (5, 9, 100, 4)])
+@pytest.mark.parametrize("bf16", [False, True])
+def test_avgpool_global(H, W, C, B, bf16):
+    import torch
+    rng = np.random.default_rng(H * C)
+    x = (rng.standard_normal((B, H, W, C)) + 0.5).astype(np.float32)
+    if bf16:
+        x = oracle.round_bf16(x)
+    ref = oracle.avgpool_global(x, out_bf16=bf16)
+    xd = torch.from_numpy(x).cuda().to(torch.bfloat16 if bf16 else torch.float32)
+    y = nm.nm_avgpool_global(xd)
+    torch.cuda.synchronize()
+    assert norm_err(y.float().cpu().numpy(), ref) <= (BF16_TOL if bf16 else FP32_TOL)
+
+
+def test_pool_argument_errors():
+    import torch
+    x = torch.zeros((1, 4, 4, 4), device="cuda")
+    with pytest.raises(nm.NMError) as e:
+        nm.nm_maxpool2d(x, 3, 2, 3)
+    assert e.value.code == nm.NM_ERR_ARG
+    with pytest.raises(nm.NMError) as e:
+        nm.nm_maxpool2d(x, 7, 1, 1, y=torch.zeros((1, 1, 1, 4), device="cuda"))
+    assert e.value.code == nm.NM_ERR_SHAPE
