@@ -40,10 +40,13 @@ def main():
     ap.add_argument("--dtype", choices=["f32", "bf16"], default="f32")
     ap.add_argument("--batch", type=int, default=None, help="default: the workload's own batch")
     ap.add_argument("--workload", default="resnet50",
-                    choices=["resnet50", "resnet18", "resnet101", "sweep", "single"],
+                    choices=["resnet50", "resnet18", "resnet101", "sweep", "single",
+                             "resnet50_net", "resnet18_net", "resnet101_net"],
                     help="resnet50 (default, the headline: 53 layers 2:4 T16 batch 64) | resnet18 (batch 32) | "
                          "resnet101 (mixed sparsity, T32, batch 256, bf16) | sweep (15 N:M x T cells of one "
-                         "3x3 layer + its dense form, batch 32) | single (one 3x3 layer, batch 1)")
+                         "3x3 layer + its dense form, batch 32) | single (one 3x3 layer, batch 1) | *_net: the "
+                         "whole network on one input batch (residual adds fused into the closing convolution of "
+                         "each block, pooling, classifier), reported in images/s")
     ap.add_argument("--tile", type=int, default=None,
                     help="experiment: tile size T of the ResNet workloads (1 = conventional row-wise N:M)")
     ap.add_argument("--nm", default=None, help="experiment: N:M of the ResNet-18/50 workloads, e.g. 1:4")
@@ -76,6 +79,8 @@ def main():
 
     n_, m_ = (int(v) for v in args.nm.split(":")) if args.nm else (2, 4)
     t_ = args.tile or 16
+    if args.workload.endswith("_net"):
+        return whole_network(args, n_, m_, t_)
     if args.workload == "resnet50":
         layers, B, seed0 = wl.resnet50_stack(n_, m_, t_), 64, 4000
         wname = f"resnet50_conv_stack_53layers_{n_}of{m_}_T{t_}"
@@ -268,6 +273,98 @@ def main():
     if args.report:
         with open(args.report, "w") as f:
             json.dump({"summary": out, "layers": per_layer}, f, indent=1)
+    print(json.dumps(out), flush=True)
+
+
+def whole_network(args, n_, m_, t_):
+    """One input batch through the whole network; a step is one forward pass."""
+    import torch
+    from paper_2507_17301_amd import binding as nm
+    from paper_2507_17301_amd import workloads as wl
+    from paper_2507_17301_amd.network import Network
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible; the library has no CPU fallback", file=sys.stderr)
+        sys.exit(3)
+    torch.cuda.set_device(0)
+    name = args.workload[:-4]
+    if name == "resnet50":
+        ops, B, seed0 = wl.resnet50_graph(n_, m_, t_), 64, 4000
+    elif name == "resnet18":
+        ops, B, seed0 = wl.resnet18_graph(n_, m_, t_), 32, 3000
+    else:
+        ops, B, seed0 = wl.resnet101_graph(args.tile or 32), 256, 5000
+        if "--dtype" not in sys.argv:
+            args.dtype = "bf16"
+    if args.batch is not None:
+        B = args.batch
+    bf16 = args.dtype == "bf16"
+    esize = 2 if bf16 else 4
+    t0 = time.time()
+    net = Network(ops, B, 224, nm.NM_BF16 if bf16 else nm.NM_F32, seed0)
+    t1 = time.time()
+    if not args.no_tune:
+        net.autotune()
+    torch.cuda.synchronize()
+    t2 = time.time()
+    gen = torch.Generator(device=net.dev)
+    gen.manual_seed(1234)
+    net.t[0].copy_(torch.rand(net.shapes[0], generator=gen, device=net.dev, dtype=torch.float32))
+    log(f"set-up: prune+pack {t1 - t0:.2f}s, tune {t2 - t1:.2f}s, {len(ops)} operators")
+
+    stream = torch.cuda.current_stream()
+    net.forward(stream=stream)
+    torch.cuda.synchronize()
+    graph = None
+    if not args.no_graph:
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            net.forward(stream=torch.cuda.current_stream())
+    run_step = graph.replay if graph is not None else (lambda: net.forward(stream=stream))
+    for _ in range(args.warmup):
+        run_step()
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record(stream)
+    for _ in range(args.steps):
+        run_step()
+    e1.record(stream)
+    torch.cuda.synchronize()
+    ms_step = e0.elapsed_time(e1) / args.steps
+
+    convs = [op.layer for op in ops if op.kind == "conv"]
+    dense = sum(l.dense_flops(B) for l in convs)
+    eff = sum(l.effective_flops(B) for l in convs)
+    # every tensor written once and read by its consumers, plus the packed weights
+    byts = sum(l.algorithmic_bytes(B, esize, esize) for l in convs)
+    for op in ops:
+        if op.residual >= 0:
+            byts += int(torch.tensor(net.shapes[op.residual]).prod()) * esize
+        if op.kind != "conv":
+            byts += (int(torch.tensor(net.shapes[op.src]).prod()) + int(torch.tensor(net.shapes[op.dst]).prod())) * esize
+    if bf16:
+        roofline = {"bound": "hbm", "achieved": byts / ms_step / 1e6, "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                    "frac": byts / ms_step / 1e6 / PEAK_HBM_GBS, "traffic": None}
+    else:
+        roofline = {"bound": "mfma", "achieved": eff / ms_step / 1e9, "peak": PEAK_TFLOPS["f32"],
+                    "unit": "TFLOP/s", "frac": eff / ms_step / 1e9 / PEAK_TFLOPS["f32"], "traffic": None}
+    roofline["note"] = "whole step (all operators) against the convolutions' flops / all tensors' bytes"
+    cpu = None
+    if not args.no_cpu_baseline:
+        cpu = cpu_baseline([l for l in convs], B, bf16, seed0)
+        cpu["sample"] += "; convolutions only"
+    out = {
+        "metric": f"images/s, {name} whole network @batch {B}", "value": B / ms_step * 1e3, "unit": "images/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_step,
+        "ms_per_img": ms_step / B, "dense_equiv_gflops": dense / ms_step / 1e6,
+        "effective_gflops": eff / ms_step / 1e6, "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": args.dtype, "data": "synthetic",
+        "config": {"workload": f"{name}_whole_network_batch{B}_{args.dtype}", "batch": B,
+                   "operators": len(ops), "tuned": not args.no_tune,
+                   "launch": "hip_graph_replay" if graph is not None else "one_launch_per_operator"},
+        "setup": {"prune_pack_s": t1 - t0, "autotune_s": t2 - t1},
+        "roofline": roofline, "cpu_baseline": cpu,
+    }
     print(json.dumps(out), flush=True)
 
 

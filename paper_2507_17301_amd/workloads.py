@@ -177,6 +177,120 @@ def with_large_groups(layers: List[ConvLayer], mode: str, keep: float = 0.5) -> 
     return out
 
 
+# --------------------------------------------------------------------------
+# whole networks: which tensor feeds which operator (structure only)
+# --------------------------------------------------------------------------
+
+@dataclass(frozen=True)
+class NetOp:
+    """One operator of a network.  Tensors are named by small integers; tensor 0 is
+    the network input.  kind: "conv" (layer, relu, optional residual tensor added
+    before the activation), "maxpool" (k, stride, pad), "avgpool" (global)."""
+    kind: str
+    src: int
+    dst: int
+    layer: Optional[ConvLayer] = None
+    relu: bool = False
+    residual: int = -1
+    k: int = 0
+    stride: int = 0
+    pad: int = 0
+
+
+def resnet_graph(blocks: Tuple[int, ...], widths: Tuple[int, ...], bottleneck: bool, in_hw: int,
+                 per_stage_nm, tile: int, stem_width: int = 64, num_classes: int = 1000) -> List[NetOp]:
+    """A Torchvision-form ResNet with batch norm folded into the convolutions' biases:
+    7x7/2 stem (dense), 3x3/2 max pooling, residual stages (the skip connection is
+    the `residual` of the block's last convolution), global average pooling and the
+    classifier as a dense 1x1 convolution on the pooled 1x1 map."""
+    ops: List[NetOp] = []
+    nxt = [1]
+
+    def new():
+        nxt[0] += 1
+        return nxt[0] - 1
+
+    n0, m0 = per_stage_nm[0]
+    stem = _dense(ConvLayer("stem_7x7", in_hw, in_hw, 3, stem_width, 7, 7, 2, 3, 1, n0, m0, tile, 0))
+    t = new()
+    ops.append(NetOp("conv", 0, t, stem, relu=True))
+    res = stem.Ho
+    t2 = new()
+    ops.append(NetOp("maxpool", t, t2, k=3, stride=2, pad=1))
+    res = (res + 2 - 3) // 2 + 1
+    cur, cin = t2, stem_width
+    exp = 4 if bottleneck else 1
+    for stage, (width, nblk) in enumerate(zip(widths, blocks), start=1):
+        n, m = per_stage_nm[stage - 1]
+        for block in range(nblk):
+            s = 2 if (stage > 1 and block == 0) else 1
+            pre = f"s{stage}b{block}"
+            res_out = res // s
+            ident = cur
+            if s == 2 or cin != width * exp:
+                ident = new()
+                ops.append(NetOp("conv", cur, ident, ConvLayer(pre + "_proj_1x1", res, res, cin, width * exp,
+                                                               1, 1, s, 0, 1, n, m, tile, stage)))
+            if bottleneck:
+                a, b_, c = new(), new(), new()
+                ops.append(NetOp("conv", cur, a, ConvLayer(pre + "_conv1_1x1", res, res, cin, width, 1, 1, 1, 0, 1,
+                                                           n, m, tile, stage), relu=True))
+                ops.append(NetOp("conv", a, b_, ConvLayer(pre + "_conv2_3x3", res, res, width, width, 3, 3, s, 1, 1,
+                                                          n, m, tile, stage), relu=True))
+                ops.append(NetOp("conv", b_, c, ConvLayer(pre + "_conv3_1x1", res_out, res_out, width, width * 4,
+                                                          1, 1, 1, 0, 1, n, m, tile, stage),
+                                 relu=True, residual=ident))
+            else:
+                a, c = new(), new()
+                ops.append(NetOp("conv", cur, a, ConvLayer(pre + "_conv1_3x3", res, res, cin, width, 3, 3, s, 1, 1,
+                                                           n, m, tile, stage), relu=True))
+                ops.append(NetOp("conv", a, c, ConvLayer(pre + "_conv2_3x3", res_out, res_out, width, width,
+                                                         3, 3, 1, 1, 1, n, m, tile, stage),
+                                 relu=True, residual=ident))
+            cur, cin, res = c, width * exp, res_out
+    t = new()
+    ops.append(NetOp("avgpool", cur, t))
+    t2 = new()
+    ops.append(NetOp("conv", t, t2, _dense(ConvLayer("fc", 1, 1, cin, num_classes, 1, 1, 1, 0, 1, 1, 1, tile, 5))))
+    return ops
+
+
+def net_parameters(ops: List[NetOp], seed0: int):
+    """Seeded weights and biases of a network's convolutions, in operator order:
+    yields (operator index, w [Cout,Kh,Kw,Cin] fp32, bias [Cout] fp32)."""
+    for i, op in enumerate(ops):
+        if op.kind == "conv":
+            _, w, bias = make_tensors(op.layer, 1, seed0 + i, with_input=False)
+            yield i, w, bias
+
+
+def net_tensor_shapes(ops: List[NetOp], batch: int, in_hw: int) -> dict:
+    """Shape of every tensor of the network (NHWC; the pooled map is [B,1,1,C])."""
+    shapes = {0: (batch, in_hw, in_hw, 3)}
+    for op in ops:
+        b, h, w, c = shapes[op.src]
+        if op.kind == "conv":
+            l = op.layer
+            shapes[op.dst] = (b, l.Ho, l.Wo, l.Cout)
+        elif op.kind == "maxpool":
+            shapes[op.dst] = (b, (h + 2 * op.pad - op.k) // op.stride + 1, (w + 2 * op.pad - op.k) // op.stride + 1, c)
+        else:
+            shapes[op.dst] = (b, 1, 1, c)
+    return shapes
+
+
+def resnet50_graph(n: int = 2, m: int = 4, tile: int = 16) -> List[NetOp]:
+    return resnet_graph((3, 4, 6, 3), (64, 128, 256, 512), True, 224, [(n, m)] * 4, tile)
+
+
+def resnet18_graph(n: int = 2, m: int = 4, tile: int = 16) -> List[NetOp]:
+    return resnet_graph((2, 2, 2, 2), (64, 128, 256, 512), False, 224, [(n, m)] * 4, tile)
+
+
+def resnet101_graph(tile: int = 32) -> List[NetOp]:
+    return resnet_graph((3, 4, 23, 3), (64, 128, 256, 512), True, 224, [(1, 4), (2, 4), (2, 8), (4, 8)], tile)
+
+
 def unique_shapes(layers: List[ConvLayer]) -> List[ConvLayer]:
     seen, out = set(), []
     for l in layers:

@@ -33,3 +33,29 @@ def test_generators_are_seeded_and_shaped():
     assert x.min() >= 0 and x.max() < 1 and abs(w.std() - 0.05) < 0.002
     pts = wl.sample_points(l, 1, 10, 0)
     assert pts.shape == (26, 4) and pts[:, 3].max() < 64
+
+
+def test_network_graphs_are_consistent_with_the_layer_tables():
+    """The whole-network graphs hold the same convolutions as the layer stacks (plus the
+    classifier), every residual tensor is shaped like the output it is added to, and every
+    operator reads a tensor that an earlier operator (or the input) produced."""
+    from paper_2507_17301_amd import workloads as wl
+    for graph, stack, batch in ((wl.resnet50_graph(), wl.resnet50_stack(), 2), (wl.resnet18_graph(), wl.resnet18_stack(), 2),
+                                (wl.resnet101_graph(), wl.resnet101_stack(), 1)):
+        convs = [op.layer for op in graph if op.kind == "conv"]
+        key = lambda l: (l.H, l.W, l.Cin, l.Cout, l.Kh, l.Kw, l.stride, l.pad, l.n, l.m, l.tile)
+        assert sorted(map(key, convs[:-1])) == sorted(map(key, stack))
+        assert convs[-1].name == "fc" and convs[-1].n == convs[-1].m
+        shapes = wl.net_tensor_shapes(graph, batch, 224)
+        made = {0}
+        for op in graph:
+            assert op.src in made and op.dst not in made
+            if op.kind == "conv":
+                assert shapes[op.src] == (batch, op.layer.H, op.layer.W, op.layer.Cin)
+                if op.residual >= 0:
+                    assert op.residual in made and shapes[op.residual] == shapes[op.dst]
+            made.add(op.dst)
+        assert shapes[graph[-1].dst] == (batch, 1, 1, 1000)
+        assert sum(op.residual >= 0 for op in graph) == sum(1 for op in graph if op.kind == "conv" and "conv1" in op.layer.name)
+    ids = [i for i, w, b in wl.net_parameters(wl.resnet18_graph(), 7)]
+    assert len(ids) == 21
