@@ -41,12 +41,14 @@ def main():
     ap.add_argument("--batch", type=int, default=None, help="default: the workload's own batch")
     ap.add_argument("--workload", default="resnet50",
                     choices=["resnet50", "resnet18", "resnet101", "sweep", "single",
-                             "resnet50_net", "resnet18_net", "resnet101_net"],
+                             "resnet50_net", "resnet18_net", "resnet101_net", "fusion"],
                     help="resnet50 (default, the headline: 53 layers 2:4 T16 batch 64) | resnet18 (batch 32) | "
                          "resnet101 (mixed sparsity, T32, batch 256, bf16) | sweep (15 N:M x T cells of one "
                          "3x3 layer + its dense form, batch 32) | single (one 3x3 layer, batch 1) | *_net: the "
                          "whole network on one input batch (residual adds fused into the closing convolution of "
-                         "each block, pooling, classifier), reported in images/s")
+                         "each block, pooling, classifier), reported in images/s | fusion: the k x k layers of "
+                         "ResNet-50 fused (nm_conv2d) against unfused (nm_im2col to memory, then the same "
+                         "contraction as a 1x1 convolution over it), the comparison of the paper's section 4.3")
     ap.add_argument("--tile", type=int, default=None,
                     help="experiment: tile size T of the ResNet workloads (1 = conventional row-wise N:M)")
     ap.add_argument("--nm", default=None, help="experiment: N:M of the ResNet-18/50 workloads, e.g. 1:4")
@@ -81,6 +83,8 @@ def main():
     t_ = args.tile or 16
     if args.workload.endswith("_net"):
         return whole_network(args, n_, m_, t_)
+    if args.workload == "fusion":
+        return fusion_ablation(args, n_, m_, t_)
     if args.workload == "resnet50":
         layers, B, seed0 = wl.resnet50_stack(n_, m_, t_), 64, 4000
         wname = f"resnet50_conv_stack_53layers_{n_}of{m_}_T{t_}"
@@ -365,6 +369,84 @@ def whole_network(args, n_, m_, t_):
         "setup": {"prune_pack_s": t1 - t0, "autotune_s": t2 - t1},
         "roofline": roofline, "cpu_baseline": cpu,
     }
+    print(json.dumps(out), flush=True)
+
+
+def fusion_ablation(args, n_, m_, t_):
+    """Fused im2col + contraction against the unfused pipeline, on the k x k layers of ResNet-50."""
+    import numpy as np
+    import torch
+    from paper_2507_17301_amd import binding as nm
+    from paper_2507_17301_amd import workloads as wl
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible; the library has no CPU fallback", file=sys.stderr)
+        sys.exit(3)
+    torch.cuda.set_device(0)
+    dev = torch.device("cuda:0")
+    B = args.batch or 64
+    bf16 = args.dtype == "bf16"
+    tdt = torch.bfloat16 if bf16 else torch.float32
+    ndt = nm.NM_BF16 if bf16 else nm.NM_F32
+    esize = 2 if bf16 else 4
+    layers = [l for l in wl.unique_shapes(wl.resnet50_stack(n_, m_, t_)) if l.Kh * l.Kw > 1]
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(1234)
+    items = []
+    for i, l in enumerate(layers):
+        _, w, bias = wl.make_tensors(l, B, 4000 + i, with_input=False)
+        wp = nm.nm_prune(w, l.n, l.m, l.tile, ndt)
+        wp1 = nm.nm_prune(np.ascontiguousarray(w.reshape(l.Cout, 1, 1, -1)), l.n, l.m, l.tile, ndt)
+        x = torch.rand((B, l.H, l.W, l.Cin), generator=gen, device=dev, dtype=torch.float32).to(tdt)
+        a = torch.empty((B, l.Ho, l.Wo, l.K), device=dev, dtype=tdt)
+        y = torch.empty((B, l.Ho, l.Wo, l.Cout), device=dev, dtype=tdt)
+        bd = torch.from_numpy(bias).to(dev)
+        if not args.no_tune:
+            nm.nm_autotune(ndt, B, l.H, l.W, l.Cin, wp, True, l.stride, l.pad, l.dil, True)
+            nm.nm_autotune(ndt, B, l.Ho, l.Wo, l.K, wp1, True, 1, 0, 1, True)
+        items.append((l, wp, wp1, x, a, y, bd))
+    stream = torch.cuda.current_stream()
+    reps = max(3, args.steps)
+    ev = lambda: torch.cuda.Event(enable_timing=True)
+    t_f, t_i, t_c = [[] for _ in items], [[] for _ in items], [[] for _ in items]
+    for r in range(args.warmup + reps):
+        for k, (l, wp, wp1, x, a, y, bd) in enumerate(items):     # all layers in turn: no layer finds its data cached
+            e = [ev() for _ in range(4)]
+            e[0].record(stream)
+            nm.nm_conv2d(x, wp, bd, l.stride, l.pad, l.dil, True, y=y, stream=stream)
+            e[1].record(stream)
+            nm.nm_im2col(x, l.Kh, l.Kw, l.stride, l.pad, l.dil, a=a, stream=stream)
+            e[2].record(stream)
+            nm.nm_conv2d(a, wp1, bd, 1, 0, 1, True, y=y, stream=stream)
+            e[3].record(stream)
+            torch.cuda.synchronize()
+            if r >= args.warmup:
+                t_f[k].append(e[0].elapsed_time(e[1]))
+                t_i[k].append(e[1].elapsed_time(e[2]))
+                t_c[k].append(e[2].elapsed_time(e[3]))
+    med = lambda v: sorted(v)[len(v) // 2]
+    rows, sf, su = [], 0.0, 0.0
+    for k, (l, *_rest) in enumerate(items):
+        f, i2c, c1 = med(t_f[k]), med(t_i[k]), med(t_c[k])
+        abytes = l.P(B) * l.K * esize
+        rows.append({"layer": l.name, "fused_ms": f, "im2col_ms": i2c, "conv_over_im2col_ms": c1,
+                     "speedup": (i2c + c1) / f, "im2col_matrix_mb": abytes / 1e6,
+                     "fused_algorithmic_mb": l.algorithmic_bytes(B, esize, esize) / 1e6})
+        sf += f
+        su += i2c + c1
+        log(f"{l.name:>18s}  fused {f * 1e3:7.1f} us | im2col {i2c * 1e3:7.1f} us + contraction {c1 * 1e3:7.1f} us "
+            f"= x{(i2c + c1) / f:.2f} | im2col matrix {abytes / 1e6:7.1f} MB written and read back, "
+            f"fused moves {l.algorithmic_bytes(B, esize, esize) / 1e6:6.1f} MB")
+    out = {"metric": f"fused-over-unfused speedup, k x k layers of ResNet-50 {n_}:{m_} T{t_} @batch {B}",
+           "value": su / sf, "unit": "x", "n_gpus": 1, "steps": reps, "warmup": args.warmup,
+           "ms_per_step": sf, "unfused_ms_per_step": su, "higher_is_better": True, "scaling": "weak",
+           "vs_baseline": None, "dtype": args.dtype, "data": "synthetic",
+           "config": {"workload": f"resnet50_kxk_layers_fused_vs_unfused_batch{B}_{args.dtype}", "batch": B,
+                      "layers": len(items)},
+           "roofline": None, "cpu_baseline": None, "layers": rows}
+    if args.report:
+        with open(args.report, "w") as f:
+            json.dump(out, f, indent=1)
     print(json.dumps(out), flush=True)
 
 

@@ -159,6 +159,22 @@ int nm_avgpool_global(const void* x_dev, nm_dtype_t dtype, int b, int h, int w, 
                       void* y_dev, void* hip_stream);
 
 /*
+ * nm_im2col -- the im2col matrix of section 2.2 written out to memory, for the
+ * unfused comparison of section 4.3 (im2col and packing as separate passes
+ * against the fused kernel).  nm_conv2d never calls it.
+ *   a_dev[p][k] = x[b][ho*stride_h - pad_h + kh*dil_h][wo*stride_w - pad_w + kw*dil_w][ci]
+ *                 or 0 outside the image,  p = (b*Hout + ho)*Wout + wo,
+ *                 k = (kh*kw_ + kw)*cin + ci   (the k order nm_prune uses)
+ * so a_dev is the NHWC tensor [b][hout][wout][kh*kw*cin] on which a 1x1
+ * convolution with the same weights, read as [cout][1][1][kh*kw*cin], gives
+ * the same result.  Same dtype in and out; enqueue-only.
+ * Errors: NM_ERR_ARG, NM_ERR_SHAPE, NM_ERR_HIP.
+ */
+int nm_im2col(const void* x_dev, nm_dtype_t dtype, int b, int h, int w, int cin, int kh, int kw,
+              int stride_h, int stride_w, int pad_h, int pad_w, int dil_h, int dil_w,
+              void* a_dev, void* hip_stream);
+
+/*
  * nm_autotune -- per-layer choice of the fastest kernel variant (section 3.3:
  * every candidate is run on the target and the fastest kept).  Runs each legal
  * variant for this shape on library-allocated scratch tensors (pseudo-random

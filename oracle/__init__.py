@@ -56,6 +56,8 @@ def _load():
         L.oracle_maxpool2d.restype = ci
         L.oracle_avgpool_global.argtypes = [fp, ci, ci, ci, ci, ci, fp]
         L.oracle_avgpool_global.restype = ci
+        L.oracle_im2col.argtypes = [fp] + [ci] * 12 + [fp]
+        L.oracle_im2col.restype = ci
         L.oracle_out_size.argtypes = [ci] * 10 + [ctypes.POINTER(ci), ctypes.POINTER(ci)]
         L.oracle_out_size.restype = ci
         _lib = L
@@ -212,6 +214,23 @@ def avgpool_global(x, out_bf16=False):
     if rc != 0:
         raise ValueError("oracle_avgpool_global rejected its arguments")
     return y
+
+
+def im2col(x, kh, kw, stride=1, pad=0, dil=1):
+    """The im2col matrix as [B,Ho,Wo,kh*kw*Cin], k order (kh, kw, ci), zero outside the image."""
+    x = np.ascontiguousarray(x, dtype=np.float32)
+    B, H, W, C = x.shape
+    sh, sw = _pair(stride)
+    ph, pw = _pair(pad)
+    dh, dw = _pair(dil)
+    Ho, Wo = out_size(H, W, kh, kw, (sh, sw), (ph, pw), (dh, dw))
+    a = np.empty((B, Ho, Wo, kh * kw * C), dtype=np.float32)
+    fp = ctypes.POINTER(ctypes.c_float)
+    rc = _load().oracle_im2col(x.ctypes.data_as(fp), B, H, W, C, int(kh), int(kw), sh, sw, ph, pw, dh, dw,
+                               a.ctypes.data_as(fp))
+    if rc != 0:
+        raise ValueError("oracle_im2col rejected its arguments")
+    return a
 
 
 def conv2d_points(x, w, pts, bias=None, stride=1, pad=0, dil=1, relu=False,

@@ -341,6 +341,35 @@ int oracle_avgpool_global(const float* x, int B, int H, int W, int C, int out_bf
 }
 
 /*
+ * The im2col matrix of section 2.2 written out: a[p][k], p = (b*Ho + ho)*Wo + wo,
+ * k = (kh*Kw + kw)*Cin + ci, zero outside the image.
+ */
+int oracle_im2col(const float* x, int B, int H, int W, int Cin, int Kh, int Kw,
+                  int sh, int sw, int ph, int pw, int dh, int dw, float* a)
+{
+    if (!x || !a || B < 1 || H < 1 || W < 1 || Cin < 1 || Kh < 1 || Kw < 1) return ORACLE_ERR_ARG;
+    if (sh < 1 || sw < 1 || ph < 0 || pw < 0 || dh < 1 || dw < 1) return ORACLE_ERR_ARG;
+    const int eh = H + 2 * ph - dh * (Kh - 1) - 1, ew = W + 2 * pw - dw * (Kw - 1) - 1;
+    if (eh < 0 || ew < 0) return ORACLE_ERR_ARG;
+    const int Ho = eh / sh + 1, Wo = ew / sw + 1;
+    const long K = (long)Kh * Kw * Cin;
+    for (int b = 0; b < B; ++b)
+        for (int ho = 0; ho < Ho; ++ho)
+            for (int wo = 0; wo < Wo; ++wo) {
+                float* row = a + (((long)b * Ho + ho) * Wo + wo) * K;
+                for (int kh = 0; kh < Kh; ++kh)
+                    for (int kw = 0; kw < Kw; ++kw) {
+                        const int hi = ho * sh - ph + kh * dh, wi = wo * sw - pw + kw * dw;
+                        const int in = hi >= 0 && hi < H && wi >= 0 && wi < W;
+                        for (int ci = 0; ci < Cin; ++ci)
+                            row[((long)kh * Kw + kw) * Cin + ci] =
+                                in ? x[(((long)b * H + hi) * W + wi) * Cin + ci] : 0.f;
+                    }
+            }
+    return ORACLE_OK;
+}
+
+/*
  * The same definition evaluated only at npts listed output positions
  * pts[i] = {b, ho, wo, co}; out[i] receives y[b][ho][wo][co].  Used to check
  * full-size layers whose whole output would take the CPU too long.

@@ -55,6 +55,7 @@ def lib():
         L.nm_conv2d_res.argtypes = [vp, ci, ci, ci, ci, ci, vp, vp, vp, ci, ci, ci, ci, ci, ci, ci, vp, ci, vp]
         L.nm_maxpool2d.argtypes = [vp, ci, ci, ci, ci, ci, ci, ci, ci, vp, vp]
         L.nm_avgpool_global.argtypes = [vp, ci, ci, ci, ci, ci, vp, vp]
+        L.nm_im2col.argtypes = [vp] + [ci] * 13 + [vp, vp]
         L.nm_autotune.argtypes = [ci, ci, ci, ci, ci, vp, ci, ci, ci, ci, ci, ci, ci, ci, ci, vp,
                                   pi, ctypes.POINTER(cf)]
         L.nm_cache_save.argtypes = [ctypes.c_char_p]
@@ -63,7 +64,7 @@ def lib():
         L.nm_variant_legal.argtypes = [ci, vp, ci, ci]
         for name in ("nm_prune", "nm_packed_free", "nm_packed_dims", "nm_packed_indices",
                      "nm_packed_values", "nm_packed_mask", "nm_conv2d", "nm_conv2d_res", "nm_maxpool2d",
-                     "nm_avgpool_global", "nm_autotune",
+                     "nm_avgpool_global", "nm_im2col", "nm_autotune",
                      "nm_cache_save", "nm_cache_load", "nm_cache_clear", "nm_cache_size",
                      "nm_force_variant", "nm_variant_legal"):
             getattr(L, name).restype = ci
@@ -256,6 +257,27 @@ def nm_avgpool_global(x, y=None, stream=None):
     _check(lib().nm_avgpool_global(x.data_ptr(), _dtype_code(x), b, h, w, c, y.data_ptr(),
                                    _stream_ptr(stream)))
     return y
+
+
+def nm_im2col(x, kh: int, kw: int, stride=1, pad=0, dil=1, a=None, stream=None):
+    """The im2col matrix of a contiguous NHWC device tensor, as the NHWC tensor
+    [B,Hout,Wout,kh*kw*Cin] (k order (kh, kw, ci))."""
+    import torch
+    if not x.is_cuda or not x.is_contiguous():
+        raise ValueError("x must be a contiguous device tensor")
+    b, h, w, c = x.shape
+    sh, sw = _pair(stride)
+    ph, pw = _pair(pad)
+    dh, dw = _pair(dil)
+    ho = (h + 2 * ph - dh * (kh - 1) - 1) // sh + 1
+    wo = (w + 2 * pw - dw * (kw - 1) - 1) // sw + 1
+    if a is None:
+        if min(ho, wo) < 1:
+            raise NMError(-2, "output would be empty")
+        a = torch.empty((b, ho, wo, kh * kw * c), dtype=x.dtype, device=x.device)
+    _check(lib().nm_im2col(x.data_ptr(), _dtype_code(x), b, h, w, c, kh, kw, sh, sw, ph, pw, dh, dw,
+                           a.data_ptr(), _stream_ptr(stream)))
+    return a
 
 
 def nm_autotune(x_dtype: int, b: int, h: int, w: int, cin: int, wp: Packed, has_bias=True,

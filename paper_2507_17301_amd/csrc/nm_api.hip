@@ -650,6 +650,31 @@ int nm_maxpool2d(const void* x, nm_dtype_t dt, int b, int h, int w, int c, int k
     return run_maxpool(x, dt, b, h, w, c, k, stride, pad, ho, wo, y, (hipStream_t)stream);
 }
 
+int nm_im2col(const void* x, nm_dtype_t dt, int b, int h, int w, int cin, int kh, int kw, int sh, int sw,
+              int ph, int pw, int dh, int dw, void* a_out, void* stream)
+{
+    if (!x || !a_out || b < 1 || h < 1 || w < 1 || cin < 1 || kh < 1 || kw < 1 || sh < 1 || sw < 1 || ph < 0 ||
+        pw < 0 || dh < 1 || dw < 1 || (dt != NM_F32 && dt != NM_BF16)) {
+        set_error("bad im2col arguments");
+        return NM_ERR_ARG;
+    }
+    if (((uintptr_t)x % 16) || ((uintptr_t)a_out % 16)) {
+        set_error("x and a must be 16-byte aligned");
+        return NM_ERR_ARG;
+    }
+    const long eh = (long)h + 2L * ph - (long)dh * (kh - 1) - 1, ew = (long)w + 2L * pw - (long)dw * (kw - 1) - 1;
+    if (eh < 0 || ew < 0) {
+        set_error("output would be empty");
+        return NM_ERR_SHAPE;
+    }
+    const int ho = (int)(eh / sh) + 1, wo = (int)(ew / sw) + 1;
+    if ((long long)b * ho * wo * kh * kw * cin > 0x7fffffffLL * 4) {
+        set_error("im2col matrix too large");
+        return NM_ERR_SHAPE;
+    }
+    return run_im2col(x, dt, b, h, w, cin, kh, kw, sh, sw, ph, pw, dh, dw, ho, wo, a_out, (hipStream_t)stream);
+}
+
 int nm_avgpool_global(const void* x, nm_dtype_t dt, int b, int h, int w, int c, void* y, void* stream)
 {
     if (!x || !y || b < 1 || h < 1 || w < 1 || c < 1 || (dt != NM_F32 && dt != NM_BF16)) {

@@ -70,7 +70,56 @@ __global__ __launch_bounds__(256) void avgpool_kernel(const T* __restrict__ x, T
     }
 }
 
+// im2col written out: one thread per (pixel, run of V channels of one tap), V elements = 16 bytes
+// when the channel count allows, else one element
+template <typename T, int V>
+__global__ __launch_bounds__(256) void im2col_kernel(const T* __restrict__ x, T* __restrict__ a, int B, int H,
+                                                     int W, int C, int Kh, int Kw, int sh, int sw, int ph, int pw,
+                                                     int dh, int dw, int Ho, int Wo)
+{
+    const int CV = C / V;
+    const size_t total = (size_t)B * Ho * Wo * Kh * Kw * CV;
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < total;
+         i += (size_t)gridDim.x * blockDim.x) {
+        const int cv = (int)(i % CV);
+        size_t r = i / CV;
+        const int kw_ = (int)(r % Kw); r /= Kw;
+        const int kh_ = (int)(r % Kh); r /= Kh;
+        const int wo = (int)(r % Wo); r /= Wo;
+        const int ho = (int)(r % Ho);
+        const int b = (int)(r / Ho);
+        const int hi = ho * sh - ph + kh_ * dh, wi = wo * sw - pw + kw_ * dw;
+        const bool in = ((unsigned)hi < (unsigned)H) & ((unsigned)wi < (unsigned)W);
+        T* dst = a + i * V;     // (pixel, tap, channel run) is exactly the order of a[p][k]
+        if constexpr (V == 1) {
+            T z; if constexpr (sizeof(T) == 4) z = 0; else z.v = 0;
+            dst[0] = in ? x[((size_t)(b * H + hi) * W + wi) * C + cv] : z;
+        } else {
+            u4v v = {0u, 0u, 0u, 0u};
+            if (in) v = *reinterpret_cast<const u4v*>(x + ((size_t)(b * H + hi) * W + wi) * C + cv * V);
+            *reinterpret_cast<u4v*>(dst) = v;
+        }
+    }
+}
+
 }  // namespace
+
+int run_im2col(const void* x, nm_dtype_t dt, int B, int H, int W, int C, int Kh, int Kw, int sh, int sw,
+               int ph, int pw, int dh, int dw, int Ho, int Wo, void* a, hipStream_t s)
+{
+    const int V = dt == NM_F32 ? 4 : 8;
+    const bool vec = (C % V == 0);
+    const size_t total = (size_t)B * Ho * Wo * Kh * Kw * (vec ? C / V : C);
+    const unsigned grid = (unsigned)std::min<size_t>((total + 255) / 256, 1u << 20);
+#define NM_IM2COL(T, VV)                                                                                    \
+    hipLaunchKernelGGL((im2col_kernel<T, VV>), dim3(grid), dim3(256), 0, s, (const T*)x, (T*)a, B, H, W, C, Kh, \
+                       Kw, sh, sw, ph, pw, dh, dw, Ho, Wo)
+    if (dt == NM_F32) { if (vec) NM_IM2COL(float, 4); else NM_IM2COL(float, 1); }
+    else { if (vec) NM_IM2COL(bf16_t, 8); else NM_IM2COL(bf16_t, 1); }
+#undef NM_IM2COL
+    NM_HIP_CHECK(hipGetLastError());
+    return NM_OK;
+}
 
 int run_maxpool(const void* x, nm_dtype_t dt, int B, int H, int W, int C, int k, int stride, int pad,
                 int Ho, int Wo, void* y, hipStream_t s)

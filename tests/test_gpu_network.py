@@ -179,3 +179,36 @@ def test_small_residual_network_end_to_end(bottleneck, bf16):
         assert got.shape == r.shape
         assert norm_err(got, r) <= tol, f"tensor {k}"
     assert out.shape == (batch, 1, 1, 10)
+
+
+@pytest.mark.parametrize("layer,batch", [(L("i2c_3x3", 13, 11, 32, 48, 3, 3, 1, 1, 1, 2, 4, 16), 2),
+                                         (L("i2c_3x3_s2", 14, 14, 16, 32, 3, 3, 2, 1, 1, 2, 4, 16), 2),
+                                         (L("i2c_7x7_c3", 20, 20, 3, 16, 7, 7, 2, 3, 1, 1, 1, 16), 2),
+                                         (L("i2c_dil2", 10, 9, 8, 16, 3, 3, 1, 2, 2, 2, 4, 16), 1)])
+@pytest.mark.parametrize("bf16", [False, True])
+def test_im2col_and_the_unfused_pipeline(layer, batch, bf16):
+    """nm_im2col is a copy (bit-exact against the oracle's); the unfused pipeline of the
+    paper's ablation -- im2col to memory, then the same kept-column contraction as a 1x1
+    convolution over it -- gives the fused kernel's result."""
+    import torch
+    x, w, bias = wl.make_tensors(layer, batch, 60, weight_sigma=0.1)
+    rnd = oracle.round_bf16 if bf16 else (lambda a: a)
+    tdt = torch.bfloat16 if bf16 else torch.float32
+    ndt = nm.NM_BF16 if bf16 else nm.NM_F32
+    xd = torch.from_numpy(x).cuda().to(tdt)
+    a = nm.nm_im2col(xd, layer.Kh, layer.Kw, layer.stride, layer.pad, layer.dil)
+    torch.cuda.synchronize()
+    ref_a = oracle.im2col(rnd(x), layer.Kh, layer.Kw, layer.stride, layer.pad, layer.dil)
+    assert np.array_equal(a.float().cpu().numpy(), ref_a)
+    _, _, wz = oracle.prune(w, layer.n, layer.m, layer.tile)
+    ref = oracle.conv2d(rnd(x), rnd(wz), bias, layer.stride, layer.pad, layer.dil, True, out_bf16=bf16)
+    bd = torch.from_numpy(bias).cuda()
+    wp1 = nm.nm_prune(np.ascontiguousarray(w.reshape(layer.Cout, 1, 1, -1)), layer.n, layer.m, layer.tile, ndt)
+    y_unfused = nm.nm_conv2d(a, wp1, bd, 1, 0, 1, True)
+    wp = nm.nm_prune(w, layer.n, layer.m, layer.tile, ndt)
+    y_fused = nm.nm_conv2d(xd, wp, bd, layer.stride, layer.pad, layer.dil, True)
+    torch.cuda.synchronize()
+    tol = BF16_TOL if bf16 else FP32_TOL
+    assert norm_err(y_unfused.float().cpu().numpy(), ref) <= tol
+    assert norm_err(y_fused.float().cpu().numpy(), ref) <= tol
+    assert np.array_equal(nm.nm_packed_indices(wp1), nm.nm_packed_indices(wp))   # same kept columns either way

@@ -92,3 +92,22 @@ def test_residual_is_added_before_the_activation_and_zero_residual_changes_nothi
     assert np.allclose(got, -1.0, atol=1e-5)
     with pytest.raises(ValueError):
         oracle.conv2d_res(x, w, zero[:, :-1], None, 1, 1, 1, True)
+
+
+@pytest.mark.parametrize("kh,kw,stride,pad,dil", [(3, 3, 1, 1, 1), (3, 3, 2, 1, 1), (1, 1, 2, 0, 1), (5, 3, 1, 2, 2), (7, 7, 2, 3, 1)])
+def test_im2col_equals_unfold_and_turns_the_convolution_into_a_matrix_product(kh, kw, stride, pad, dil):
+    rng = np.random.default_rng(kh * 7 + stride)
+    x = rng.standard_normal((2, 11, 10, 3)).astype(np.float32)
+    a = oracle.im2col(x, kh, kw, stride, pad, dil)
+    # torch.unfold orders k as (ci, kh, kw); reorder to (kh, kw, ci)
+    u = F.unfold(_nchw(x), (kh, kw), dilation=dil, padding=pad, stride=stride)        # [B, C*kh*kw, L]
+    B, _, Lp = u.shape
+    u = u.reshape(B, 3, kh, kw, Lp).permute(0, 4, 2, 3, 1).reshape(B, Lp, kh * kw * 3).numpy()
+    assert np.array_equal(a.reshape(B, Lp, -1), u.astype(np.float32))
+    w = rng.standard_normal((4, kh, kw, 3)).astype(np.float32)
+    y = oracle.conv2d(x, w, None, stride, pad, dil, False)
+    ref = a.reshape(B, Lp, -1).astype(np.float64) @ w.reshape(4, -1).astype(np.float64).T
+    assert np.allclose(y.reshape(B, Lp, 4), ref, rtol=0, atol=1e-5)
+    # and a 1x1 convolution over the im2col tensor is the original convolution
+    y1 = oracle.conv2d(a, w.reshape(4, 1, 1, -1), None, 1, 0, 1, False)
+    assert np.array_equal(y1, y)
