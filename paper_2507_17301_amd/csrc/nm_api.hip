@@ -23,6 +23,24 @@ void set_error(const char* fmt, ...)
     va_end(ap);
 }
 
+int allow_lds(const void* fn, size_t bytes, unsigned long long* done)
+{
+    if (bytes <= 64 * 1024) return NM_OK;
+    int dev = 0;
+    NM_HIP_CHECK(hipGetDevice(&dev));
+    const unsigned long long bit = 1ull << (dev & 63);
+    static std::mutex mu;
+    std::lock_guard<std::mutex> lk(mu);
+    if (*done & bit) return NM_OK;
+    const hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
+    if (e != hipSuccess) {
+        set_error("hipFuncSetAttribute(LDS %zu) failed: %s", bytes, hipGetErrorString(e));
+        return NM_ERR_HIP;
+    }
+    *done |= bit;
+    return NM_OK;
+}
+
 namespace {
 
 constexpr int kMaxLdsBytes = 160 * 1024;

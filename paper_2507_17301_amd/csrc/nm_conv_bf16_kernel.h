@@ -271,13 +271,10 @@ int launch16_t(const ConvParams& p, hipStream_t s)
     constexpr int OPR = CK / 8, PSTEP = 256 / OPR, NIT = (BP * OPR + 255) / 256;
     constexpr int ROWS = NIT * PSTEP > BP ? NIT * PSTEP : BP;
     constexpr size_t lds = (size_t)2 * ROWS * strip16_stride(CK);
-    if (lds > 64 * 1024) {
-        static hipError_t once = hipFuncSetAttribute(
-            reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-        if (once != hipSuccess) {
-            set_error("hipFuncSetAttribute(LDS %zu) failed: %s", lds, hipGetErrorString(once));
-            return NM_ERR_HIP;
-        }
+    {
+        static unsigned long long done = 0;
+        const int rc = allow_lds(reinterpret_cast<const void*>(kern), lds, &done);
+        if (rc != NM_OK) return rc;
     }
     hipLaunchKernelGGL(kern, dim3(p.wg_per_xcd * 8), dim3(256), lds, s, p);
     NM_HIP_CHECK(hipGetLastError());

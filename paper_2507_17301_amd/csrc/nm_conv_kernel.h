@@ -463,13 +463,10 @@ int launch_t(const ConvParams& p, hipStream_t s)
 {
     auto kern = nm_conv_kernel<NBLK, WP, NJ, CK, SPC, VEC, TIN, TOUT>;
     constexpr size_t lds = (size_t)2 * CK * strip_stride(16 * NBLK * WP, CK, VEC) * sizeof(float);
-    if (lds > 64 * 1024) {
-        static hipError_t once = hipFuncSetAttribute(
-            reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-        if (once != hipSuccess) {
-            set_error("hipFuncSetAttribute(LDS %zu) failed: %s", lds, hipGetErrorString(once));
-            return NM_ERR_HIP;
-        }
+    {
+        static unsigned long long done = 0;
+        const int rc = allow_lds(reinterpret_cast<const void*>(kern), lds, &done);
+        if (rc != NM_OK) return rc;
     }
     hipLaunchKernelGGL(kern, dim3(p.wg_per_xcd * 8), dim3(256), lds, s, p);
     NM_HIP_CHECK(hipGetLastError());

@@ -220,13 +220,10 @@ int launch_run16_t(const ConvParams& p, hipStream_t s)
 {
     auto kern = nm_conv_run16_kernel<NBLK, WP, NJ, KS>;
     constexpr size_t lds = run16_lds_bytes(16 * NBLK * WP, WP, NJ, KS);
-    if (lds > 64 * 1024) {
-        static hipError_t once = hipFuncSetAttribute(
-            reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-        if (once != hipSuccess) {
-            set_error("hipFuncSetAttribute(LDS %zu) failed: %s", lds, hipGetErrorString(once));
-            return NM_ERR_HIP;
-        }
+    {
+        static unsigned long long done = 0;
+        const int rc = allow_lds(reinterpret_cast<const void*>(kern), lds, &done);
+        if (rc != NM_OK) return rc;
     }
     hipLaunchKernelGGL(kern, dim3(p.wg_per_xcd * 8), dim3(256), lds, s, p);
     NM_HIP_CHECK(hipGetLastError());

@@ -390,13 +390,10 @@ int launch_sp16_t(const ConvParams& p, hipStream_t s)
     constexpr size_t stage = sp16_stage_bytes(16 * NBLK * WP, CK, NJ, SPARSE);
     // the most this kernel may ever be launched with: the full ring, or what the CU has
     constexpr size_t most = kSp16Stages * stage < 160 * 1024 ? kSp16Stages * stage : 160 * 1024;
-    if (most > 64 * 1024) {
-        static hipError_t once = hipFuncSetAttribute(
-            reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)most);
-        if (once != hipSuccess) {
-            set_error("hipFuncSetAttribute(LDS %zu) failed: %s", most, hipGetErrorString(once));
-            return NM_ERR_HIP;
-        }
+    {
+        static unsigned long long done = 0;
+        const int rc = allow_lds(reinterpret_cast<const void*>(kern), most, &done);
+        if (rc != NM_OK) return rc;
     }
     // short K loops use (and allocate) fewer stages, which leaves room for more workgroups per CU
     const size_t lds = stage * (size_t)(p.nchunks < kSp16Stages ? p.nchunks : kSp16Stages);

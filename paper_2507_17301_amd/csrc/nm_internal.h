@@ -156,6 +156,10 @@ struct VariantDesc {
     int share; // kind 1: row blocks fed from one gathered operand
 };
 
+// Allows kernel `fn` more than 64 KB of dynamic LDS on the current device; done once per
+// (kernel, device) -- `done` is the caller's per-kernel bit set, one bit per device ordinal.
+int allow_lds(const void* fn, size_t bytes, unsigned long long* done);
+
 int variant_count();
 const VariantDesc& variant_desc(int v);
 // Launches variant v; x/y dtypes select the instantiation.
