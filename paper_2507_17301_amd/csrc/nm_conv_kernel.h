@@ -269,11 +269,14 @@ __global__ __launch_bounds__(256) void nm_conv_kernel(const ConvParams p)
     };
     auto stash_item = [&](int it, float* dst) {
         if constexpr (VEC) {
-            float* d = dst + (quad * 4) * SP + pl0 + it * PSTEP;
+            // im2col row 4*quad + j of the chunk lives in LDS row j*QPR + quad: the quads a
+            // wavefront writes together are then consecutive rows, and with the row stride
+            // chosen in strip_stride() its 64 lanes fall into 64 different banks
+            float* d = dst + quad * SP + pl0 + it * PSTEP;
             d[0] = st[it].x;
-            d[SP] = st[it].y;
-            d[2 * SP] = st[it].z;
-            d[3 * SP] = st[it].w;
+            d[QPR * SP] = st[it].y;
+            d[2 * QPR * SP] = st[it].z;
+            d[3 * QPR * SP] = st[it].w;
         } else {
             dst[(r0s * NITS + it) * SP + pl0] = sts[it];
         }

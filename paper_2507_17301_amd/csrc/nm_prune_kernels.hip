@@ -105,7 +105,7 @@ __device__ inline void chunk_of(int k, int cin, int CK, int vec, int ncpt, int* 
 // One workgroup per column tile.  Kept columns are ascending in k, hence
 // grouped by chunk; the i-th kept column of a chunk becomes quarter i % 4 of
 // k-step i / 4 of that chunk.  Outputs (zero-initialised by the caller):
-//   rows [j][c][q][SPC] u32      LDS row of the kept column used by quarter q in step s
+//   rows [j][c][q][SPC] u32      LDS row (strip_row() in vector mode) of the kept column used by quarter q in step s
 //   wfrag[rb][c][lane][SPC]      weight for MFMA A-operand lane (q*16 + t)
 // err[0] is set if a chunk holds more than 4*SPC kept columns.
 __global__ __launch_bounds__(256) void build_prepack_kernel(
@@ -141,7 +141,7 @@ __global__ __launch_bounds__(256) void build_prepack_kernel(
         const int i = kk - first[c];
         const int step = i >> 2, q = i & 3;
         if (step >= SPC) continue;
-        rows[(((size_t)j * nchunks + c) * 4 + q) * SPC + step] = (uint32_t)r;
+        rows[(((size_t)j * nchunks + c) * 4 + q) * SPC + step] = (uint32_t)(vec ? strip_row(r, CK) : r);
         for (int sub = 0; sub < rbpt; ++sub) {
             const size_t rb = (size_t)j * rbpt + sub;
             for (int t = 0; t < 16; ++t) {
