@@ -270,8 +270,8 @@ __global__ __launch_bounds__(256) void nm_conv_kernel(const ConvParams p)
     auto stash_item = [&](int it, float* dst) {
         if constexpr (VEC) {
             // im2col row 4*quad + j of the chunk lives in LDS row j*QPR + quad: the quads a
-            // wavefront writes together are then consecutive rows, and with the row stride
-            // chosen in strip_stride() its 64 lanes fall into 64 different banks
+            // wavefront writes together are then consecutive rows, which the row stride
+            // chosen in strip_stride() spreads over the banks
             float* d = dst + quad * SP + pl0 + it * PSTEP;
             d[0] = st[it].x;
             d[QPR * SP] = st[it].y;

@@ -54,7 +54,9 @@ constexpr int sp16_stage_bytes(int BP, int CK, int NJ, bool sparse)
 {
     return BP * CK * 2 + 4 * NJ * (CK / 64) * ((sparse ? 1 : 2) * 1024 + (sparse ? 256 : 0));
 }
-__device__ inline int sp16_swz(int row, int CK) { return CK == 64 ? ((row >> 1) & 7) : (row & 15); }
+// (8 consecutive lanes of a 16-byte LDS read are served together: their granules must differ
+// modulo 128 bytes; the extra bit keeps rows r and r + 8 apart modulo 256 bytes as well)
+__device__ inline int sp16_swz(int row, int CK) { return CK == 64 ? ((row & 7) ^ ((row >> 3) & 1)) : (row & 15); }
 
 // s_waitcnt with only the vector-memory counter set (gfx9 encoding: vmcnt in
 // bits 3:0 and 15:14, the other counters at their maxima).

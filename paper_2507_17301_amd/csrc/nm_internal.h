@@ -85,16 +85,16 @@ struct Prepack {
 };
 
 // LDS row stride (floats) of the im2col strip: the pixel tile, widened to what
-// the staging threads write, plus a pad.  Rows stay 16-byte aligned.  In vector
-// mode a wavefront writes 8 pixels of 8 consecutive LDS rows (CK = 32) or 4
-// pixels of 16 rows (CK = 64) at a time; a stride of 8 (resp. 4) times an odd
-// number spreads those 64 words over 64 different banks.
+// the staging threads write (a multiple of 16), plus 4.  Rows stay 16-byte
+// aligned, and the stride is 4 times an odd number: the 8 (CK = 32) or 16
+// (CK = 64) consecutive LDS rows that a wavefront's transposing writes touch
+// start in different groups of four banks.
 constexpr int strip_stride(int BP, int CK, bool vec)
 {
     const int pstep = 256 / (CK / 4);
     const int nit = (BP * (CK / 4) + 255) / 256;
-    const int cols = vec && nit * pstep > BP ? nit * pstep : BP;   // a multiple of 16
-    return cols + (vec && CK == 32 ? 8 : 4);
+    const int cols = vec && nit * pstep > BP ? nit * pstep : BP;
+    return cols + 4;
 }
 
 // Vector mode stores im2col row r of a chunk (r = 4 * quad + j) in LDS row j * (CK / 4) + quad.
