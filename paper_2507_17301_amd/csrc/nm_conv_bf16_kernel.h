@@ -245,7 +245,7 @@ __global__ __launch_bounds__(256) void nm_conv_bf16_kernel(const ConvParams p)
                 const int pp = p0 + wpix + b * 16 + n;
                 if (pp >= p.P) continue;
                 f4 v = acc[jj][b] + bb;
-                emit4(p, y, (size_t)pp * p.Cout + co, v);
+                emit4(p, y, (unsigned)pp * (unsigned)p.Cout + (unsigned)co, v);
             }
         } else {
 #pragma unroll
@@ -256,7 +256,7 @@ __global__ __launch_bounds__(256) void nm_conv_bf16_kernel(const ConvParams p)
                 for (int r = 0; r < 4; ++r) {
                     if (rit + r >= p.tile || co + r >= p.Cout) continue;
                     float v = acc[jj][b][r] + (p.bias ? p.bias[co + r] : 0.f);
-                    emit1(p, y, (size_t)pp * p.Cout + co + r, v);
+                    emit1(p, y, (unsigned)pp * (unsigned)p.Cout + (unsigned)(co + r), v);
                 }
             }
         }

@@ -38,19 +38,21 @@ typedef float f2 __attribute__((ext_vector_type(2)));
 typedef unsigned u4v __attribute__((ext_vector_type(4)));
 typedef unsigned u2v __attribute__((ext_vector_type(2)));
 
-__device__ inline unsigned short to_bf16_bits(float v)
+// fp32 -> bf16, round to nearest even, NaN stays NaN: the hardware conversion of gfx950
+// (v_cvt_pk_bf16_f32), two values per instruction
+typedef float f2v __attribute__((ext_vector_type(2)));
+typedef __bf16 bf2v __attribute__((ext_vector_type(2)));
+__device__ inline unsigned pack_bf16(float lo, float hi)
 {
-    unsigned u = __float_as_uint(v);
-    if ((u & 0x7fffffffu) > 0x7f800000u) return (unsigned short)((u >> 16) | 0x40u);  // NaN
-    u += 0x7fffu + ((u >> 16) & 1u);
-    return (unsigned short)(u >> 16);
+    return __builtin_bit_cast(unsigned, __builtin_convertvector(f2v{lo, hi}, bf2v));
 }
+__device__ inline unsigned short to_bf16_bits(float v) { return (unsigned short)(pack_bf16(v, 0.f) & 0xffffu); }
 __device__ inline void store4(float* p, f4 v) { *reinterpret_cast<f4*>(p) = v; }
 __device__ inline void store4(bf16_t* p, f4 v)
 {
     uint2 u;
-    u.x = (unsigned)to_bf16_bits(v.x) | ((unsigned)to_bf16_bits(v.y) << 16);
-    u.y = (unsigned)to_bf16_bits(v.z) | ((unsigned)to_bf16_bits(v.w) << 16);
+    u.x = pack_bf16(v.x, v.y);
+    u.y = pack_bf16(v.z, v.w);
     *reinterpret_cast<uint2*>(p) = u;
 }
 __device__ inline void store1(float* p, float v) { *p = v; }
@@ -67,7 +69,8 @@ __device__ inline float load1(const bf16_t* p) { return __uint_as_float((unsigne
 
 // Tail of every epilogue: optional residual (a tensor shaped like the output,
 // added before the activation), ReLU, cast, store.
-template <typename TOUT> __device__ inline void emit4(const ConvParams& p, TOUT* y, size_t off, f4 v)
+// (offsets are element counts below 2^31, so 32-bit arithmetic is enough)
+template <typename TOUT> __device__ inline void emit4(const ConvParams& p, TOUT* y, unsigned off, f4 v)
 {
     if (p.res) v = v + load4(reinterpret_cast<const TOUT*>(p.res) + off);
     if (p.relu) {
@@ -76,7 +79,7 @@ template <typename TOUT> __device__ inline void emit4(const ConvParams& p, TOUT*
     }
     store4(y + off, v);
 }
-template <typename TOUT> __device__ inline void emit1(const ConvParams& p, TOUT* y, size_t off, float v)
+template <typename TOUT> __device__ inline void emit1(const ConvParams& p, TOUT* y, unsigned off, float v)
 {
     if (p.res) v += load1(reinterpret_cast<const TOUT*>(p.res) + off);
     if (p.relu) v = fmaxf(v, 0.f);
@@ -443,7 +446,7 @@ __global__ __launch_bounds__(256) void nm_conv_kernel(const ConvParams p)
                 const int pp = p0 + wpix + pixel_of(b);
                 if (pp >= p.P) continue;
                 f4 v = acc[jj][b] + bb;
-                emit4(p, y, (size_t)pp * p.Cout + co, v);
+                emit4(p, y, (unsigned)pp * (unsigned)p.Cout + (unsigned)co, v);
             }
         } else {
 #pragma unroll
@@ -454,7 +457,7 @@ __global__ __launch_bounds__(256) void nm_conv_kernel(const ConvParams p)
                 for (int r = 0; r < 4; ++r) {
                     if (rit + r >= p.tile || co + r >= p.Cout) continue;
                     float v = acc[jj][b][r] + (p.bias ? p.bias[co + r] : 0.f);
-                    emit1(p, y, (size_t)pp * p.Cout + co + r, v);
+                    emit1(p, y, (unsigned)pp * (unsigned)p.Cout + (unsigned)(co + r), v);
                 }
             }
         }

@@ -154,7 +154,7 @@ __global__ __launch_bounds__(256) void nm_conv_run16_kernel(const ConvParams p)
 #pragma unroll
     for (int jj = 0; jj < NJ; ++jj)
 #pragma unroll
-        for (int b = 0; b < NBLK; ++b) acc[jj][b] = f4{0.f, 0.f, 0.f, 0.f};
+        for (int b = 0; b < NBLK; ++b) acc[jj][b] = bb[jj];   // start from the bias
 
     const char* const abase = lds8 + BP * RB + wcx * AW + lane * 16;
     const int sw = run16_swz(n, KS);             // rows of block b are 16 b + n: same swizzle for every block
@@ -196,8 +196,8 @@ __global__ __launch_bounds__(256) void nm_conv_run16_kernel(const ConvParams p)
             for (int b = 0; b < NBLK; ++b) {
                 const int pp = p0 + wpix + b * 16 + n;
                 if (pp >= p.P) continue;
-                f4 v = acc[jj][b] + bb[jj];
-                emit4(p, y, (size_t)pp * p.Cout + co, v);
+                const f4 v = acc[jj][b];   // the bias is already in the accumulator
+                emit4(p, y, (unsigned)pp * (unsigned)p.Cout + (unsigned)co, v);
             }
         } else {
 #pragma unroll
@@ -208,7 +208,7 @@ __global__ __launch_bounds__(256) void nm_conv_run16_kernel(const ConvParams p)
                 for (int r = 0; r < 4; ++r) {
                     if (rit + r >= p.tile || co + r >= p.Cout) continue;
                     float v = acc[jj][b][r] + (p.bias ? p.bias[co + r] : 0.f);
-                    emit1(p, y, (size_t)pp * p.Cout + co + r, v);
+                    emit1(p, y, (unsigned)pp * (unsigned)p.Cout + (unsigned)(co + r), v);
                 }
             }
         }

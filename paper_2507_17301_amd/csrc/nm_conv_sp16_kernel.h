@@ -203,12 +203,6 @@ __global__ __launch_bounds__(256) void nm_conv_sp16_kernel(const ConvParams p)
         ++o_c;
     };
 
-    f4 acc[NJ][NBLK];
-#pragma unroll
-    for (int jj = 0; jj < NJ; ++jj)
-#pragma unroll
-        for (int b = 0; b < NBLK; ++b) acc[jj][b] = f4{0.f, 0.f, 0.f, 0.f};
-
     // this lane's operand granules inside block 0 of a stage: k-step s, half h
     unsigned roff[KS][2];
 #pragma unroll
@@ -227,11 +221,7 @@ __global__ __launch_bounds__(256) void nm_conv_sp16_kernel(const ConvParams p)
         fetch_advance();
         fetch_ops(stage);
     };
-    retap();
-    fetch_stage(0);
-    if (p.nchunks > 1) fetch_stage(1);
-
-    // bias of this lane's rows, fetched now so that its latency hides behind the loop
+    // bias of this lane's rows, requested first: the accumulators start from it
     const bool fast = (p.tile % 4 == 0) && (p.Cout % 4 == 0);
     f4 bb[NJ];
 #pragma unroll
@@ -244,6 +234,16 @@ __global__ __launch_bounds__(256) void nm_conv_sp16_kernel(const ConvParams p)
         if (fast && p.bias && rb < p.n_rowblocks && rit < p.tile && co < p.Cout)
             bb[jj] = *reinterpret_cast<const f4*>(p.bias + co);
     }
+    retap();
+    fetch_stage(0);
+    if (p.nchunks > 1) fetch_stage(1);
+
+    // the accumulators start from the bias (zero where there is none or rows are handled one by one)
+    f4 acc[NJ][NBLK];
+#pragma unroll
+    for (int jj = 0; jj < NJ; ++jj)
+#pragma unroll
+        for (int b = 0; b < NBLK; ++b) acc[jj][b] = bb[jj];
 
     constexpr int NM = KS * NBLK;                // B operands (LDS reads) per chunk for this wavefront
     static_assert((NBLK - 1) * 16 * RB < 65536, "block offsets must fit the LDS instruction's immediate");
@@ -366,8 +366,8 @@ __global__ __launch_bounds__(256) void nm_conv_sp16_kernel(const ConvParams p)
             for (int b = 0; b < NBLK; ++b) {
                 const int pp = p0 + wpix + b * 16 + n;
                 if (pp >= p.P) continue;
-                f4 v = acc[jj][b] + bb[jj];
-                emit4(p, y, (size_t)pp * p.Cout + co, v);
+                const f4 v = acc[jj][b];   // the bias is already in the accumulator
+                emit4(p, y, (unsigned)pp * (unsigned)p.Cout + (unsigned)co, v);
             }
         } else {
 #pragma unroll
@@ -378,7 +378,7 @@ __global__ __launch_bounds__(256) void nm_conv_sp16_kernel(const ConvParams p)
                 for (int r = 0; r < 4; ++r) {
                     if (rit + r >= p.tile || co + r >= p.Cout) continue;
                     float v = acc[jj][b][r] + (p.bias ? p.bias[co + r] : 0.f);
-                    emit1(p, y, (size_t)pp * p.Cout + co + r, v);
+                    emit1(p, y, (unsigned)pp * (unsigned)p.Cout + (unsigned)(co + r), v);
                 }
             }
         }
