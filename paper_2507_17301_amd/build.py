@@ -66,6 +66,14 @@ def _shapes_run():
     return [tuple(int(v) for v in m) for m in re.findall(r"X\((\d+),\s*(\d+),\s*(\d+)\)", body)]
 
 
+def _shapes_var():
+    """(NBLK, WP, NJ) of NMVAR_SHAPES in nm_variants.h."""
+    text = open(os.path.join(CSRC, "nm_variants.h")).read()
+    body = text[text.index("#define NMVAR_SHAPES(X)"):]
+    body = body[:body.index("// Y(")]
+    return [tuple(int(v) for v in m) for m in re.findall(r"X\((\d+),\s*(\d+),\s*(\d+)\)", body)]
+
+
 def _jobs():
     jobs = []
     for src in ("nm_api.hip", "nm_prune_kernels.hip", "nm_pool_kernels.hip", "nm_conv_registry.hip"):
@@ -75,6 +83,9 @@ def _jobs():
         jobs.append((inst, os.path.join(OBJDIR, f"nm_conv_inst_{nb}_{wp}_{nj}.o"),
                      [f"-DNM_INST_NBLK={nb}", f"-DNM_INST_WP={wp}", f"-DNM_INST_NJ={nj}"]))
     jobs.append((inst, os.path.join(OBJDIR, "nm_conv_inst_scalar.o"), ["-DNM_INST_SCALAR"]))
+    for nb, wp, nj in _shapes_var():
+        jobs.append((inst, os.path.join(OBJDIR, f"nm_conv_inst_var_{nb}_{wp}_{nj}.o"),
+                     ["-DNM_INST_VAR", f"-DNM_INST_NBLK={nb}", f"-DNM_INST_WP={wp}", f"-DNM_INST_NJ={nj}"]))
     inst16 = os.path.join(CSRC, "nm_conv16_inst.hip")
     for nb, wp, nj, sh in _shapes16():
         jobs.append((inst16, os.path.join(OBJDIR, f"nm_conv16_inst_{nb}_{wp}_{nj}_{sh}.o"),

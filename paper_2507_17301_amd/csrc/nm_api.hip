@@ -75,7 +75,7 @@ size_t lds_bytes(const VariantDesc& d, const nm_packed* wp)
 {
     if (d.kind == 4)   // the strip [BP][64 SPC] bf16 plus the dense weights of the workgroup's row blocks
         return (size_t)d.BP * d.SPC * 128 + (size_t)(4 / d.WP) * d.NJ * d.SPC * 2048;
-    if (d.kind >= 2) {   // up to three stages of the strip [BP][CK] bf16 plus each wave's operands
+    if (d.kind >= 2 && d.kind <= 4) {   // up to three stages of the strip [BP][CK] bf16 plus each wave's operands
         const int nchunks = wp->kh * wp->kw * ((wp->cin + d.CK - 1) / d.CK);
         return (size_t)std::min(3, nchunks) *
                (d.BP * d.CK * 2 + 4 * d.NJ * (d.CK / 64) * (d.kind == 2 ? 1024 + 256 : 2048));
@@ -116,7 +116,8 @@ bool variant_legal(int v, const nm_packed* wp, nm_dtype_t xdt, const RunArgs* ra
     if (v < 0 || v >= variant_count()) return false;
     const VariantDesc& d = variant_desc(v);
     if (lds_bytes(d, wp) > (size_t)kMaxLdsBytes) return false;
-    if (d.kind >= 1) {
+    if (d.kind == 5 && xdt != NM_F32) return false;   // instantiated for fp32 tensors only
+    if (d.kind >= 1 && d.kind <= 4) {
         // bf16 matrix cores: bf16 tensors, weights already rounded to bf16, and a
         // shared operand only for column tiles made of exactly two row blocks
         if (xdt != NM_BF16 || wp->value_dtype != NM_BF16) return false;
@@ -244,7 +245,7 @@ int heuristic_variant(const nm_packed* wp, int P, nm_dtype_t xdt, const RunArgs*
         const double mfma = (double)d.BP * rb_per_wg;            // per chunk step, relative
         const double stage = (double)d.BP * 2.0;                 // staging cost per chunk, relative
         // the bf16 matrix-core kernel contracts several times faster where it applies
-        const double speed[5] = {1.0, 0.3, 0.1, 0.2, 0.1};        // relative cost of a unit of contraction
+        const double speed[6] = {1.0, 0.3, 0.1, 0.2, 0.1, 0.7};   // relative cost of a unit of contraction
         const double cost = (double)rounds * occ * (mfma + stage) * speed[d.kind];
         if (best < 0 || cost < best_cost * 0.999) {
             best = v;
@@ -417,7 +418,9 @@ int nm_prune(const float* w, int cout, int kh, int kw, int cin, int n, int m, in
             }
             continue;
         }
-        if (d.kind >= 2) {
+        if (d.kind == 5) {
+            if (!vec_ok || value_dtype != NM_F32) continue;
+        } else if (d.kind >= 2) {
             // gather-free bf16 kernel: whole 64-channel k-steps of one tap per chunk; the
             // sparse operand holds at most 2 kept columns per aligned group of 4
             if (value_dtype != NM_BF16 || cin % d.CK != 0) continue;
@@ -441,13 +444,18 @@ int nm_prune(const float* w, int cout, int kh, int kw, int cin, int n, int m, in
                     pick = e.SPC;
             }
             if (pick == 0 || pick != d.SPC) continue;
+        } else if (d.kind == 5) {
+            // worth its table only where the kept columns are spread unevenly over the
+            // chunks: otherwise the fixed-step form does the same work
+            const int most = max_kept_per_chunk(wp, g);
+            if ((long)most * g.nchunks * 10 <= (long)wp->kprime * 11) continue;
         }
         Prepack pp;
         pp.kind = d.kind;
         pp.geom = g;
         pp.SPC = d.SPC;
         size_t rows_bytes, wf_bytes;
-        if (d.kind >= 2) {
+        if (d.kind >= 2 && d.kind <= 4) {
             rows_bytes = (size_t)wp->n_tiles * g.nchunks * 4 * pp.SPC * sizeof(uint32_t);
             wf_bytes = (size_t)wp->n_rowblocks * g.nchunks * pp.SPC * (d.kind == 2 ? 1 : 2) * 64 * 8 *
                        sizeof(uint16_t);

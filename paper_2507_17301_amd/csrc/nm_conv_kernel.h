@@ -145,9 +145,14 @@ __device__ inline unsigned fdiv(unsigned x, unsigned mul, unsigned shift)
     return __umulhi(x << 1, mul) >> shift;
 }
 
-template <int NBLK, int WP, int NJ, int CK, int SPC, bool VEC, typename TIN, typename TOUT>
+// MODE 0: element-wise staging on the flat k axis; 1: 16-byte channel loads, every chunk
+// runs SPC k-steps; 2: as 1, but each (column tile, chunk) runs only the k-steps that
+// hold kept columns (their number rides in the upper half of the first row-table word).
+template <int NBLK, int WP, int NJ, int CK, int SPC, int MODE, typename TIN, typename TOUT>
 __global__ __launch_bounds__(256) void nm_conv_kernel(const ConvParams p)
 {
+    constexpr bool VEC = MODE != 0;
+    constexpr bool VAR = MODE == 2;
     constexpr int BPW = 16 * NBLK;        // pixels per wavefront
     constexpr int BP = BPW * WP;          // pixels per workgroup
     constexpr int SP = strip_stride(BP, CK, VEC);
@@ -383,22 +388,54 @@ __global__ __launch_bounds__(256) void nm_conv_kernel(const ConvParams p)
             if constexpr (R == 1 || R == 3)
                 dst[NBLK - 1] = *reinterpret_cast<const float*>(base8 + (__umul24(row, SP * 4) + l32));
         };
+        if constexpr (VAR) {
+            // The first SMIN k-steps of a row block always run (slots past the kept
+            // columns carry weight 0) and carry the staging tasks; the others run only
+            // up to the count the table gives for this (tile, chunk).
+            constexpr int SMIN = SPC / 4;
+            constexpr int NMV = NJ * SMIN * NBLK;
 #pragma unroll
-        for (int t = 0; t < DEPTH && t < TOT; ++t) read_b(t, bv[t % RING]);
+            for (int jj = 0; jj < NJ; ++jj) {
+                const int ns = __builtin_amdgcn_readfirstlane((int)(cur[jj].row[0] >> 16));
+                cur[jj].row[0] &= 0xffffu;
 #pragma unroll
-        for (int t = 0; t < TOT; ++t) {
-            // the LDS reads of k-step t+DEPTH lead the MFMAs of k-step t
-            if (t + DEPTH < TOT) read_b(t + DEPTH, bv[(t + DEPTH) % RING]);
-            __builtin_amdgcn_sched_barrier(0);
-            const int jj = t / SPC, s = t % SPC;
-            const float a = cur[jj].a[s];
+                for (int s = 0; s < DEPTH && s < SPC; ++s) read_b(jj * SPC + s, bv[s % RING]);
 #pragma unroll
-            for (int b = 0; b < NBLK; ++b) {
-                const int m = t * NBLK + b;
-                acc[jj][b] = __builtin_amdgcn_mfma_f32_16x16x4f32(a, bv[t % RING][b], acc[jj][b], 0, 0, 0);
+                for (int s = 0; s < SPC; ++s) {
+                    if (s >= SMIN && s >= ns) break;
+                    if (s + DEPTH < SPC) read_b(jj * SPC + s + DEPTH, bv[(s + DEPTH) % RING]);
+                    __builtin_amdgcn_sched_barrier(0);
+                    const float a = cur[jj].a[s];
 #pragma unroll
-                for (int i = m * NTASK / NM; i < (m + 1) * NTASK / NM; ++i) task(i);
+                    for (int b = 0; b < NBLK; ++b) {
+                        acc[jj][b] = __builtin_amdgcn_mfma_f32_16x16x4f32(a, bv[s % RING][b], acc[jj][b], 0, 0, 0);
+                        if (s < SMIN) {
+                            const int m = (jj * SMIN + s) * NBLK + b;
+#pragma unroll
+                            for (int i = m * NTASK / NMV; i < (m + 1) * NTASK / NMV; ++i) task(i);
+                        }
+                        __builtin_amdgcn_sched_barrier(0);
+                    }
+                }
+            }
+        } else {
+#pragma unroll
+            for (int t = 0; t < DEPTH && t < TOT; ++t) read_b(t, bv[t % RING]);
+#pragma unroll
+            for (int t = 0; t < TOT; ++t) {
+                // the LDS reads of k-step t+DEPTH lead the MFMAs of k-step t
+                if (t + DEPTH < TOT) read_b(t + DEPTH, bv[(t + DEPTH) % RING]);
                 __builtin_amdgcn_sched_barrier(0);
+                const int jj = t / SPC, s = t % SPC;
+                const float a = cur[jj].a[s];
+#pragma unroll
+                for (int b = 0; b < NBLK; ++b) {
+                    const int m = t * NBLK + b;
+                    acc[jj][b] = __builtin_amdgcn_mfma_f32_16x16x4f32(a, bv[t % RING][b], acc[jj][b], 0, 0, 0);
+#pragma unroll
+                    for (int i = m * NTASK / NM; i < (m + 1) * NTASK / NM; ++i) task(i);
+                    __builtin_amdgcn_sched_barrier(0);
+                }
             }
         }
         __syncthreads();
@@ -464,11 +501,11 @@ __global__ __launch_bounds__(256) void nm_conv_kernel(const ConvParams p)
     }
 }
 
-template <int NBLK, int WP, int NJ, int CK, int SPC, bool VEC, typename TIN, typename TOUT>
+template <int NBLK, int WP, int NJ, int CK, int SPC, int MODE, typename TIN, typename TOUT>
 int launch_t(const ConvParams& p, hipStream_t s)
 {
-    auto kern = nm_conv_kernel<NBLK, WP, NJ, CK, SPC, VEC, TIN, TOUT>;
-    constexpr size_t lds = (size_t)2 * CK * strip_stride(16 * NBLK * WP, CK, VEC) * sizeof(float);
+    auto kern = nm_conv_kernel<NBLK, WP, NJ, CK, SPC, MODE, TIN, TOUT>;
+    constexpr size_t lds = (size_t)2 * CK * strip_stride(16 * NBLK * WP, CK, MODE != 0) * sizeof(float);
     {
         static unsigned long long done = 0;
         const int rc = allow_lds(reinterpret_cast<const void*>(kern), lds, &done);

@@ -13,8 +13,8 @@ struct Entry {
 
 #define NM_ENTRY(NB, WP, NJ, CK, SPC, VEC)                                                     \
     {{"NB" #NB "_WP" #WP "_NJ" #NJ "_CK" #CK "_SPC" #SPC "_V" #VEC, 16 * NB * WP, NB, WP, NJ, CK, SPC, VEC, 0, 1}, \
-     &launch_t<NB, WP, NJ, CK, SPC, (VEC) != 0, float, float>,                                 \
-     &launch_t<NB, WP, NJ, CK, SPC, (VEC) != 0, bf16_t, bf16_t>},
+     &launch_t<NB, WP, NJ, CK, SPC, (VEC) != 0 ? 1 : 0, float, float>,                                 \
+     &launch_t<NB, WP, NJ, CK, SPC, (VEC) != 0 ? 1 : 0, bf16_t, bf16_t>},
 #define NM_SHAPE_ENTRIES(NB, WP, NJ) NM_VEC_CHUNKS(NM_ENTRY, NB, WP, NJ)
 
 #define NM_ENTRY16(NB, WP, NJ, SH, CK, SPC)                                                     \
@@ -34,9 +34,15 @@ struct Entry {
      nullptr, &launch_run16_t<NB, WP, NJ, KS>},
 #define NM_SHAPE_ENTRIESRUN(NB, WP, NJ) NMRUN_CHUNKS(NM_ENTRYRUN, NB, WP, NJ)
 
+// kind 5: fp32 MFMA kernel, per-(tile, chunk) number of k-steps (fp32 tensors only)
+#define NM_ENTRYVAR(NB, WP, NJ, CK, SPC)                                                        \
+    {{"VAR_NB" #NB "_WP" #WP "_NJ" #NJ "_CK" #CK "_SPC" #SPC, 16 * NB * WP, NB, WP, NJ, CK, SPC, 1, 5, 1}, \
+     &launch_t<NB, WP, NJ, CK, SPC, 2, float, float>, nullptr},
+#define NM_SHAPE_ENTRIESVAR(NB, WP, NJ) NMVAR_CHUNKS(NM_ENTRYVAR, NB, WP, NJ)
+
 const Entry kEntries[] = {NM_SHAPES(NM_SHAPE_ENTRIES) NM_SCALAR_VARIANTS(NM_ENTRY)
                           NM16_SHAPES(NM_SHAPE_ENTRIES16) NMSP_SHAPES(NM_SHAPE_ENTRIESSP)
-                          NMRUN_SHAPES(NM_SHAPE_ENTRIESRUN)};
+                          NMRUN_SHAPES(NM_SHAPE_ENTRIESRUN) NMVAR_SHAPES(NM_SHAPE_ENTRIESVAR)};
 constexpr int kCount = (int)(sizeof(kEntries) / sizeof(kEntries[0]));
 }  // namespace
 
@@ -50,7 +56,7 @@ int launch_conv(int v, nm_dtype_t xdt, nm_dtype_t ydt, const ConvParams& p, hipS
         return NM_ERR_UNSUPPORTED;
     }
     if (xdt == NM_F32 && ydt == NM_F32 && kEntries[v].ff) return kEntries[v].ff(p, s);
-    if (xdt == NM_BF16 && ydt == NM_BF16) return kEntries[v].bb(p, s);
+    if (xdt == NM_BF16 && ydt == NM_BF16 && kEntries[v].bb) return kEntries[v].bb(p, s);
     set_error("unsupported dtype pair: input and output must both be fp32 or both bf16");
     return NM_ERR_UNSUPPORTED;
 }

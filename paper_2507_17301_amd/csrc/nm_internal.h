@@ -61,12 +61,15 @@ inline ChunkGeom make_chunk_geom(int cin, int K, int CK, int vec)
 // tile; the i-th kept column of the chunk is quarter i % 4 of step i / 4, and
 // unused slots carry weight 0 and row 0.
 struct Prepack {
-    int kind = 0;                     // 0: fp32 MFMA kernel, 1: bf16 MFMA gather kernel, 2/3: gather-free bf16 kernel
+    int kind = 0;                     // 0: fp32 MFMA kernel, 1: bf16 MFMA gather kernel, 2/3: gather-free bf16 kernel,
+                                      // 4: bf16 kernel-row runs, 5: fp32 MFMA kernel with per-chunk step counts
     ChunkGeom geom{};
     int SPC = 0;                      // k-steps per chunk (1, 2, 4 or 8)
     // kind 0: a k-step is 4 kept columns
     //   d_rows  [n_tiles][nchunks][4][SPC] u32        LDS row (k - k0) that quarter q reads in step s
     //   d_wfrag [n_rowblocks][nchunks][64][SPC] fp32  MFMA A-operand lane values
+    // kind 5: as kind 0 with SPC = CK / 4; bits 16.. of d_rows[j][c][q][0] hold the number of
+    //   k-steps that carry kept columns of (tile j, chunk c)
     // kind 1: a k-step is 32 kept columns
     //   d_rows  [n_tiles][nchunks][SPC][4][8] u32     byte offset (k - k0) * 2 of the 8 columns of quarter q
     //   d_wfrag [n_rowblocks][nchunks][SPC][64][8] bf16  MFMA A-operand lane values
@@ -157,7 +160,8 @@ struct VariantDesc {
     int vec;   // chunk mode: 1 = 16-byte channel loads, 0 = element-wise on flat k
     int kind;  // 0 = fp32 MFMA kernel (fp32 or bf16 I/O), 1 = bf16 MFMA gather kernel (bf16 I/O, bf16 weights),
                // 2 = bf16 sparse-matrix-instruction kernel, 3 = bf16 dense kernel on zero-filled weights,
-               // 4 = bf16 dense kernel on contiguous kernel-row runs (very few input channels)
+               // 4 = bf16 dense kernel on contiguous kernel-row runs (very few input channels),
+               // 5 = fp32 MFMA kernel that runs only the k-steps holding kept columns of each (tile, chunk)
     int share; // kind 1: row blocks fed from one gathered operand
 };
 

@@ -6,7 +6,7 @@
 namespace nm {
 struct bf16_t { unsigned short v; };
 
-template <int NBLK, int WP, int NJ, int CK, int SPC, bool VEC, typename TIN, typename TOUT>
+template <int NBLK, int WP, int NJ, int CK, int SPC, int MODE, typename TIN, typename TOUT>
 int launch_t(const ConvParams& p, hipStream_t s);
 template <int NBLK, int WP, int NJ, int CK, int SPC, int SHARE>
 int launch16_t(const ConvParams& p, hipStream_t s);

@@ -110,7 +110,7 @@ __device__ inline void chunk_of(int k, int cin, int CK, int vec, int ncpt, int* 
 // err[0] is set if a chunk holds more than 4*SPC kept columns.
 __global__ __launch_bounds__(256) void build_prepack_kernel(
     const int32_t* __restrict__ idx, const float* __restrict__ vals, int kprime, int T, int rbpt,
-    int cin, int CK, int vec, int ncpt, int nchunks, int SPC,
+    int cin, int CK, int vec, int ncpt, int nchunks, int SPC, int with_counts,
     uint32_t* __restrict__ rows, float* __restrict__ wfrag, int* __restrict__ err)
 {
     extern __shared__ int sm_int[];
@@ -149,6 +149,14 @@ __global__ __launch_bounds__(256) void build_prepack_kernel(
                 const float v = tt < T ? vals[((size_t)j * kprime + kk) * T + tt] : 0.f;
                 wfrag[((rb * nchunks + c) * 64 + q * 16 + t) * SPC + step] = v;
             }
+        }
+    }
+    if (with_counts) {
+        // number of k-steps that hold kept columns, in the upper half of each quarter's first word
+        __syncthreads();
+        for (int i = threadIdx.x; i < nchunks * 4; i += blockDim.x) {
+            const int c = i >> 2, q = i & 3;
+            rows[(((size_t)j * nchunks + c) * 4 + q) * SPC] |= (uint32_t)((cnt[c] + 3) >> 2) << 16;
         }
     }
 }
@@ -396,10 +404,10 @@ int run_build_prepack(nm_packed* wp, Prepack& pp, hipStream_t s)
     NM_HIP_CHECK(hipMalloc(&d_err, sizeof(int)));
     NM_HIP_CHECK(hipMemsetAsync(d_err, 0, sizeof(int), s));
     const size_t lds = (size_t)2 * g.nchunks * sizeof(int);
-    if (pp.kind == 0)
+    if (pp.kind == 0 || pp.kind == 5)
         hipLaunchKernelGGL(build_prepack_kernel, dim3(wp->n_tiles), dim3(256), lds, s, wp->d_idx,
                            wp->d_vals, wp->kprime, wp->tile, wp->rbpt, wp->cin, g.CK, g.vec, g.ncpt,
-                           g.nchunks, pp.SPC, pp.d_rows, pp.d_wfrag, d_err);
+                           g.nchunks, pp.SPC, pp.kind == 5 ? 1 : 0, pp.d_rows, pp.d_wfrag, d_err);
     else if (pp.kind == 4) {
         const int KwC = wp->kw * wp->cin, GR = (pp.par + KwC + 7) / 8;
         const size_t total = (size_t)wp->n_rowblocks * pp.SPC * 2 * 64;

@@ -22,6 +22,16 @@
     Y(NB, WP, NJ, 32, 2, 1) Y(NB, WP, NJ, 32, 4, 1) Y(NB, WP, NJ, 32, 8, 1)       \
     Y(NB, WP, NJ, 64, 2, 1) Y(NB, WP, NJ, 64, 4, 1) Y(NB, WP, NJ, 64, 8, 1)
 
+// fp32 kernel with a per-(tile, chunk) number of k-steps: for kept sets that are not
+// spread evenly over the chunks (group size M larger than a chunk).  SPC = CK / 4 is
+// the width of the operand table, not the work done.
+// X(NBLK, WP, NJ)
+#define NMVAR_SHAPES(X)                                                             \
+    X(2, 1, 1) X(3, 1, 1) X(4, 1, 1) X(5, 1, 1) X(6, 1, 1) X(7, 1, 1) X(8, 1, 1)    \
+    X(10, 1, 1) X(13, 1, 1) X(2, 1, 2) X(4, 1, 2) X(8, 1, 2) X(2, 2, 1) X(4, 2, 2)
+// Y(NBLK, WP, NJ, CK, SPC)
+#define NMVAR_CHUNKS(Y, NB, WP, NJ) Y(NB, WP, NJ, 32, 8) Y(NB, WP, NJ, 64, 16)
+
 #define NM_SCALAR_VARIANTS(Y) Y(4, 4, 4, 32, 8, 0) Y(4, 2, 2, 32, 8, 0) Y(4, 1, 1, 32, 8, 0)
 
 // bf16 matrix-core kernel (bf16 activations, bf16-rounded weights):

@@ -84,7 +84,10 @@ def test_every_variant_in_turn():
     assert ran >= 9
 
 
-@pytest.mark.parametrize("n,m,tile", [(1, 8, 32), (1, 4, 8), (4, 8, 16), (1, 1, 16)])
+# the last four have groups wider than a chunk (M = Cin, M = the whole row, few kept columns so
+# that some chunks of a tile hold none): the kept columns are spread unevenly over the chunks
+@pytest.mark.parametrize("n,m,tile", [(1, 8, 32), (1, 4, 8), (4, 8, 16), (1, 1, 16),
+                                      (64, 128, 16), (32, 128, 32), (576, 1152, 16), (8, 128, 16)])
 def test_every_variant_other_sparsities(n, m, tile):
     layer = L("variants2", 9, 9, 128, 64, 3, 3, 2, 1, 1, n, m, tile)
     x, w, bias = wl.make_tensors(layer, 6, 8, weight_sigma=0.1)
@@ -93,7 +96,7 @@ def test_every_variant_other_sparsities(n, m, tile):
     wp = nm.nm_prune(w, n, m, tile)
     xd = torch.from_numpy(x).cuda()
     bd = torch.from_numpy(bias).cuda()
-    ran = 0
+    ran = var_ran = 0
     try:
         for v in range(nm.nm_variant_count()):
             if not nm.nm_variant_legal(v, wp):
@@ -104,9 +107,11 @@ def test_every_variant_other_sparsities(n, m, tile):
             torch.cuda.synchronize()
             assert norm_err(y.cpu().numpy(), ref) <= FP32_TOL, nm.nm_variant_name(v)
             ran += 1
+            var_ran += nm.nm_variant_name(v).startswith("VAR_")
     finally:
         nm.nm_force_variant(-1)
     assert ran >= 9
+    assert (var_ran > 0) == (m >= 128)   # the variable-step form exists exactly where it pays
 
 
 @pytest.mark.parametrize("n,m,tile,cin,ksize", [
