@@ -54,6 +54,9 @@ def main():
     ap.add_argument("--nm", default=None, help="experiment: N:M of the ResNet-18/50 workloads, e.g. 1:4")
     ap.add_argument("--group", choices=["cin", "row"], default=None,
                     help="experiment: one group per kernel tap (M = Cin) or per row (M = K), half the columns kept")
+    ap.add_argument("--tune-tile", default=None,
+                    help="experiment: comma-separated tile sizes; the tuner prunes every pruned layer at each and "
+                         "keeps the fastest per layer (nm_autotune_tile), e.g. 8,16,32")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-tune", action="store_true", help="use the untuned default variant")
     ap.add_argument("--no-graph", action="store_true",
@@ -106,7 +109,11 @@ def main():
         wname += "_groups_per_" + args.group
     if args.batch is not None:
         B = args.batch
-    headline = (args.workload == "resnet50" and B == 64 and not args.group and (n_, m_, t_) == (2, 4, 16))
+    cand_tiles = [int(t) for t in args.tune_tile.split(",")] if args.tune_tile else None
+    if cand_tiles:
+        wname += "_T_per_layer_of_" + "_".join(str(t) for t in cand_tiles)
+    headline = (args.workload == "resnet50" and B == 64 and not args.group and (n_, m_, t_) == (2, 4, 16)
+                and not cand_tiles)
     bf16 = args.dtype == "bf16"
     tdt = torch.bfloat16 if bf16 else torch.float32
     ndt = nm.NM_BF16 if bf16 else nm.NM_F32
@@ -123,7 +130,15 @@ def main():
     for i, l in enumerate(layers):
         _, w, bias = wl.make_tensors(l, B, seed0 + i, with_input=False)
         tp = time.time()
-        wp = nm.nm_prune(w, l.n, l.m, l.tile, ndt)
+        if cand_tiles and l.n < l.m:
+            import dataclasses
+            wp, best_t, t_ms = nm.nm_autotune_tile(w, l.n, l.m, cand_tiles, ndt, B, l.H, l.W, True,
+                                                   l.stride, l.pad, l.dil, True)
+            log(f"{l.name:>22s}  T -> {best_t:2d}   " +
+                "  ".join(f"T{t}: {v * 1e3:7.1f} us" for t, v in zip(cand_tiles, t_ms)))
+            layers[i] = l = dataclasses.replace(l, tile=best_t)
+        else:
+            wp = nm.nm_prune(w, l.n, l.m, l.tile, ndt)
         prune_s += time.time() - tp
         packed.append(wp)
         x = torch.rand((B, l.H, l.W, l.Cin), generator=gen, device=dev, dtype=torch.float32).to(tdt)

@@ -191,6 +191,31 @@ int nm_autotune(nm_dtype_t x_dtype, int b, int h, int w, int cin,
                 int relu, nm_dtype_t y_dtype, void* hip_stream,
                 int* chosen_variant, float* best_ms);
 
+/*
+ * nm_autotune_tile -- the tuner also chooses the tile size T (section 3.3 spans
+ * T in [1, 32]; the accuracy study of section 4.4 has a configuration whose T is
+ * picked per layer by profiling).  For every candidate T the weights are pruned
+ * at that T (nm_prune) and the convolution is tuned for the given shape
+ * (nm_autotune, which also caches the variant); the handle of the fastest
+ * candidate is returned and the others are freed.  T changes which weights
+ * survive, so the candidates are different models: the choice is a
+ * deployment-time trade that the paper pairs with retraining.
+ *   w_host .. m, value_dtype   as nm_prune
+ *   tiles[n_candidates]        host array of candidate T, tried in order (ties keep the earlier)
+ *   x_dtype .. hip_stream      as nm_autotune
+ *   out                        receives the winning handle, owned by the caller (nm_packed_free)
+ *   best_tile                  may be NULL
+ *   ms_per_candidate           host array [n_candidates] of each candidate's best time, or NULL
+ * Synchronous.  Any error of nm_prune or nm_autotune for any candidate fails the
+ * call and frees every handle; *out is then NULL.
+ */
+int nm_autotune_tile(const float* w_host, int cout, int kh, int kw, int cin, int n, int m,
+                     const int* tiles, int n_candidates, nm_dtype_t value_dtype,
+                     nm_dtype_t x_dtype, int b, int h, int w, int has_bias,
+                     int stride_h, int stride_w, int pad_h, int pad_w, int dil_h, int dil_w,
+                     int relu, nm_dtype_t y_dtype, void* hip_stream,
+                     nm_packed_t** out, int* best_tile, float* ms_per_candidate);
+
 /* Tuning cache: text file, one line per shape.  Loading merges into the cache. */
 int nm_cache_save(const char* path);
 int nm_cache_load(const char* path);

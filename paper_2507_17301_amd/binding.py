@@ -58,6 +58,8 @@ def lib():
         L.nm_im2col.argtypes = [vp] + [ci] * 13 + [vp, vp]
         L.nm_autotune.argtypes = [ci, ci, ci, ci, ci, vp, ci, ci, ci, ci, ci, ci, ci, ci, ci, vp,
                                   pi, ctypes.POINTER(cf)]
+        L.nm_autotune_tile.argtypes = ([vp] + [ci] * 6 + [pi, ci, ci] + [ci] * 13 +
+                                       [vp, ctypes.POINTER(vp), pi, ctypes.POINTER(ctypes.c_float)])
         L.nm_cache_save.argtypes = [ctypes.c_char_p]
         L.nm_cache_load.argtypes = [ctypes.c_char_p]
         L.nm_force_variant.argtypes = [ci]
@@ -291,6 +293,27 @@ def nm_autotune(x_dtype: int, b: int, h: int, w: int, cin: int, wp: Packed, has_
                              dh, dw, int(bool(relu)), x_dtype if y_dtype is None else y_dtype,
                              _stream_ptr(stream), ctypes.byref(v), ctypes.byref(ms)))
     return v.value, ms.value
+
+
+def nm_autotune_tile(w_ohwi: np.ndarray, n: int, m: int, tiles, x_dtype: int, b: int, h: int, w: int,
+                     has_bias=True, stride=1, pad=0, dil=1, relu=True, value_dtype: Optional[int] = None,
+                     stream=None):
+    """Prunes at every candidate tile size, tunes each and returns
+    (handle of the fastest, its tile size, [ms per candidate])."""
+    wt = np.ascontiguousarray(w_ohwi, dtype=np.float32)
+    cout, kh, kw, cin = wt.shape
+    sh, sw = _pair(stride)
+    ph, pw = _pair(pad)
+    dh, dw = _pair(dil)
+    vd = x_dtype if value_dtype is None else value_dtype
+    cand = (ctypes.c_int * len(tiles))(*[int(t) for t in tiles])
+    ms = (ctypes.c_float * len(tiles))()
+    hnd, best = ctypes.c_void_p(), ctypes.c_int(0)
+    _check(lib().nm_autotune_tile(wt.ctypes.data, cout, kh, kw, cin, n, m, cand, len(tiles), vd,
+                                  x_dtype, b, h, w, int(bool(has_bias)), sh, sw, ph, pw, dh, dw,
+                                  int(bool(relu)), x_dtype, _stream_ptr(stream),
+                                  ctypes.byref(hnd), ctypes.byref(best), ms))
+    return Packed(hnd, cout, kh, kw, cin, n, m, best.value, vd), best.value, list(ms)
 
 
 def nm_cache_save(path: str):

@@ -835,6 +835,45 @@ int nm_autotune(nm_dtype_t xdt, int b, int h, int w, int cin, const nm_packed_t*
     return NM_OK;
 }
 
+int nm_autotune_tile(const float* w, int cout, int kh, int kw, int cin, int n, int m,
+                     const int* tiles, int n_candidates, nm_dtype_t value_dtype,
+                     nm_dtype_t xdt, int b, int h, int wd, int has_bias,
+                     int sh, int sw, int ph, int pw, int dh, int dw, int relu, nm_dtype_t ydt,
+                     void* stream, nm_packed_t** out, int* best_tile, float* ms_per_candidate)
+{
+    if (!out || !tiles || n_candidates < 1) {
+        set_error("null output or empty candidate list");
+        return NM_ERR_ARG;
+    }
+    *out = nullptr;
+    nm_packed_t* best = nullptr;
+    float best_ms = 0.f;
+    for (int i = 0; i < n_candidates; ++i) {
+        nm_packed_t* wp = nullptr;
+        int rc = nm_prune(w, cout, kh, kw, cin, n, m, tiles[i], value_dtype, &wp);
+        float ms = 0.f;
+        if (rc == NM_OK)
+            rc = nm_autotune(xdt, b, h, wd, cin, wp, has_bias, sh, sw, ph, pw, dh, dw, relu, ydt, stream,
+                             nullptr, &ms);
+        if (rc != NM_OK) {   // the message of the failing call stands
+            free_packed(wp);
+            free_packed(best);
+            return rc;
+        }
+        if (ms_per_candidate) ms_per_candidate[i] = ms;
+        if (!best || ms < best_ms) {
+            free_packed(best);
+            best = wp;
+            best_ms = ms;
+            if (best_tile) *best_tile = tiles[i];
+        } else {
+            free_packed(wp);
+        }
+    }
+    *out = best;
+    return NM_OK;
+}
+
 int nm_cache_clear(void)
 {
     std::lock_guard<std::mutex> lk(g_mu);

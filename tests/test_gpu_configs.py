@@ -6,8 +6,12 @@ batch 1, one whole image of selected ResNet-50 layers); elsewhere a few thousand
 sampled outputs per layer, always including the corners of the first and last
 image and the last channel, are computed one by one by the oracle.
 """
+import dataclasses
+
 import numpy as np
 import pytest
+
+import oracle
 
 from paper_2507_17301_amd import binding as nm
 from paper_2507_17301_amd import workloads as wl
@@ -115,3 +119,29 @@ def test_tuning_cache_round_trip(tmp_path):
     assert v2 == v and abs(ms2 - ms) < 1e-6
     with pytest.raises(nm.NMError):
         nm.nm_cache_load(str(tmp_path / "missing.txt"))
+
+
+def test_tuner_chooses_the_tile_size():
+    """nm_autotune_tile: every candidate T is pruned and tuned, the fastest handle
+    comes back, its masks are the oracle's at that T and it convolves like the oracle."""
+    import torch
+    layer = wl.ConvLayer("tile_choice", 14, 14, 64, 96, 3, 3, 1, 1, 1, 2, 4, 16)
+    x, w, bias = wl.make_tensors(layer, 4, 77, weight_sigma=0.1)
+    tiles = [8, 16, 32]
+    say(f"autotune over tiles {tiles} {layer}")
+    wp, best, ms = nm.nm_autotune_tile(w, layer.n, layer.m, tiles, nm.NM_F32, 4, layer.H, layer.W,
+                                       True, layer.stride, layer.pad, layer.dil, True)
+    assert best in tiles and wp.tile == best
+    assert len(ms) == 3 and all(t > 0 for t in ms)
+    assert ms[tiles.index(best)] == min(ms)
+    mask_ref, _, _ = oracle.prune(w, layer.n, layer.m, best)
+    assert np.array_equal(nm.nm_packed_mask(wp), mask_ref)
+    y = nm.nm_conv2d(torch.from_numpy(x).cuda(), wp, torch.from_numpy(bias).cuda(),
+                     layer.stride, layer.pad, layer.dil, True)
+    torch.cuda.synchronize()
+    chosen = dataclasses.replace(layer, tile=best)
+    ref = oracle_conv(chosen, x, w, bias, relu=True)
+    assert norm_err(y.cpu().numpy(), ref) <= FP32_TOL
+    # errors of a candidate fail the whole call: tile 0 is not a tile
+    with pytest.raises(nm.NMError):
+        nm.nm_autotune_tile(w, layer.n, layer.m, [16, 0], nm.NM_F32, 4, layer.H, layer.W)
