@@ -86,6 +86,55 @@ template <typename TOUT> __device__ inline void emit1(const ConvParams& p, TOUT*
     store1(y + off, v);
 }
 
+// ---- workgroup-wide output tile ---------------------------------------------
+// A store straight from the MFMA accumulator layout touches 16 pixels x 32 bytes (bf16)
+// or 64 bytes (fp32) per instruction, and streams of such partial-line writes reach
+// about two thirds of the memory rate that whole 128-byte lines reach (measured with a
+// load-then-store microbenchmark of the same tile sizes).  So where the layer allows
+// (T a multiple of 16, 16-byte aligned pixel rows) the workgroup first assembles its
+// output tile [pixel][channel] in LDS -- residual, ReLU and the cast applied on the way
+// in, one rounding -- and then writes it out 16 bytes per lane with consecutive lanes
+// on consecutive bytes of a pixel.  The row pitch is an odd number of 16-byte units.
+template <typename TOUT> constexpr int tile_pitch(int wgc) { return wgc * (int)sizeof(TOUT) + 16; }
+constexpr size_t out_tile_bytes(int bp, int wgc, int es) { return (size_t)bp * (wgc * es + 16); }
+
+template <typename TOUT> __device__ inline bool tile_out_ok(const ConvParams& p)
+{
+    return (p.tile % 16 == 0) && ((p.Cout * (int)sizeof(TOUT)) % 16 == 0);
+}
+// four consecutive channels of one pixel into the tile; `goff` is the element offset of
+// the same four values in the output (for the residual), `live` whether they exist
+template <typename TOUT>
+__device__ inline void tile_put4(const ConvParams& p, char* dst, unsigned goff, bool live, f4 v)
+{
+    if (p.res && live) v = v + load4(reinterpret_cast<const TOUT*>(p.res) + goff);
+    if (p.relu) {
+        v.x = fmaxf(v.x, 0.f); v.y = fmaxf(v.y, 0.f);
+        v.z = fmaxf(v.z, 0.f); v.w = fmaxf(v.w, 0.f);
+    }
+    store4(reinterpret_cast<TOUT*>(dst), v);
+}
+// the tile [BP][WGC] (first pixel p0, first channel co0) from LDS to the NHWC output
+template <typename TOUT, int BP, int WGC>
+__device__ inline void tile_flush(const ConvParams& p, const char* tile, int p0, int co0)
+{
+    constexpr int CPG = 16 / (int)sizeof(TOUT);      // channels per 16-byte granule
+    constexpr int GPR = WGC / CPG;                   // granules per pixel
+    constexpr int PITCH = tile_pitch<TOUT>(WGC);
+    constexpr int NG = (BP * GPR + 255) / 256;
+    TOUT* __restrict__ y = reinterpret_cast<TOUT*>(p.y);
+#pragma unroll
+    for (int it = 0; it < NG; ++it) {
+        const int g = (int)threadIdx.x + it * 256;
+        const int r = g / GPR, cg = g % GPR;
+        const int pp = p0 + r, co = co0 + cg * CPG;
+        if ((BP * GPR % 256 == 0 || r < BP) && pp < p.P && co < p.Cout) {
+            const u4v v = *reinterpret_cast<const u4v*>(tile + r * PITCH + cg * 16);
+            *reinterpret_cast<u4v*>(y + ((unsigned)pp * (unsigned)p.Cout + (unsigned)co)) = v;
+        }
+    }
+}
+
 // Buffer loads: an offset at or beyond the descriptor's size returns zeros, which
 // is how padding, ragged pixel tiles and partial chunks are filled without a branch.
 constexpr unsigned kOOB = 0x80000000u;   // beyond any tensor this library accepts (< 2 GiB)
@@ -466,6 +515,31 @@ __global__ __launch_bounds__(256) void nm_conv_kernel(const ConvParams p)
         if (R >= 2 && b < 4 * NF + 2) return OFF2 + n * 2 + (b - 4 * NF);
         return OFF1 + n;
     };
+    constexpr int WGC = WC * NJ * 16;     // output channels of the workgroup
+    if (WGC * (int)sizeof(TOUT) >= 128 && tile_out_ok<TOUT>(p)) {
+        // through the LDS tile (every wavefront is past its last strip read: the chunk ends with a barrier)
+        constexpr int PITCH = tile_pitch<TOUT>(WGC);
+        char* const tile = reinterpret_cast<char*>(lds);
+#pragma unroll
+        for (int jj = 0; jj < NJ; ++jj) {
+            const int rb = rb0 + jj;
+            const int co = rb * 16 + q * 4;           // T is a multiple of 16: row block rb is channels 16 rb ..
+            const bool row_live = rb < p.n_rowblocks && co < p.Cout;
+            f4 bb = {0.f, 0.f, 0.f, 0.f};
+            if (p.bias && row_live) bb = *reinterpret_cast<const f4*>(p.bias + co);
+#pragma unroll
+            for (int b = 0; b < NBLK; ++b) {
+                const int pl = wpix + pixel_of(b);
+                const int pp = p0 + pl;
+                tile_put4<TOUT>(p, tile + pl * PITCH + ((wcx * NJ + jj) * 16 + q * 4) * (int)sizeof(TOUT),
+                                (unsigned)pp * (unsigned)p.Cout + (unsigned)co, row_live && pp < p.P,
+                                acc[jj][b] + bb);
+            }
+        }
+        __syncthreads();
+        tile_flush<TOUT, BP, WGC>(p, tile, p0, cblock * WGC);
+        return;
+    }
 #pragma unroll
     for (int jj = 0; jj < NJ; ++jj) {
         const int rb = rb0 + jj;
@@ -505,7 +579,9 @@ template <int NBLK, int WP, int NJ, int CK, int SPC, int MODE, typename TIN, typ
 int launch_t(const ConvParams& p, hipStream_t s)
 {
     auto kern = nm_conv_kernel<NBLK, WP, NJ, CK, SPC, MODE, TIN, TOUT>;
-    constexpr size_t lds = (size_t)2 * CK * strip_stride(16 * NBLK * WP, CK, MODE != 0) * sizeof(float);
+    constexpr size_t strip = (size_t)2 * CK * strip_stride(16 * NBLK * WP, CK, MODE != 0) * sizeof(float);
+    constexpr size_t otile = out_tile_bytes(16 * NBLK * WP, (4 / WP) * NJ * 16, (int)sizeof(TOUT));
+    constexpr size_t lds = strip > otile ? strip : otile;
     {
         static unsigned long long done = 0;
         const int rc = allow_lds(reinterpret_cast<const void*>(kern), lds, &done);

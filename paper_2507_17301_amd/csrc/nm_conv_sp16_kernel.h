@@ -352,6 +352,29 @@ __global__ __launch_bounds__(256) void nm_conv_sp16_kernel(const ConvParams p)
 
     // ---- epilogue: bias, ReLU, round to bf16, NHWC store ------------------------
     bf16_t* __restrict__ y = reinterpret_cast<bf16_t*>(p.y);
+    constexpr int WGC = WC * NJ * 16;            // output channels of the workgroup
+    if (WGC * 2 >= 128 && fast && tile_out_ok<bf16_t>(p)) {
+        // whole 128-byte lines through the LDS tile, once every wavefront is past its last strip read
+        constexpr int PITCH = tile_pitch<bf16_t>(WGC);
+        __syncthreads();
+#pragma unroll
+        for (int jj = 0; jj < NJ; ++jj) {
+            const int rb = rb0 + jj;
+            const int co = rb * 16 + q * 4;       // T is a multiple of 16: row block rb is channels 16 rb ..
+            const bool row_live = rb < p.n_rowblocks && co < p.Cout;
+#pragma unroll
+            for (int b = 0; b < NBLK; ++b) {
+                const int pl = wpix + b * 16 + n;
+                const int pp = p0 + pl;
+                tile_put4<bf16_t>(p, lds8 + pl * PITCH + ((wcx * NJ + jj) * 16 + q * 4) * 2,
+                                  (unsigned)pp * (unsigned)p.Cout + (unsigned)co, row_live && pp < p.P,
+                                  acc[jj][b]);   // the bias is already in the accumulator
+            }
+        }
+        __syncthreads();
+        tile_flush<bf16_t, BP, WGC>(p, lds8, p0, cblock * WGC);
+        return;
+    }
 #pragma unroll
     for (int jj = 0; jj < NJ; ++jj) {
         const int rb = rb0 + jj;
@@ -391,14 +414,19 @@ int launch_sp16_t(const ConvParams& p, hipStream_t s)
     auto kern = nm_conv_sp16_kernel<NBLK, WP, NJ, CK, SPARSE>;
     constexpr size_t stage = sp16_stage_bytes(16 * NBLK * WP, CK, NJ, SPARSE);
     // the most this kernel may ever be launched with: the full ring, or what the CU has
-    constexpr size_t most = kSp16Stages * stage < 160 * 1024 ? kSp16Stages * stage : 160 * 1024;
+    constexpr size_t ring = kSp16Stages * stage > out_tile_bytes(16 * NBLK * WP, (4 / WP) * NJ * 16, 2)
+                                ? kSp16Stages * stage : out_tile_bytes(16 * NBLK * WP, (4 / WP) * NJ * 16, 2);
+    constexpr size_t most = ring < 160 * 1024 ? ring : 160 * 1024;
     {
         static unsigned long long done = 0;
         const int rc = allow_lds(reinterpret_cast<const void*>(kern), most, &done);
         if (rc != NM_OK) return rc;
     }
-    // short K loops use (and allocate) fewer stages, which leaves room for more workgroups per CU
-    const size_t lds = stage * (size_t)(p.nchunks < kSp16Stages ? p.nchunks : kSp16Stages);
+    // short K loops use (and allocate) fewer stages, which leaves room for more workgroups per CU;
+    // the epilogue's output tile needs its share too
+    constexpr size_t otile = out_tile_bytes(16 * NBLK * WP, (4 / WP) * NJ * 16, 2);
+    size_t lds = stage * (size_t)(p.nchunks < kSp16Stages ? p.nchunks : kSp16Stages);
+    if (lds < otile) lds = otile;
     if (lds > most) {
         set_error("internal: LDS %zu bytes exceed the CU's 160 KB", lds);
         return NM_ERR_UNSUPPORTED;
