@@ -76,7 +76,7 @@ size_t lds_bytes(const VariantDesc& d, const nm_packed* wp)
     // the epilogue's output tile [BP][channels of the workgroup] plus 16 bytes per pixel
     const size_t otile = (size_t)d.BP * ((size_t)(4 / d.WP) * d.NJ * 16 * (d.kind == 0 || d.kind == 5 ? 4 : 2) + 16);
     if (d.kind == 4)   // the strip [BP][64 SPC] bf16 plus the dense weights of the workgroup's row blocks
-        return (size_t)d.BP * d.SPC * 128 + (size_t)(4 / d.WP) * d.NJ * d.SPC * 2048;
+        return std::max(otile, (size_t)d.BP * d.SPC * 128 + (size_t)(4 / d.WP) * d.NJ * d.SPC * 2048);
     if (d.kind >= 2 && d.kind <= 4) {   // up to three stages of the strip [BP][CK] bf16 plus each wave's operands
         const int nchunks = wp->kh * wp->kw * ((wp->cin + d.CK - 1) / d.CK);
         return std::max(otile, (size_t)std::min(3, nchunks) *
@@ -85,7 +85,7 @@ size_t lds_bytes(const VariantDesc& d, const nm_packed* wp)
     if (d.kind == 1) {
         const int opr = d.CK / 8, pstep = 256 / opr, nit = (d.BP * opr + 255) / 256;
         const int rows = nit * pstep > d.BP ? nit * pstep : d.BP;
-        return (size_t)2 * rows * (d.CK * 2 + 4);
+        return std::max(otile, (size_t)2 * rows * (d.CK * 2 + 4));
     }
     return std::max(otile, (size_t)2 * d.CK * strip_stride(d.BP, d.CK, d.vec != 0) * sizeof(float));
 }

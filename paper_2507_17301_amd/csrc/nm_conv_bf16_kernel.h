@@ -228,6 +228,30 @@ __global__ __launch_bounds__(256) void nm_conv_bf16_kernel(const ConvParams p)
     // ---- epilogue ---------------------------------------------------------------
     bf16_t* __restrict__ y = reinterpret_cast<bf16_t*>(p.y);
     const bool fast = (p.tile % 4 == 0) && (p.Cout % 4 == 0);
+    constexpr int WGC = WC * NJ * 16;            // output channels of the workgroup
+    if (WGC * 2 >= 128 && tile_out_ok<bf16_t>(p)) {
+        // whole 128-byte lines through the LDS tile (the last chunk ended with a barrier)
+        constexpr int PITCH = tile_pitch<bf16_t>(WGC);
+#pragma unroll
+        for (int jj = 0; jj < NJ; ++jj) {
+            const int rb = rb0 + jj;
+            const int co = rb * 16 + q * 4;       // T is a multiple of 16: row block rb is channels 16 rb ..
+            const bool row_live = rb < p.n_rowblocks && co < p.Cout;
+            f4 bb = {0.f, 0.f, 0.f, 0.f};
+            if (p.bias && row_live) bb = *reinterpret_cast<const f4*>(p.bias + co);
+#pragma unroll
+            for (int b = 0; b < NBLK; ++b) {
+                const int pl = wpix + b * 16 + n;
+                const int pp = p0 + pl;
+                tile_put4<bf16_t>(p, lds8 + pl * PITCH + ((wcx * NJ + jj) * 16 + q * 4) * 2,
+                                  (unsigned)pp * (unsigned)p.Cout + (unsigned)co, row_live && pp < p.P,
+                                  acc[jj][b] + bb);
+            }
+        }
+        __syncthreads();
+        tile_flush<bf16_t, BP, WGC>(p, lds8, p0, cblock * WGC);
+        return;
+    }
 #pragma unroll
     for (int jj = 0; jj < NJ; ++jj) {
         const int rb = rb0 + jj;
@@ -270,7 +294,9 @@ int launch16_t(const ConvParams& p, hipStream_t s)
     constexpr int BP = 16 * NBLK * WP;
     constexpr int OPR = CK / 8, PSTEP = 256 / OPR, NIT = (BP * OPR + 255) / 256;
     constexpr int ROWS = NIT * PSTEP > BP ? NIT * PSTEP : BP;
-    constexpr size_t lds = (size_t)2 * ROWS * strip16_stride(CK);
+    constexpr size_t strip = (size_t)2 * ROWS * strip16_stride(CK);
+    constexpr size_t otile = out_tile_bytes(BP, (4 / WP) * NJ * 16, 2);
+    constexpr size_t lds = strip > otile ? strip : otile;
     {
         static unsigned long long done = 0;
         const int rc = allow_lds(reinterpret_cast<const void*>(kern), lds, &done);

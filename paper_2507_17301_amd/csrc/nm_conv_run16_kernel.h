@@ -182,6 +182,29 @@ __global__ __launch_bounds__(256) void nm_conv_run16_kernel(const ConvParams p)
 
     // ---- epilogue: bias, ReLU, round to bf16, NHWC store ------------------------
     bf16_t* __restrict__ y = reinterpret_cast<bf16_t*>(p.y);
+    constexpr int WGC = WC * NJ * 16;            // output channels of the workgroup
+    if (WGC * 2 >= 128 && fast && tile_out_ok<bf16_t>(p)) {
+        // whole 128-byte lines through the LDS tile, once every wavefront is past its last strip read
+        constexpr int PITCH = tile_pitch<bf16_t>(WGC);
+        __syncthreads();
+#pragma unroll
+        for (int jj = 0; jj < NJ; ++jj) {
+            const int rb = rb0 + jj;
+            const int co = rb * 16 + q * 4;       // T is a multiple of 16: row block rb is channels 16 rb ..
+            const bool row_live = rb < p.n_rowblocks && co < p.Cout;
+#pragma unroll
+            for (int b = 0; b < NBLK; ++b) {
+                const int pl = wpix + b * 16 + n;
+                const int pp = p0 + pl;
+                tile_put4<bf16_t>(p, lds8 + pl * PITCH + ((wcx * NJ + jj) * 16 + q * 4) * 2,
+                                  (unsigned)pp * (unsigned)p.Cout + (unsigned)co, row_live && pp < p.P,
+                                  acc[jj][b]);   // the bias is already in the accumulator
+            }
+        }
+        __syncthreads();
+        tile_flush<bf16_t, BP, WGC>(p, lds8, p0, cblock * WGC);
+        return;
+    }
 #pragma unroll
     for (int jj = 0; jj < NJ; ++jj) {
         const int rb = rb0 + jj;
@@ -219,7 +242,9 @@ template <int NBLK, int WP, int NJ, int KS>
 int launch_run16_t(const ConvParams& p, hipStream_t s)
 {
     auto kern = nm_conv_run16_kernel<NBLK, WP, NJ, KS>;
-    constexpr size_t lds = run16_lds_bytes(16 * NBLK * WP, WP, NJ, KS);
+    constexpr size_t work = run16_lds_bytes(16 * NBLK * WP, WP, NJ, KS);
+    constexpr size_t otile = out_tile_bytes(16 * NBLK * WP, (4 / WP) * NJ * 16, 2);
+    constexpr size_t lds = work > otile ? work : otile;
     {
         static unsigned long long done = 0;
         const int rc = allow_lds(reinterpret_cast<const void*>(kern), lds, &done);
