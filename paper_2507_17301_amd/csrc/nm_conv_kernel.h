@@ -114,9 +114,13 @@ __device__ inline void tile_put4(const ConvParams& p, char* dst, unsigned goff, 
     }
     store4(reinterpret_cast<TOUT*>(dst), v);
 }
-// the tile [BP][WGC] (first pixel p0, first channel co0) from LDS to the NHWC output
-template <typename TOUT, int BP, int WGC>
-__device__ inline void tile_flush(const ConvParams& p, const char* tile, int p0, int co0)
+// the tile [BP][WGC] (first pixel p0, first channel co0) from LDS to the NHWC output;
+// pix(r) is the pixel, inside the workgroup's range, that LDS row r holds
+struct TileRowIsPixel {
+    __device__ int operator()(int r) const { return r; }
+};
+template <typename TOUT, int BP, int WGC, typename PIX = TileRowIsPixel>
+__device__ inline void tile_flush(const ConvParams& p, const char* tile, int p0, int co0, PIX pix = PIX())
 {
     constexpr int CPG = 16 / (int)sizeof(TOUT);      // channels per 16-byte granule
     constexpr int GPR = WGC / CPG;                   // granules per pixel
@@ -127,7 +131,7 @@ __device__ inline void tile_flush(const ConvParams& p, const char* tile, int p0,
     for (int it = 0; it < NG; ++it) {
         const int g = (int)threadIdx.x + it * 256;
         const int r = g / GPR, cg = g % GPR;
-        const int pp = p0 + r, co = co0 + cg * CPG;
+        const int pp = p0 + pix(r), co = co0 + cg * CPG;
         if ((BP * GPR % 256 == 0 || r < BP) && pp < p.P && co < p.Cout) {
             const u4v v = *reinterpret_cast<const u4v*>(tile + r * PITCH + cg * 16);
             *reinterpret_cast<u4v*>(y + ((unsigned)pp * (unsigned)p.Cout + (unsigned)co)) = v;
@@ -324,20 +328,21 @@ __global__ __launch_bounds__(256) void nm_conv_kernel(const ConvParams p)
             }
         }
     };
-    auto stash_item = [&](int it, float* dst) {
+    auto stash_value = [&](int it, float* dst, const f4& v4, float v1) {
         if constexpr (VEC) {
             // im2col row 4*quad + j of the chunk lives in LDS row j*QPR + quad: the quads a
             // wavefront writes together are then consecutive rows, which the row stride
             // chosen in strip_stride() spreads over the banks
             float* d = dst + quad * SP + pl0 + it * PSTEP;
-            d[0] = st[it].x;
-            d[QPR * SP] = st[it].y;
-            d[2 * QPR * SP] = st[it].z;
-            d[3 * QPR * SP] = st[it].w;
+            d[0] = v4.x;
+            d[QPR * SP] = v4.y;
+            d[2 * QPR * SP] = v4.z;
+            d[3 * QPR * SP] = v4.w;
         } else {
-            dst[(r0s * NITS + it) * SP + pl0] = sts[it];
+            dst[(r0s * NITS + it) * SP + pl0] = v1;
         }
     };
+    auto stash_item = [&](int it, float* dst) { stash_value(it, dst, st[VEC ? it : 0], sts[VEC ? 0 : it]); };
 
     // ---- operand streams ----------------------------------------------------
     // A wavefront whose row blocks lie beyond the last one still takes part in
@@ -361,29 +366,49 @@ __global__ __launch_bounds__(256) void nm_conv_kernel(const ConvParams p)
         load_words<SPC>(o.row, rr, rvoff, rsoff[jj] + (unsigned)c * (4 * SPC * 4));
     };
 
-    f4 acc[NJ][NBLK];
-#pragma unroll
-    for (int jj = 0; jj < NJ; ++jj)
-#pragma unroll
-        for (int b = 0; b < NBLK; ++b) acc[jj][b] = f4{0.f, 0.f, 0.f, 0.f};
-
     StepOps<SPC> opsA[NJ], opsB[NJ];
 
-    // Prologue: operands of chunk 0, strip of chunk 0 into LDS, strip of chunk 1
-    // into registers.  The operand loads go out first so that the wait for the
-    // strip also covers them.
+    // Prologue: bias and operands of chunk 0, then the strips of chunk 0 and of chunk 1
+    // into registers, and only then chunk 0 into LDS: the first wait of the workgroup
+    // covers one memory round trip, not three.
+    const bool bias_first = (p.tile % 4 == 0) && (p.Cout % 4 == 0);   // the accumulators can start from it
+    f4 bb0[NJ];
+#pragma unroll
+    for (int jj = 0; jj < NJ; ++jj) {
+        bb0[jj] = f4{0.f, 0.f, 0.f, 0.f};
+        const int rb = rb0 + jj;
+        const int j = rb / p.rbpt;
+        const int rit = (rb - j * p.rbpt) * 16 + q * 4;
+        const int co = j * p.tile + rit;
+        if (bias_first && p.bias && rb < p.n_rowblocks && rit < p.tile && co < p.Cout)
+            bb0[jj] = *reinterpret_cast<const f4*>(p.bias + co);
+    }
 #pragma unroll
     for (int jj = 0; jj < NJ; ++jj) load_ops(opsA[jj], jj, 0);
     if constexpr (VEC) retap();
 #pragma unroll
     for (int it = 0; it < NST; ++it) fetch_item(it);
     fetch_advance();
+    {
+        f4 first4[VEC ? NIT : 1];
+        float first1[VEC ? 1 : NITS];
 #pragma unroll
-    for (int it = 0; it < NST; ++it) stash_item(it, lds);
+        for (int it = 0; it < (VEC ? NIT : 1); ++it) first4[it] = st[it];
 #pragma unroll
-    for (int it = 0; it < NST; ++it) fetch_item(it);
-    fetch_advance();
+        for (int it = 0; it < (VEC ? 1 : NITS); ++it) first1[it] = sts[it];
+#pragma unroll
+        for (int it = 0; it < NST; ++it) fetch_item(it);
+        fetch_advance();
+#pragma unroll
+        for (int it = 0; it < NST; ++it) stash_value(it, lds, first4[VEC ? it : 0], first1[VEC ? 0 : it]);
+    }
     __syncthreads();
+
+    f4 acc[NJ][NBLK];
+#pragma unroll
+    for (int jj = 0; jj < NJ; ++jj)
+#pragma unroll
+        for (int b = 0; b < NBLK; ++b) acc[jj][b] = bb0[jj];
 
     constexpr int TOT = NJ * SPC;          // k-steps per chunk for this wavefront
     constexpr int DEPTH = NBLK <= 4 ? 2 : 1;   // LDS reads run this many k-steps ahead
@@ -515,6 +540,11 @@ __global__ __launch_bounds__(256) void nm_conv_kernel(const ConvParams p)
         if (R >= 2 && b < 4 * NF + 2) return OFF2 + n * 2 + (b - 4 * NF);
         return OFF1 + n;
     };
+    auto row_of = [&](int b) {     // LDS row of the output tile that holds this lane's pixel of block b
+        if (b < 4 * NF) return (b >> 2) * 64 + (b & 3) * 16 + n;
+        if (R >= 2 && b < 4 * NF + 2) return OFF2 + (b - 4 * NF) * 16 + n;
+        return OFF1 + n;
+    };
     constexpr int WGC = WC * NJ * 16;     // output channels of the workgroup
     if (WGC * (int)sizeof(TOUT) >= 128 && tile_out_ok<TOUT>(p)) {
         // through the LDS tile (every wavefront is past its last strip read: the chunk ends with a barrier)
@@ -525,19 +555,26 @@ __global__ __launch_bounds__(256) void nm_conv_kernel(const ConvParams p)
             const int rb = rb0 + jj;
             const int co = rb * 16 + q * 4;           // T is a multiple of 16: row block rb is channels 16 rb ..
             const bool row_live = rb < p.n_rowblocks && co < p.Cout;
-            f4 bb = {0.f, 0.f, 0.f, 0.f};
-            if (p.bias && row_live) bb = *reinterpret_cast<const f4*>(p.bias + co);
 #pragma unroll
             for (int b = 0; b < NBLK; ++b) {
-                const int pl = wpix + pixel_of(b);
-                const int pp = p0 + pl;
-                tile_put4<TOUT>(p, tile + pl * PITCH + ((wcx * NJ + jj) * 16 + q * 4) * (int)sizeof(TOUT),
+                const int pp = p0 + wpix + pixel_of(b);
+                // the lanes of one store go to consecutive LDS rows (conflict-free with the odd pitch)
+                const int row = wpix + row_of(b);
+                tile_put4<TOUT>(p, tile + row * PITCH + ((wcx * NJ + jj) * 16 + q * 4) * (int)sizeof(TOUT),
                                 (unsigned)pp * (unsigned)p.Cout + (unsigned)co, row_live && pp < p.P,
-                                acc[jj][b] + bb);
+                                acc[jj][b]);   // the bias is already in the accumulator
             }
         }
         __syncthreads();
-        tile_flush<TOUT, BP, WGC>(p, tile, p0, cblock * WGC);
+        auto pixel_of_row = [](int r) {   // inverse of row_of over the workgroup's rows
+            const int w = r / BPW, rr = r - w * BPW;
+            int pl;
+            if (rr < NF * 64) pl = (rr & ~63) + (rr & 15) * 4 + ((rr >> 4) & 3);
+            else if (R >= 2 && rr < OFF1) pl = OFF2 + ((rr - OFF2) & 15) * 2 + ((rr - OFF2) >> 4);
+            else pl = rr;
+            return w * BPW + pl;
+        };
+        tile_flush<TOUT, BP, WGC>(p, tile, p0, cblock * WGC, pixel_of_row);
         return;
     }
 #pragma unroll
@@ -550,14 +587,11 @@ __global__ __launch_bounds__(256) void nm_conv_kernel(const ConvParams p)
         const int co = j * p.tile + rit;
         if (fast) {
             if (rit >= p.tile || co >= p.Cout) continue;
-            f4 bb = {0.f, 0.f, 0.f, 0.f};
-            if (p.bias) bb = *reinterpret_cast<const f4*>(p.bias + co);
 #pragma unroll
             for (int b = 0; b < NBLK; ++b) {
                 const int pp = p0 + wpix + pixel_of(b);
                 if (pp >= p.P) continue;
-                f4 v = acc[jj][b] + bb;
-                emit4(p, y, (unsigned)pp * (unsigned)p.Cout + (unsigned)co, v);
+                emit4(p, y, (unsigned)pp * (unsigned)p.Cout + (unsigned)co, acc[jj][b]);   // bias included
             }
         } else {
 #pragma unroll

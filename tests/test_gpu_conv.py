@@ -31,6 +31,11 @@ GRID = [
     (L("dense_cin32", 8, 8, 32, 32, 3, 3, 1, 1, 1, 1, 1, 16), 2),
     (L("M_is_cin", 8, 8, 64, 32, 3, 3, 1, 1, 1, 16, 64, 16), 2),
     (L("one_pixel", 3, 3, 16, 16, 3, 3, 1, 0, 1, 2, 4, 16), 1),
+    # output tiles with a ragged last column tile: 4 and 8 live channels of 16, and a channel count
+    # whose bf16 pixel rows are not 16-byte aligned (direct stores instead of the LDS output tile)
+    (L("cout20_T16", 11, 9, 32, 20, 3, 3, 1, 1, 1, 2, 4, 16), 3),
+    (L("cout24_T16", 11, 9, 64, 24, 1, 1, 1, 0, 1, 2, 4, 16), 3),
+    (L("cout36_T16", 9, 11, 64, 36, 3, 3, 1, 1, 1, 2, 4, 16), 2),
 ]
 
 
@@ -47,8 +52,8 @@ def test_shape_grid_fp32(layer, batch):
     assert norm_err(got, ref) <= FP32_TOL
 
 
-@pytest.mark.parametrize("layer,batch", GRID[:4] + GRID[7:10] + GRID[14:15],
-                         ids=[g[0].name for g in GRID[:4] + GRID[7:10] + GRID[14:15]])
+@pytest.mark.parametrize("layer,batch", GRID[:4] + GRID[7:10] + GRID[14:15] + GRID[18:],
+                         ids=[g[0].name for g in GRID[:4] + GRID[7:10] + GRID[14:15] + GRID[18:]])
 def test_shape_grid_bf16(layer, batch):
     say(f"grid bf16 {layer} batch={batch}")
     x, w, bias = wl.make_tensors(layer, batch, 200 + batch, weight_sigma=0.1)
