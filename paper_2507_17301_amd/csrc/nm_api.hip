@@ -225,6 +225,8 @@ void fill_params(ConvParams& p, const VariantDesc& d, const Prepack& pp, const n
     p.x_bytes = (unsigned)((size_t)b * h * w * wp->cin * es);
     p.run_d = pp.par;
     p.run_gr = (pp.par + wp->kw * wp->cin + 7) / 8;
+    magic_div((unsigned)p.run_gr, &p.gr_mul, &p.gr_shift);
+    magic_div((unsigned)wp->cin, &p.cin_mul, &p.cin_shift);
 }
 
 // Deterministic default when the shape has not been tuned: a small model of

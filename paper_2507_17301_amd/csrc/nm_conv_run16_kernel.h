@@ -92,7 +92,7 @@ __global__ __launch_bounds__(256) void nm_conv_run16_kernel(const ConvParams p)
         const int G = (wave + 4 * it) * 64 + lane;            // granule slot of the strip this lane fills
         const int pl = G / GPR;
         const int g = (G % GPR) ^ run16_swz(pl, KS);          // the granule that belongs at that slot
-        const int kh = g / GR, gi = g - kh * GR;
+        const int kh = (int)fdiv((unsigned)g, p.gr_mul, p.gr_shift), gi = g - kh * GR;
         const int pp = p0 + pl;
         const int b = (int)fdiv((unsigned)pp, p.howo_mul, p.howo_shift);
         const int rem = pp - b * HoWo;
@@ -103,12 +103,14 @@ __global__ __launch_bounds__(256) void nm_conv_run16_kernel(const ConvParams p)
         const bool rowok = (pp < p.P) & (kh < p.Kh) & ((unsigned)hi < (unsigned)p.H);
         // first element of the granule in the tensor, and which of its 8 elements are real taps
         const int e0 = gi * 8 - dsh;                          // position in the run of element 0
-        const long long start = ((long long)(b * p.H + hi) * p.W + wi0) * p.Cin + e0;
+        // (32-bit: the tensor has fewer than 2^30 elements and rows that pass `rowok` lie inside it)
+        const int start = ((b * p.H + hi) * p.W + wi0) * p.Cin + e0;
         // columns the real taps of this granule touch: elements max(e0,0) .. min(e0+7, KwC-1)
         const int lo = e0 > 0 ? e0 : 0, hi_e = e0 + 7 < KwC - 1 ? e0 + 7 : KwC - 1;
         const bool any = lo <= hi_e;
-        const int wlo = wi0 + lo / p.Cin, whi = wi0 + hi_e / p.Cin;
-        const bool inside = (wlo >= 0) & (whi < p.W) & (start >= 0) & (start + 8 <= (long long)p.x_elems);
+        const int wlo = wi0 + (int)fdiv((unsigned)lo, p.cin_mul, p.cin_shift);
+        const int whi = wi0 + (any ? (int)fdiv((unsigned)hi_e, p.cin_mul, p.cin_shift) : 0);
+        const bool inside = (wlo >= 0) & (whi < p.W) & (start >= 0) & ((unsigned)start + 8u <= p.x_elems);
         const bool dma = rowok & any & inside;
         need[it] = rowok & any & !inside;
         const unsigned off = dma ? (unsigned)start * 2u : kOOB;
@@ -120,7 +122,7 @@ __global__ __launch_bounds__(256) void nm_conv_run16_kernel(const ConvParams p)
 #pragma unroll
             for (int e = 0; e < 8; ++e) {
                 const int er = e0 + e;
-                const int wi = wi0 + (er >= 0 ? er / p.Cin : -1);
+                const int wi = wi0 + (er >= 0 ? (int)fdiv((unsigned)er, p.cin_mul, p.cin_shift) : -1);
                 const bool ok = (er >= 0) & (er < KwC) & ((unsigned)wi < (unsigned)p.W);
                 v[e] = __builtin_amdgcn_raw_buffer_load_b16(xr, ok ? (unsigned)(start + e) * 2u : kOOB, 0, 0);
             }

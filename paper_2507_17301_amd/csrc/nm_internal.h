@@ -144,6 +144,7 @@ struct ConvParams {
     // launch-time divisors as multiply-shift pairs (x / d = umulhi(x, mul) >> shift, mul == 0: d == 1)
     unsigned howo_mul, howo_shift, wo_mul, wo_shift;
     int run_gr, run_d; // kind 4: granules per kernel-row run, lead-in elements of a run
+    unsigned gr_mul, gr_shift, cin_mul, cin_shift;   // kind 4: multiply-shift pairs for / run_gr and / Cin
     unsigned x_elems;  // elements of x
     unsigned x_bytes;  // size of x in bytes (< 2 GiB), the range of the buffer descriptor
     unsigned wfrag_bytes, rows_bytes;
