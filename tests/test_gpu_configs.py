@@ -78,6 +78,22 @@ def test_config4_resnet50_batch64_fp32_sampled(part):
             assert norm_err(y[31:32].cpu().numpy(), ref) <= FP32_TOL, layer.name
 
 
+def test_config4_resnet50_batch64_large_groups_sampled():
+    """Section 3.1's adaptive setting at full size: one group per kernel tap (M = Cin, half
+    kept) and one group per row of the weight matrix (M = K), tuned launch configuration."""
+    stack = wl.resnet50_stack()
+    names = ("s2b1_conv2_3x3", "s3b1_conv1_1x1", "s4b1_conv3_1x1")
+    picked = [l for l in stack if l.name in names]
+    assert len(picked) == len(names)
+    for mode in ("cin", "row"):
+        for layer in wl.with_large_groups(picked, mode):
+            if mode == "row" and layer.K > 16384:
+                continue   # beyond the group size the library accepts
+            i = [l.name for l in stack].index(layer.name)
+            say(f"config 4 fp32 batch 64 groups per {mode} layer {i} {layer.name} {layer.n}:{layer.m}")
+            _check_sampled(layer, 64, 4100 + i, False)
+
+
 def test_config4_resnet50_batch64_bf16_sampled():
     stack = wl.resnet50_stack()
     shapes = wl.unique_shapes(stack)
