@@ -67,22 +67,29 @@ __device__ inline f4 load4(const bf16_t* p)
 __device__ inline float load1(const float* p) { return *p; }
 __device__ inline float load1(const bf16_t* p) { return __uint_as_float((unsigned)p->v << 16); }
 
+// max(v, 0) as one instruction per value (fmaxf costs a second one that quiets NaNs first;
+// the hardware maximum already returns the number when the other operand is a NaN)
+__device__ inline float relu1(float v)
+{
+    float r;
+    asm("v_max_f32_e32 %0, 0, %1" : "=v"(r) : "v"(v));
+    return r;
+}
+__device__ inline f4 relu4(f4 v) { return f4{relu1(v.x), relu1(v.y), relu1(v.z), relu1(v.w)}; }
+
 // Tail of every epilogue: optional residual (a tensor shaped like the output,
 // added before the activation), ReLU, cast, store.
 // (offsets are element counts below 2^31, so 32-bit arithmetic is enough)
 template <typename TOUT> __device__ inline void emit4(const ConvParams& p, TOUT* y, unsigned off, f4 v)
 {
     if (p.res) v = v + load4(reinterpret_cast<const TOUT*>(p.res) + off);
-    if (p.relu) {
-        v.x = fmaxf(v.x, 0.f); v.y = fmaxf(v.y, 0.f);
-        v.z = fmaxf(v.z, 0.f); v.w = fmaxf(v.w, 0.f);
-    }
+    if (p.relu) v = relu4(v);
     store4(y + off, v);
 }
 template <typename TOUT> __device__ inline void emit1(const ConvParams& p, TOUT* y, unsigned off, float v)
 {
     if (p.res) v += load1(reinterpret_cast<const TOUT*>(p.res) + off);
-    if (p.relu) v = fmaxf(v, 0.f);
+    if (p.relu) v = relu1(v);
     store1(y + off, v);
 }
 
@@ -108,33 +115,31 @@ template <typename TOUT>
 __device__ inline void tile_put4(const ConvParams& p, char* dst, unsigned goff, bool live, f4 v)
 {
     if (p.res && live) v = v + load4(reinterpret_cast<const TOUT*>(p.res) + goff);
-    if (p.relu) {
-        v.x = fmaxf(v.x, 0.f); v.y = fmaxf(v.y, 0.f);
-        v.z = fmaxf(v.z, 0.f); v.w = fmaxf(v.w, 0.f);
-    }
+    if (p.relu) v = relu4(v);
     store4(reinterpret_cast<TOUT*>(dst), v);
 }
-// the tile [BP][WGC] (first pixel p0, first channel co0) from LDS to the NHWC output;
-// pix(r) is the pixel, inside the workgroup's range, that LDS row r holds
-struct TileRowIsPixel {
-    __device__ int operator()(int r) const { return r; }
-};
-template <typename TOUT, int BP, int WGC, typename PIX = TileRowIsPixel>
-__device__ inline void tile_flush(const ConvParams& p, const char* tile, int p0, int co0, PIX pix = PIX())
+// the tile [BP][WGC] (first pixel p0, first channel co0) from LDS to the NHWC output: a thread
+// keeps its 16-byte column and walks down the rows, so one compare and one add per store
+template <typename TOUT, int BP, int WGC>
+__device__ inline void tile_flush(const ConvParams& p, const char* tile, int p0, int co0)
 {
     constexpr int CPG = 16 / (int)sizeof(TOUT);      // channels per 16-byte granule
     constexpr int GPR = WGC / CPG;                   // granules per pixel
     constexpr int PITCH = tile_pitch<TOUT>(WGC);
-    constexpr int NG = (BP * GPR + 255) / 256;
-    TOUT* __restrict__ y = reinterpret_cast<TOUT*>(p.y);
+    static_assert(GPR <= 256 && 256 % GPR == 0, "a row's granules divide the workgroup");
+    constexpr int RSTEP = 256 / GPR;                 // rows covered by one pass of the workgroup
+    constexpr int NG = (BP + RSTEP - 1) / RSTEP;
+    const int r0 = (int)threadIdx.x / GPR, cg = (int)threadIdx.x % GPR;
+    const int co = co0 + cg * CPG;
+    if (co >= p.Cout) return;
+    TOUT* __restrict__ y = reinterpret_cast<TOUT*>(p.y) + ((unsigned)(p0 + r0) * (unsigned)p.Cout + (unsigned)co);
+    const char* src = tile + r0 * PITCH + cg * 16;
+    const int rows_left = p.P - p0 - r0;             // rows r0 + k RSTEP with k RSTEP < rows_left exist
 #pragma unroll
     for (int it = 0; it < NG; ++it) {
-        const int g = (int)threadIdx.x + it * 256;
-        const int r = g / GPR, cg = g % GPR;
-        const int pp = p0 + pix(r), co = co0 + cg * CPG;
-        if ((BP * GPR % 256 == 0 || r < BP) && pp < p.P && co < p.Cout) {
-            const u4v v = *reinterpret_cast<const u4v*>(tile + r * PITCH + cg * 16);
-            *reinterpret_cast<u4v*>(y + ((unsigned)pp * (unsigned)p.Cout + (unsigned)co)) = v;
+        if ((BP % RSTEP == 0 || r0 + it * RSTEP < BP) && it * RSTEP < rows_left) {
+            const u4v v = *reinterpret_cast<const u4v*>(src + it * (RSTEP * PITCH));
+            *reinterpret_cast<u4v*>(y + (unsigned)(it * RSTEP) * (unsigned)p.Cout) = v;
         }
     }
 }
@@ -540,11 +545,6 @@ __global__ __launch_bounds__(256) void nm_conv_kernel(const ConvParams p)
         if (R >= 2 && b < 4 * NF + 2) return OFF2 + n * 2 + (b - 4 * NF);
         return OFF1 + n;
     };
-    auto row_of = [&](int b) {     // LDS row of the output tile that holds this lane's pixel of block b
-        if (b < 4 * NF) return (b >> 2) * 64 + (b & 3) * 16 + n;
-        if (R >= 2 && b < 4 * NF + 2) return OFF2 + (b - 4 * NF) * 16 + n;
-        return OFF1 + n;
-    };
     constexpr int WGC = WC * NJ * 16;     // output channels of the workgroup
     if (WGC * (int)sizeof(TOUT) >= 128 && tile_out_ok<TOUT>(p)) {
         // through the LDS tile (every wavefront is past its last strip read: the chunk ends with a barrier)
@@ -557,24 +557,15 @@ __global__ __launch_bounds__(256) void nm_conv_kernel(const ConvParams p)
             const bool row_live = rb < p.n_rowblocks && co < p.Cout;
 #pragma unroll
             for (int b = 0; b < NBLK; ++b) {
-                const int pp = p0 + wpix + pixel_of(b);
-                // the lanes of one store go to consecutive LDS rows (conflict-free with the odd pitch)
-                const int row = wpix + row_of(b);
-                tile_put4<TOUT>(p, tile + row * PITCH + ((wcx * NJ + jj) * 16 + q * 4) * (int)sizeof(TOUT),
+                const int pl = wpix + pixel_of(b);
+                const int pp = p0 + pl;
+                tile_put4<TOUT>(p, tile + pl * PITCH + ((wcx * NJ + jj) * 16 + q * 4) * (int)sizeof(TOUT),
                                 (unsigned)pp * (unsigned)p.Cout + (unsigned)co, row_live && pp < p.P,
                                 acc[jj][b]);   // the bias is already in the accumulator
             }
         }
         __syncthreads();
-        auto pixel_of_row = [](int r) {   // inverse of row_of over the workgroup's rows
-            const int w = r / BPW, rr = r - w * BPW;
-            int pl;
-            if (rr < NF * 64) pl = (rr & ~63) + (rr & 15) * 4 + ((rr >> 4) & 3);
-            else if (R >= 2 && rr < OFF1) pl = OFF2 + ((rr - OFF2) & 15) * 2 + ((rr - OFF2) >> 4);
-            else pl = rr;
-            return w * BPW + pl;
-        };
-        tile_flush<TOUT, BP, WGC>(p, tile, p0, cblock * WGC, pixel_of_row);
+        tile_flush<TOUT, BP, WGC>(p, tile, p0, cblock * WGC);
         return;
     }
 #pragma unroll
