@@ -791,37 +791,60 @@ int nm_autotune(nm_dtype_t xdt, int b, int h, int w, int cin, const nm_packed_t*
     int best_v = -1;
     float best = 0.f;
     int turn = 0;
+    int rc_t = NM_OK;
+    // one timed group of `reps` launches of variant v on fresh tensor sets: ms per launch, < 0 on error
+    auto time_group = [&](int v, int reps) -> float {
+        const VariantDesc& d = variant_desc(v);
+        const Prepack* pp = find_prepack(wp, d, (pw * wp->cin) % 2);
+        ConvParams p;
+        if (hipEventRecord(e0, s) != hipSuccess) { rc_t = NM_ERR_HIP; return -1.f; }
+        for (int i = 0; i < reps; ++i) {
+            char* set = dpool + (xbytes + ybytes) * (turn++ % nbuf);
+            fill_params(p, d, *pp, wp, set, set + xbytes, dbias, b, h, w, g, sh, sw, ph, pw, dh, dw, relu, es);
+            rc_t = launch_conv(v, xdt, ydt, p, s);
+            if (rc_t != NM_OK) return -1.f;
+        }
+        float ms = 0.f;
+        if (hipEventRecord(e1, s) != hipSuccess || hipEventSynchronize(e1) != hipSuccess ||
+            hipEventElapsedTime(&ms, e0, e1) != hipSuccess) {
+            set_error("timing a tuning candidate failed");
+            rc_t = NM_ERR_HIP;
+            return -1.f;
+        }
+        return ms / reps;
+    };
+    // First pass: every legal variant, one warm-up launch (code object, attributes) and the
+    // median of three groups.  Second pass: the five fastest again, interleaved so that clock
+    // and cache drift hit them alike, median of seven groups -- single passes were seen to
+    // pick variants a few percent off the best from run to run.
+    std::vector<std::pair<float, int>> first;
     for (int v = 0; v < variant_count(); ++v) {
         if (!variant_legal(v, wp, xdt, &ra)) continue;
-        const VariantDesc& d = variant_desc(v);
-        ConvParams p;
-        auto launch_next = [&]() {
-            char* set = dpool + (xbytes + ybytes) * (turn++ % nbuf);
-            fill_params(p, d, *find_prepack(wp, d, (pw * wp->cin) % 2), wp, set, set + xbytes, dbias, b, h, w, g, sh, sw, ph, pw,
-                        dh, dw, relu, es);
-            return launch_conv(v, xdt, ydt, p, s);
-        };
-        // warm-up (code object, attributes), then the median of 5 timed groups
-        rc = launch_next();
-        if (rc != NM_OK) { cleanup(); return rc; }
-        NM_TRY(hipStreamSynchronize(s), NM_ERR_HIP);
-        float t[5];
-        const int reps = 3;
-        for (int r = 0; r < 5; ++r) {
-            NM_TRY(hipEventRecord(e0, s), NM_ERR_HIP);
-            for (int i = 0; i < reps; ++i) {
-                rc = launch_next();
-                if (rc != NM_OK) { cleanup(); return rc; }
-            }
-            NM_TRY(hipEventRecord(e1, s), NM_ERR_HIP);
-            NM_TRY(hipEventSynchronize(e1), NM_ERR_HIP);
-            NM_TRY(hipEventElapsedTime(&t[r], e0, e1), NM_ERR_HIP);
-            t[r] /= reps;
+        if (time_group(v, 1) < 0.f) { cleanup(); return rc_t; }
+        float t[3];
+        for (int r = 0; r < 3; ++r)
+            if ((t[r] = time_group(v, 3)) < 0.f) { cleanup(); return rc_t; }
+        std::sort(t, t + 3);
+        first.push_back(std::make_pair(t[1], v));
+    }
+    std::sort(first.begin(), first.end());
+    const int finalists = (int)std::min<size_t>(5, first.size());
+    std::vector<std::vector<float>> again(finalists);
+    for (int r = 0; r < 7 && finalists > 1; ++r)
+        for (int c = 0; c < finalists; ++c) {
+            const float t = time_group(first[c].second, 4);
+            if (t < 0.f) { cleanup(); return rc_t; }
+            again[c].push_back(t);
         }
-        std::sort(t, t + 5);
-        if (best_v < 0 || t[2] < best) {
-            best_v = v;
-            best = t[2];
+    for (int c = 0; c < finalists; ++c) {
+        float t = first[c].first;
+        if (!again[c].empty()) {
+            std::sort(again[c].begin(), again[c].end());
+            t = again[c][again[c].size() / 2];
+        }
+        if (best_v < 0 || t < best) {
+            best_v = first[c].second;
+            best = t;
         }
     }
 #undef NM_TRY
