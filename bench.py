@@ -255,7 +255,7 @@ def main():
     roofline.update({
         # HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled by what the same
         # counters read for the 1 GiB device copy above (profiles/); measured for the default workload only
-        "traffic": {"f32": 111.8e6, "bf16": 54.7e6}[args.dtype] if headline else None,
+        "traffic": {"f32": 112.5e6, "bf16": 54.7e6}[args.dtype] if headline else None,
         "kernel": "nm_conv_sp16_kernel" if bf16 else "nm_conv_kernel", "launches_per_step": len(layers),
         "avg_launch_ms": kern_ms / len(layers),
         "frac_of_binding_roofline_per_layer": tmin_ms / kern_ms,
