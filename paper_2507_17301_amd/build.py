@@ -24,6 +24,8 @@ LIB = os.path.join(PKG, "libnmconv.so")
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [
     "-O3", "--offload-arch=gfx950", "-fPIC", "-std=c++17", "-Wall", "-Wno-unused-function",
+    # ragged-tail loops of some tile shapes keep a run-time trip count; their unroll hint is best-effort
+    "-Wno-pass-failed",
     # the compiler must not form packed fp32 instructions on this target
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
     # MFMA accumulators stay in ordinary VGPRs: with the AGPR form the register
