@@ -243,24 +243,29 @@ def main():
         f"sum of per-layer lower bounds {tmin_ms:.3f} ms -> {tmin_ms / kern_ms * 100:.1f}% of binding roofline")
 
     # The convolution kernel, all launches of a step taken together.  fp32 is bound by the
-    # fp32 matrix cores (2*P*K'*Cout flops per launch over the summed durations); with bf16
-    # tensors nearly every layer sits below the ridge, so the bound is HBM (algorithmic bytes
-    # per launch over the summed durations).
+    # fp32 matrix cores (2*P*K'*Cout flops per launch); with bf16 tensors nearly every layer
+    # sits below the ridge, so the bound is HBM (algorithmic bytes per launch).  The average
+    # launch duration comes from the timed region itself: the launches of a step run back to
+    # back on one stream, so step time / launches is the kernel's duration plus whatever gap
+    # the launches leave (an upper bound on the duration; the kernel trace shows no gap).
+    avg_ms = ms_step / len(layers)
     if bf16:
-        roofline = {"bound": "hbm", "achieved": byts / kern_ms / 1e6, "peak": PEAK_HBM_GBS, "unit": "GB/s",
-                    "frac": byts / kern_ms / 1e6 / PEAK_HBM_GBS}
+        roofline = {"bound": "hbm", "achieved": byts / ms_step / 1e6, "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                    "frac": byts / ms_step / 1e6 / PEAK_HBM_GBS}
     else:
-        roofline = {"bound": "mfma", "achieved": eff / kern_ms / 1e9, "peak": PEAK_TFLOPS["f32"],
-                    "unit": "TFLOP/s", "frac": eff / kern_ms / 1e9 / PEAK_TFLOPS["f32"]}
+        roofline = {"bound": "mfma", "achieved": eff / ms_step / 1e9, "peak": PEAK_TFLOPS["f32"],
+                    "unit": "TFLOP/s", "frac": eff / ms_step / 1e9 / PEAK_TFLOPS["f32"]}
     roofline.update({
         # HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled by what the same
         # counters read for the 1 GiB device copy above (profiles/); measured for the default workload only
         "traffic": {"f32": 112.5e6, "bf16": 54.7e6}[args.dtype] if headline else None,
         "kernel": "nm_conv_sp16_kernel" if bf16 else "nm_conv_kernel", "launches_per_step": len(layers),
-        "avg_launch_ms": kern_ms / len(layers),
+        "avg_launch_ms": avg_ms,
+        # with an event after every layer of three extra steps (adds the events' own cost)
+        "avg_launch_ms_event_per_layer": kern_ms / len(layers),
         "frac_of_binding_roofline_per_layer": tmin_ms / kern_ms,
-        "effective_tflops": eff / kern_ms / 1e9,
-        "algorithmic_gbytes_per_step": byts / 1e9, "achieved_gbs": byts / kern_ms / 1e6,
+        "effective_tflops": eff / ms_step / 1e9,
+        "algorithmic_gbytes_per_step": byts / 1e9, "achieved_gbs": byts / ms_step / 1e6,
     })
 
     if args.workload == "sweep":
