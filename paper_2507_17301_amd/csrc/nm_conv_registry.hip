@@ -25,8 +25,13 @@ struct Entry {
 // kind 2: sparse matrix instruction, kind 3: dense instruction on zero-filled weights
 #define NM_ENTRYSP(NB, WP, NJ, CK, SP)                                                          \
     {{"SP" #SP "_NB" #NB "_WP" #WP "_NJ" #NJ "_CK" #CK, 16 * NB * WP, NB, WP, NJ, CK, CK / 64, 1, (SP) ? 2 : 3, 1}, \
-     nullptr, &launch_sp16_t<NB, WP, NJ, CK, (SP) != 0>},
+     nullptr, &launch_sp16_t<NB, WP, NJ, CK, (SP) != 0, false>},
 #define NM_SHAPE_ENTRIESSP(NB, WP, NJ) NMSP_CHUNKS(NM_ENTRYSP, NB, WP, NJ)
+// the same with producer wavefronts (same operand tables, same LDS footprint)
+#define NM_ENTRYSPW(NB, WP, NJ, CK, SP)                                                         \
+    {{"SPW" #SP "_NB" #NB "_WP" #WP "_NJ" #NJ "_CK" #CK, 16 * NB * WP, NB, WP, NJ, CK, CK / 64, 1, (SP) ? 2 : 3, 1}, \
+     nullptr, &launch_sp16_t<NB, WP, NJ, CK, (SP) != 0, true>},
+#define NM_SHAPE_ENTRIESSPW(NB, WP, NJ) NMSPW_CHUNKS(NM_ENTRYSPW, NB, WP, NJ)
 
 // kind 4: contiguous kernel-row runs
 #define NM_ENTRYRUN(NB, WP, NJ, KS)                                                             \
@@ -41,7 +46,7 @@ struct Entry {
 #define NM_SHAPE_ENTRIESVAR(NB, WP, NJ) NMVAR_CHUNKS(NM_ENTRYVAR, NB, WP, NJ)
 
 const Entry kEntries[] = {NM_SHAPES(NM_SHAPE_ENTRIES) NM_SCALAR_VARIANTS(NM_ENTRY)
-                          NM16_SHAPES(NM_SHAPE_ENTRIES16) NMSP_SHAPES(NM_SHAPE_ENTRIESSP)
+                          NM16_SHAPES(NM_SHAPE_ENTRIES16) NMSP_SHAPES(NM_SHAPE_ENTRIESSP) NMSPW_SHAPES(NM_SHAPE_ENTRIESSPW)
                           NMRUN_SHAPES(NM_SHAPE_ENTRIESRUN) NMVAR_SHAPES(NM_SHAPE_ENTRIESVAR)};
 constexpr int kCount = (int)(sizeof(kEntries) / sizeof(kEntries[0]));
 }  // namespace

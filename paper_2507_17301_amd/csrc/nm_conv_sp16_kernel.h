@@ -64,8 +64,14 @@ __device__ inline int sp16_swz(int row, int CK) { return CK == 64 ? ((row & 7) ^
 
 typedef __attribute__((address_space(3))) void* lds_ptr_t;
 
-template <int NBLK, int WP, int NJ, int CK, bool SPARSE>
-__global__ __launch_bounds__(256) void nm_conv_sp16_kernel(const ConvParams p)
+//
+// SPEC = true adds four producer wavefronts to the workgroup (512 threads): they issue every
+// load of the ring and nothing else, the other four contract and never touch global memory
+// until the epilogue.  A wave-wide load into LDS occupies the CU's memory path for 16 clocks
+// and stalls its wavefront while the path is backed up, so a wavefront that does both jobs
+// alternates between them; split, the two overlap.  Both roles execute the same barriers.
+template <int NBLK, int WP, int NJ, int CK, bool SPARSE, bool SPEC>
+__global__ __launch_bounds__(SPEC ? 512 : 256) void nm_conv_sp16_kernel(const ConvParams p)
 {
     constexpr int BPW = 16 * NBLK;
     constexpr int BP = BPW * WP;
@@ -81,7 +87,9 @@ __global__ __launch_bounds__(256) void nm_conv_sp16_kernel(const ConvParams p)
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wave_id = __builtin_amdgcn_readfirstlane(tid >> 6);   // 0..3; 4..7 are the producers
+    const bool producer = SPEC && wave_id >= 4;
+    const int wave = SPEC ? (wave_id & 3) : wave_id;                // position among the four of its role
     const int q = lane >> 4;
     const int n = lane & 15;
 
@@ -234,9 +242,37 @@ __global__ __launch_bounds__(256) void nm_conv_sp16_kernel(const ConvParams p)
         if (fast && p.bias && rb < p.n_rowblocks && rit < p.tile && co < p.Cout)
             bb[jj] = *reinterpret_cast<const f4*>(p.bias + co);
     }
-    retap();
-    fetch_stage(0);
-    if (p.nchunks > 1) fetch_stage(1);
+    constexpr int WGC = WC * NJ * 16;            // output channels of the workgroup
+    // whole 128-byte lines through an LDS tile (two more barriers), or stores straight from the accumulators
+    const bool tile_path = WGC * 2 >= 128 && fast && tile_out_ok<bf16_t>(p);
+    if (!SPEC || producer) {
+        retap();
+        fetch_stage(0);
+        if (p.nchunks > 1) fetch_stage(1);
+    }
+    if constexpr (SPEC) {
+        if (producer) {
+            // the producer's whole life: per chunk, wait until its own loads of that chunk have
+            // landed, meet the consumers at the barrier, then refill the stage they have just left
+            const bool short_w = (NW % 4 != 0) && (wave + 4 * (NIT - 1) >= NW);
+            int wst = D - 1;
+            for (int c = 0; c < p.nchunks; ++c) {
+                if (c + 1 < p.nchunks) {
+                    if (short_w) NM_WAIT_VMCNT(NL - 1); else NM_WAIT_VMCNT(NL);
+                } else {
+                    NM_WAIT_VMCNT(0);
+                }
+                __builtin_amdgcn_s_barrier();
+                if (c + 2 < p.nchunks) fetch_stage(wst);
+                wst = wst + 1 == D ? 0 : wst + 1;
+            }
+            if (tile_path) {   // the consumers' two epilogue barriers
+                __syncthreads();
+                __syncthreads();
+            }
+            return;
+        }
+    }
 
     // the accumulators start from the bias (zero where there is none or rows are handled one by one)
     f4 acc[NJ][NBLK];
@@ -261,10 +297,12 @@ __global__ __launch_bounds__(256) void nm_conv_sp16_kernel(const ConvParams p)
     auto chunk = [&](int c) {
         // all of this wave's loads for chunk c have landed once at most the next
         // stage's loads (if there is a next chunk) are outstanding
-        if (c + 1 < p.nchunks) {
-            if (short_wave) NM_WAIT_VMCNT(NL - 1); else NM_WAIT_VMCNT(NL);
-        } else {
-            NM_WAIT_VMCNT(0);
+        if constexpr (!SPEC) {
+            if (c + 1 < p.nchunks) {
+                if (short_wave) NM_WAIT_VMCNT(NL - 1); else NM_WAIT_VMCNT(NL);
+            } else {
+                NM_WAIT_VMCNT(0);
+            }
         }
         // A bare barrier: the fences of __syncthreads() would wait for every load
         // into LDS that is in flight, i.e. for the stages being filled ahead.  What
@@ -272,7 +310,9 @@ __global__ __launch_bounds__(256) void nm_conv_sp16_kernel(const ConvParams p)
         // landed (the wait above), and its LDS reads of chunk c - 1 have returned
         // (each was waited for before the matrix instruction that used it).
         __builtin_amdgcn_s_barrier();
-        if (c + 2 < p.nchunks) fetch_stage(wstage);
+        if constexpr (!SPEC) {
+            if (c + 2 < p.nchunks) fetch_stage(wstage);
+        }
 
         const unsigned sbase = lds0 + (unsigned)(rstage * STAGE);
         u4v a[NJ][KS][AH];
@@ -352,8 +392,7 @@ __global__ __launch_bounds__(256) void nm_conv_sp16_kernel(const ConvParams p)
 
     // ---- epilogue: bias, ReLU, round to bf16, NHWC store ------------------------
     bf16_t* __restrict__ y = reinterpret_cast<bf16_t*>(p.y);
-    constexpr int WGC = WC * NJ * 16;            // output channels of the workgroup
-    if (WGC * 2 >= 128 && fast && tile_out_ok<bf16_t>(p)) {
+    if (tile_path) {
         // whole 128-byte lines through the LDS tile, once every wavefront is past its last strip read
         constexpr int PITCH = tile_pitch<bf16_t>(WGC);
         __syncthreads();
@@ -408,10 +447,10 @@ __global__ __launch_bounds__(256) void nm_conv_sp16_kernel(const ConvParams p)
     }
 }
 
-template <int NBLK, int WP, int NJ, int CK, bool SPARSE>
+template <int NBLK, int WP, int NJ, int CK, bool SPARSE, bool SPEC>
 int launch_sp16_t(const ConvParams& p, hipStream_t s)
 {
-    auto kern = nm_conv_sp16_kernel<NBLK, WP, NJ, CK, SPARSE>;
+    auto kern = nm_conv_sp16_kernel<NBLK, WP, NJ, CK, SPARSE, SPEC>;
     constexpr size_t stage = sp16_stage_bytes(16 * NBLK * WP, CK, NJ, SPARSE);
     // the most this kernel may ever be launched with: the full ring, or what the CU has
     constexpr size_t ring = kSp16Stages * stage > out_tile_bytes(16 * NBLK * WP, (4 / WP) * NJ * 16, 2)
@@ -431,7 +470,7 @@ int launch_sp16_t(const ConvParams& p, hipStream_t s)
         set_error("internal: LDS %zu bytes exceed the CU's 160 KB", lds);
         return NM_ERR_UNSUPPORTED;
     }
-    hipLaunchKernelGGL(kern, dim3(p.wg_per_xcd * 8), dim3(256), lds, s, p);
+    hipLaunchKernelGGL(kern, dim3(p.wg_per_xcd * 8), dim3(SPEC ? 512 : 256), lds, s, p);
     NM_HIP_CHECK(hipGetLastError());
     return NM_OK;
 }

@@ -59,6 +59,14 @@
     Y(NB, WP, NJ, 64, 1) Y(NB, WP, NJ, 128, 1) Y(NB, WP, NJ, 256, 1) \
     Y(NB, WP, NJ, 64, 0) Y(NB, WP, NJ, 128, 0) Y(NB, WP, NJ, 256, 0)
 
+// The same kernels with four producer wavefronts that issue the loads (512 threads).
+// X(NBLK, WP, NJ)
+#define NMSPW_SHAPES(X) X(8, 1, 2) X(4, 1, 2) X(4, 2, 4) X(4, 1, 4) X(4, 2, 2) X(6, 1, 2) X(2, 1, 2) X(2, 2, 4)
+// Y(NBLK, WP, NJ, CK, SP)
+#define NMSPW_CHUNKS(Y, NB, WP, NJ)                                  \
+    Y(NB, WP, NJ, 64, 1) Y(NB, WP, NJ, 128, 1) Y(NB, WP, NJ, 256, 1) \
+    Y(NB, WP, NJ, 64, 0) Y(NB, WP, NJ, 128, 0) Y(NB, WP, NJ, 256, 0)
+
 // bf16 kernel for layers with very few input channels (contiguous kernel-row
 // runs, one chunk of KS 64-element k-steps).
 // X(NBLK, WP, NJ)
