@@ -148,6 +148,9 @@ def build(jobs: int = 8, force: bool = True) -> str:
     r = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
     if r.returncode != 0:
         raise RuntimeError("link failed:\n" + r.stdout)
+    # a kernel whose host stub was not emitted only shows when the library is loaded
+    import ctypes
+    ctypes.CDLL(LIB)
     return LIB
 
 
