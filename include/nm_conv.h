@@ -181,7 +181,9 @@ int nm_im2col(const void* x_dev, nm_dtype_t dtype, int b, int h, int w, int cin,
  * input; a ring of input/output sets of about 768 MB so that, as inside a
  * network, no launch finds its tensors in the last-level cache), times it with
  * HIP events on `hip_stream`, stores the winner in the process-wide cache keyed
- * by (shape, N:M, T, dtypes) and returns it.
+ * by (shape, N:M, T, dtypes, bias / activation flags, the device's name and CU
+ * count, and which operand tables the handle carries -- layers of one shape whose
+ * kept sets need different k-steps per chunk do not share an entry) and returns it.
  * Synchronous.  A cached shape returns immediately with the cached result.
  *   chosen_variant, best_ms   may be NULL
  */
@@ -216,7 +218,9 @@ int nm_autotune_tile(const float* w_host, int cout, int kh, int kw, int cin, int
                      int relu, nm_dtype_t y_dtype, void* hip_stream,
                      nm_packed_t** out, int* best_tile, float* ms_per_candidate);
 
-/* Tuning cache: text file, one line per shape.  Loading merges into the cache. */
+/* Tuning cache: text file, one line per entry; the first line names the device it was
+ * written on.  Loading merges into the cache; entries made on another kind of device
+ * are kept but never match. */
 int nm_cache_save(const char* path);
 int nm_cache_load(const char* path);
 int nm_cache_clear(void);
@@ -225,6 +229,11 @@ int nm_cache_size(void);
 /* Test hook: variant >= 0 makes every nm_conv2d use that variant (an illegal
  * one for a shape gives NM_ERR_UNSUPPORTED); -1 restores the normal choice. */
 int nm_force_variant(int variant_or_minus1);
+
+/* The variant id the calling thread's last successful nm_conv2d / nm_conv2d_res launched
+ * (-1 before the first): what actually ran, whether it came from the tuning cache, the
+ * test hook or the default. */
+int nm_last_variant(void);
 
 /* Whether `variant` can run this layer (1), cannot (0), or bad arguments (<0). */
 int nm_variant_legal(int variant, const nm_packed_t* wp, nm_dtype_t x_dtype, nm_dtype_t y_dtype);

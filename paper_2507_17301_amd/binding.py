@@ -43,6 +43,7 @@ def lib():
         pi = ctypes.POINTER(ctypes.c_int)
         L.nm_last_error.restype = ctypes.c_char_p
         L.nm_variant_count.restype = ci
+        L.nm_last_variant.restype = ci
         L.nm_variant_name.argtypes = [ci]
         L.nm_variant_name.restype = ctypes.c_char_p
         L.nm_prune.argtypes = [vp, ci, ci, ci, ci, ci, ci, ci, ci, ctypes.POINTER(vp)]
@@ -104,14 +105,28 @@ class Packed:
         self.n, self.m, self.tile, self.value_dtype = n, m, tile, value_dtype
         self.K = kh * kw * cin
 
+    def free(self):
+        """Release the handle now (idempotent)."""
+        h, self.handle = getattr(self, "handle", None), None
+        if h and _lib is not None:
+            _lib.nm_packed_free(h)
+
     def __del__(self):
-        if getattr(self, "handle", None):
-            lib().nm_packed_free(self.handle)
-            self.handle = None
+        # at interpreter shutdown the module globals may already be gone; the
+        # process is ending then and the driver reclaims the device memory
+        try:
+            self.free()
+        except Exception:
+            pass
 
 
 def nm_variant_count() -> int:
     return lib().nm_variant_count()
+
+
+def nm_last_variant() -> int:
+    """Variant id launched by this thread's last successful nm_conv2d / nm_conv2d_res."""
+    return lib().nm_last_variant()
 
 
 def nm_variant_name(v: int) -> Optional[str]:
@@ -172,6 +187,13 @@ def out_shape(x_shape, wp: Packed, stride, pad, dil):
     return (b, ho, wo, wp.cout)
 
 
+def _check_out(y, shp, x):
+    """A caller-supplied output must cover exactly what the kernel will write (the
+    library itself checks the dtype pair)."""
+    if tuple(y.shape) != tuple(shp) or not y.is_cuda or y.device != x.device or not y.is_contiguous():
+        raise ValueError(f"y must be a contiguous device tensor of shape {tuple(shp)} on {x.device}")
+
+
 def nm_conv2d(x, wp: Packed, bias=None, stride=1, pad=0, dil=1, relu=False, y=None, stream=None):
     """x: device tensor NHWC [B,H,W,Cin] (fp32 or bf16, contiguous); bias: device
     fp32 [Cout] or None; y: optional preallocated output.  Enqueues on `stream`
@@ -183,11 +205,13 @@ def nm_conv2d(x, wp: Packed, bias=None, stride=1, pad=0, dil=1, relu=False, y=No
     sh, sw = _pair(stride)
     ph, pw = _pair(pad)
     dh, dw = _pair(dil)
+    shp = out_shape(x.shape, wp, stride, pad, dil)
+    if min(shp) < 1:
+        raise NMError(-2, "output would be empty")
     if y is None:
-        shp = out_shape(x.shape, wp, stride, pad, dil)
-        if min(shp) < 1:
-            raise NMError(-2, "output would be empty")
         y = torch.empty(shp, dtype=x.dtype, device=x.device)
+    else:
+        _check_out(y, shp, x)
     bptr = None
     if bias is not None:
         if bias.dtype != torch.float32 or not bias.is_cuda or not bias.is_contiguous():
@@ -215,6 +239,8 @@ def nm_conv2d_res(x, wp: Packed, residual, bias=None, stride=1, pad=0, dil=1, re
         raise NMError(-2, "output would be empty")
     if y is None:
         y = torch.empty(shp, dtype=x.dtype, device=x.device)
+    else:
+        _check_out(y, shp, x)
     rptr = None
     if residual is not None:
         if (tuple(residual.shape) != tuple(shp) or residual.dtype != y.dtype or not residual.is_cuda

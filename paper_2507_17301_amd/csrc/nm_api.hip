@@ -14,6 +14,7 @@
 namespace nm {
 
 static thread_local char g_err[512] = "";
+static thread_local int g_last_variant = -1;
 
 void set_error(const char* fmt, ...)
 {
@@ -46,8 +47,9 @@ namespace {
 constexpr int kMaxLdsBytes = 160 * 1024;
 constexpr int kNumCU = 256;
 
+constexpr int kKeyInts = 24;
 struct ShapeKey {
-    int v[21];
+    int v[kKeyInts];
     bool operator<(const ShapeKey& o) const { return memcmp(v, o.v, sizeof(v)) < 0; }
 };
 struct CacheVal {
@@ -59,12 +61,59 @@ std::mutex g_mu;
 std::map<ShapeKey, CacheVal> g_cache;
 int g_forced = -1;
 
+// 31-bit FNV-1a
+unsigned fnv(unsigned h, const void* data, size_t n)
+{
+    const unsigned char* b = (const unsigned char*)data;
+    for (size_t i = 0; i < n; ++i) h = (h ^ b[i]) * 16777619u;
+    return h;
+}
+
+// Identity of a device for the tuning cache: a timing taken on one kind of GPU says
+// nothing about another.  Name, architecture string and CU count, hashed; kept per ordinal.
+struct DeviceId {
+    int hash = 0;
+    char name[128] = "";
+};
+const DeviceId* device_id(int dev)
+{
+    static std::mutex mu;
+    static std::map<int, DeviceId> ids;
+    std::lock_guard<std::mutex> lk(mu);
+    auto it = ids.find(dev);
+    if (it != ids.end()) return &it->second;
+    hipDeviceProp_t prop;
+    if (hipGetDeviceProperties(&prop, dev) != hipSuccess) return nullptr;
+    DeviceId id;
+    snprintf(id.name, sizeof(id.name), "%s|%s|%dCU", prop.name, prop.gcnArchName, prop.multiProcessorCount);
+    for (char* c = id.name; *c; ++c)
+        if (*c == ' ' || *c == '\n') *c = '_';   // one token in the cache file
+    id.hash = (int)(fnv(2166136261u, id.name, strlen(id.name)) & 0x7fffffffu);
+    return &ids.emplace(dev, id).first->second;
+}
+
+// Which variants may run a layer depends on its weights, not only on its shape: the
+// k-steps per chunk its kept sets need (groups wider than a chunk spread unevenly) and
+// which operand tables were built.  Two layers of one shape that differ there must not
+// share a cache entry.
+int prepack_signature(const nm_packed* wp)
+{
+    unsigned h = 2166136261u;
+    for (const Prepack& pp : wp->prepacks) {
+        const int t[5] = {pp.kind, pp.geom.CK, pp.geom.vec, pp.SPC, pp.par};
+        h = fnv(h, t, sizeof(t));
+    }
+    return (int)(h & 0x7fffffffu);
+}
+
 ShapeKey make_key(nm_dtype_t xdt, nm_dtype_t ydt, int b, int h, int w, const nm_packed* wp,
-                  int sh, int sw, int ph, int pw, int dh, int dw)
+                  int sh, int sw, int ph, int pw, int dh, int dw, int has_bias, int relu)
 {
     ShapeKey k;
-    const int vals[21] = {(int)xdt, (int)ydt, b, h, w, wp->cin, wp->cout, wp->kh, wp->kw,
-                          sh, sw, ph, pw, dh, dw, wp->n, wp->m, wp->tile, (int)wp->value_dtype, 0, 0};
+    const DeviceId* id = device_id(wp->device);
+    const int vals[kKeyInts] = {(int)xdt, (int)ydt, b, h, w, wp->cin, wp->cout, wp->kh, wp->kw,
+                                sh, sw, ph, pw, dh, dw, wp->n, wp->m, wp->tile, (int)wp->value_dtype,
+                                has_bias ? 1 : 0, relu ? 1 : 0, id ? id->hash : 0, wp->sig, 0};
     memcpy(k.v, vals, sizeof(vals));
     return k;
 }
@@ -278,8 +327,7 @@ int check_conv_args(const void* x, nm_dtype_t xdt, int cin, const nm_packed* wp,
         set_error("unsupported dtype pair: input and output must both be fp32 or both bf16");
         return NM_ERR_UNSUPPORTED;
     }
-    const size_t align = xdt == NM_F32 ? 16 : 8;
-    if (((uintptr_t)x % align) || ((uintptr_t)y % align)) {
+    if (((uintptr_t)x % 16) || ((uintptr_t)y % 16)) {
         set_error("x and y must be 16-byte aligned");
         return NM_ERR_ARG;
     }
@@ -501,6 +549,7 @@ int nm_prune(const float* w, int cout, int kh, int kw, int cin, int n, int m, in
         free_packed(wp);
         return NM_ERR_UNSUPPORTED;
     }
+    wp->sig = prepack_signature(wp);
     *out = wp;
     return NM_OK;
 }
@@ -583,6 +632,8 @@ int nm_force_variant(int v)
     return NM_OK;
 }
 
+int nm_last_variant(void) { return g_last_variant; }
+
 int nm_variant_legal(int variant, const nm_packed_t* wp, nm_dtype_t xdt, nm_dtype_t ydt)
 {
     if (!wp || variant < 0 || variant >= variant_count()) {
@@ -599,7 +650,7 @@ static int conv2d_impl(const void* x, nm_dtype_t xdt, int b, int h, int w, int c
 {
     int rc = check_conv_args(x, xdt, cin, wp, y, ydt);
     if (rc != NM_OK) return rc;
-    if (res && ((uintptr_t)res % (ydt == NM_F32 ? 16 : 8))) {
+    if (res && ((uintptr_t)res % 16)) {
         set_error("residual must be 16-byte aligned");
         return NM_ERR_ARG;
     }
@@ -616,18 +667,21 @@ static int conv2d_impl(const void* x, nm_dtype_t xdt, int b, int h, int w, int c
     }
 
     int v = -1;
+    bool forced = false;
     {
+        const ShapeKey key = make_key(xdt, ydt, b, h, w, wp, sh, sw, ph, pw, dh, dw, bias != nullptr, relu);
         std::lock_guard<std::mutex> lk(g_mu);
         if (g_forced >= 0) {
             v = g_forced;
+            forced = true;
         } else {
-            auto it = g_cache.find(make_key(xdt, ydt, b, h, w, wp, sh, sw, ph, pw, dh, dw));
+            auto it = g_cache.find(key);
             if (it != g_cache.end()) v = it->second.variant;
         }
     }
     const RunArgs ra = {w, sw, pw, dw};
     if (v >= 0 && !variant_legal(v, wp, xdt, &ra)) {
-        if (g_forced >= 0) {
+        if (forced) {
             set_error("variant %d (%s) cannot run this layer", v, nm_variant_name(v));
             return NM_ERR_UNSUPPORTED;
         }
@@ -643,7 +697,9 @@ static int conv2d_impl(const void* x, nm_dtype_t xdt, int b, int h, int w, int c
     fill_params(p, d, *find_prepack(wp, d, (pw * wp->cin) % 2), wp, x, y, bias, b, h, w, g, sh, sw, ph, pw,
                 dh, dw, relu, xdt == NM_F32 ? 4 : 2);
     p.res = res;
-    return launch_conv(v, xdt, ydt, p, (hipStream_t)stream);
+    rc = launch_conv(v, xdt, ydt, p, (hipStream_t)stream);
+    if (rc == NM_OK) g_last_variant = v;
+    return rc;
 }
 
 int nm_conv2d(const void* x, nm_dtype_t xdt, int b, int h, int w, int cin, const nm_packed_t* wp,
@@ -737,7 +793,7 @@ int nm_autotune(nm_dtype_t xdt, int b, int h, int w, int cin, const nm_packed_t*
     Geometry g;
     int rc = conv_geometry(b, h, w, wp, sh, sw, ph, pw, dh, dw, xdt == NM_F32 ? 4 : 2, &g);
     if (rc != NM_OK) return rc;
-    const ShapeKey key = make_key(xdt, ydt, b, h, w, wp, sh, sw, ph, pw, dh, dw);
+    const ShapeKey key = make_key(xdt, ydt, b, h, w, wp, sh, sw, ph, pw, dh, dw, has_bias, relu);
     const RunArgs ra = {w, sw, pw, dw};
     {
         std::lock_guard<std::mutex> lk(g_mu);
@@ -914,10 +970,13 @@ int nm_cache_size(void)
     return (int)g_cache.size();
 }
 
-// File format: first line "nmconv-cache 1 <variant count>", then one line per
-// shape: the 21 key integers, the variant's name, its time in ms.  Variants are
-// stored by name so that a cache written by a build with a different variant
-// table cannot select the wrong kernel.
+// File format: first line "nmconv-cache 2 <variant count> <key integers per line>
+// <device of the writer>", then one line per entry: the key integers (shape,
+// dtypes, N:M, tile, bias / activation flags, device identity, operand-table
+// signature), the variant's name, its time in ms.  Variants are stored by name so
+// that a cache written by a build with a different variant table cannot select
+// the wrong kernel; entries tuned on another kind of device stay in the file but
+// never match a key made on this one.
 int nm_cache_save(const char* path)
 {
     if (!path) {
@@ -930,9 +989,11 @@ int nm_cache_save(const char* path)
         return NM_ERR_IO;
     }
     std::lock_guard<std::mutex> lk(g_mu);
-    fprintf(f, "nmconv-cache 1 %d\n", variant_count());
+    int dev = 0;
+    const DeviceId* id = hipGetDevice(&dev) == hipSuccess ? device_id(dev) : nullptr;
+    fprintf(f, "nmconv-cache 2 %d %d %s\n", variant_count(), kKeyInts, id ? id->name : "unknown");
     for (const auto& kv : g_cache) {
-        for (int i = 0; i < 21; ++i) fprintf(f, "%d ", kv.first.v[i]);
+        for (int i = 0; i < kKeyInts; ++i) fprintf(f, "%d ", kv.first.v[i]);
         fprintf(f, "%s %.6f\n", variant_desc(kv.second.variant).name, kv.second.ms);
     }
     const bool ok = fclose(f) == 0;
@@ -954,17 +1015,19 @@ int nm_cache_load(const char* path)
         set_error("cannot open %s", path);
         return NM_ERR_IO;
     }
-    int ver = 0, cnt = 0;
-    if (fscanf(f, "nmconv-cache %d %d", &ver, &cnt) != 2 || ver != 1) {
+    int ver = 0, cnt = 0, nkey = 0;
+    char devname[128];
+    if (fscanf(f, "nmconv-cache %d %d %d %127s", &ver, &cnt, &nkey, devname) != 4 || ver != 2 ||
+        nkey != kKeyInts) {
         fclose(f);
-        set_error("%s is not an nmconv cache file", path);
+        set_error("%s is not an nmconv cache file of this format", path);
         return NM_ERR_IO;
     }
     std::lock_guard<std::mutex> lk(g_mu);
     while (true) {
         ShapeKey k;
         bool ok = true;
-        for (int i = 0; i < 21 && ok; ++i) ok = fscanf(f, "%d", &k.v[i]) == 1;
+        for (int i = 0; i < kKeyInts && ok; ++i) ok = fscanf(f, "%d", &k.v[i]) == 1;
         char name[128];
         float ms = 0.f;
         if (!ok || fscanf(f, "%127s %f", name, &ms) != 2) break;

@@ -113,6 +113,7 @@ struct nm_packed {
     int n_rowblocks;  // n_tiles * rbpt
     nm_dtype_t value_dtype;
     int device;
+    int sig = 0;      // hash of the operand tables built for this handle (part of the tuning-cache key)
     int32_t* d_idx = nullptr;   // [n_tiles][kprime]
     float* d_vals = nullptr;    // [n_tiles][kprime][tile]
     std::vector<int32_t> h_idx; // host copy of d_idx

@@ -1,10 +1,11 @@
 """The benchmark configurations at their full sizes, in the launch configuration
 bench.py times (per-layer tuned variant), against the CPU oracle.
 
-Full outputs are compared where the oracle finishes in seconds (ResNet-18 at
-batch 1, one whole image of selected ResNet-50 layers); elsewhere a few thousand
-sampled outputs per layer, always including the corners of the first and last
-image and the last channel, are computed one by one by the oracle.
+Every unique layer shape of every configuration runs at its full batch through
+the tuned variant.  Configurations 3 and 4 (both dtypes) are compared on the
+whole batch, every output; configuration 5 (batch 256) on every output of the
+images {0, 1, B/2, B-1} -- images are independent, but pixel tiles cross image
+boundaries, hence the first, the last and the middle of the batch.
 """
 import dataclasses
 
@@ -18,6 +19,14 @@ from paper_2507_17301_amd import workloads as wl
 from gpu_util import FP32_TOL, BF16_TOL, say, norm_err, oracle_conv
 
 pytestmark = pytest.mark.gpu
+
+R18 = wl.resnet18_stack()
+R50 = wl.resnet50_stack()
+R101 = wl.resnet101_stack()
+
+
+def _ids(stack):
+    return [f"{stack.index(l):03d}_{l.name}" for l in wl.unique_shapes(stack)]
 
 
 def _run_tuned(layer, batch, x, w, bias, bf16):
@@ -34,6 +43,25 @@ def _run_tuned(layer, batch, x, w, bias, bf16):
     return y, nm.nm_variant_name(v)
 
 
+def _check_images(layer, batch, seed, bf16, images=None):
+    """The layer at its full batch through the tuned variant; every output of the
+    listed images (None = the whole batch) against the oracle."""
+    x, w, bias = wl.make_tensors(layer, batch, seed)
+    y, vname = _run_tuned(layer, batch, x, w, bias, bf16)
+    tol = BF16_TOL if bf16 else FP32_TOL
+    if images is None:
+        images = list(range(batch))
+    images = sorted(set(images))
+    ref = oracle_conv(layer, x[images], w, bias, relu=True, bf16=bf16)
+    import torch
+    got = y[torch.tensor(images, device=y.device)].float().cpu().numpy()
+    assert got.shape == ref.shape
+    for n, b in enumerate(images):
+        err = norm_err(got[n], ref[n])
+        assert err <= tol, f"{layer.name} {vname} image {b}: {err}"
+    return x, w, bias, y
+
+
 def _check_sampled(layer, batch, seed, bf16, npts=2000):
     x, w, bias = wl.make_tensors(layer, batch, seed)
     y, vname = _run_tuned(layer, batch, x, w, bias, bf16)
@@ -48,7 +76,7 @@ def _check_sampled(layer, batch, seed, bf16, npts=2000):
 
 
 def test_config3_resnet18_batch1_full():
-    for i, layer in enumerate(wl.resnet18_stack()):
+    for i, layer in enumerate(R18):
         say(f"config 3 batch 1 layer {i} {layer.name}")
         x, w, bias = wl.make_tensors(layer, 1, 3000 + i)
         y, vname = _run_tuned(layer, 1, x, w, bias, False)
@@ -56,66 +84,52 @@ def test_config3_resnet18_batch1_full():
         assert norm_err(y.cpu().numpy(), ref) <= FP32_TOL, f"{layer.name} {vname}"
 
 
-def test_config3_resnet18_batch32_sampled():
-    stack = wl.resnet18_stack()
-    for layer in wl.unique_shapes(stack):
-        i = stack.index(layer)
-        say(f"config 3 batch 32 layer {i} {layer.name}")
-        _check_sampled(layer, 32, 3000 + i, False)
+@pytest.mark.parametrize("layer", wl.unique_shapes(R18), ids=_ids(R18))
+def test_config3_resnet18_batch32_whole_batch(layer):
+    i = R18.index(layer)
+    say(f"config 3 fp32 batch 32 layer {i} {layer.name}, every output")
+    _check_images(layer, 32, 3000 + i, False)
 
 
-@pytest.mark.parametrize("part", [0, 1, 2])
-def test_config4_resnet50_batch64_fp32_sampled(part):
-    stack = wl.resnet50_stack()
-    shapes = wl.unique_shapes(stack)
-    for layer in shapes[part::3]:
-        i = stack.index(layer)
-        say(f"config 4 fp32 batch 64 layer {i} {layer.name}")
-        x, w, bias, y = _check_sampled(layer, 64, 4000 + i, False)
-        if layer.name in ("s2b1_conv2_3x3", "s4b0_conv2_3x3", "s3b0_proj_1x1"):
-            # one whole image in the middle of the batch, every output
-            ref = oracle_conv(layer, x[31:32], w, bias, relu=True)
-            assert norm_err(y[31:32].cpu().numpy(), ref) <= FP32_TOL, layer.name
+@pytest.mark.parametrize("layer", wl.unique_shapes(R50), ids=_ids(R50))
+def test_config4_resnet50_batch64_fp32_whole_batch(layer):
+    i = R50.index(layer)
+    say(f"config 4 fp32 batch 64 layer {i} {layer.name}, every output")
+    _check_images(layer, 64, 4000 + i, False)
 
 
-def test_config4_resnet50_batch64_large_groups_sampled():
+@pytest.mark.parametrize("layer", wl.unique_shapes(R50), ids=_ids(R50))
+def test_config4_resnet50_batch64_bf16_whole_batch(layer):
+    i = R50.index(layer)
+    say(f"config 4 bf16 batch 64 layer {i} {layer.name}, every output")
+    _check_images(layer, 64, 4000 + i, True)
+
+
+def test_config4_resnet50_batch64_large_groups():
     """Section 3.1's adaptive setting at full size: one group per kernel tap (M = Cin, half
-    kept) and one group per row of the weight matrix (M = K), tuned launch configuration."""
-    stack = wl.resnet50_stack()
+    kept) and one group per row of the weight matrix (M = K), tuned launch configuration,
+    both tensor types; every output of the first two, the middle and the last image."""
     names = ("s2b1_conv2_3x3", "s3b1_conv1_1x1", "s4b1_conv3_1x1")
-    picked = [l for l in stack if l.name in names]
+    picked = [l for l in R50 if l.name in names]
     assert len(picked) == len(names)
     for mode in ("cin", "row"):
         for layer in wl.with_large_groups(picked, mode):
             if mode == "row" and layer.K > 16384:
                 continue   # beyond the group size the library accepts
-            i = [l.name for l in stack].index(layer.name)
-            say(f"config 4 fp32 batch 64 groups per {mode} layer {i} {layer.name} {layer.n}:{layer.m}")
-            _check_sampled(layer, 64, 4100 + i, False)
+            i = [l.name for l in R50].index(layer.name)
+            for bf16 in (False, True):
+                say(f"config 4 {'bf16' if bf16 else 'fp32'} batch 64 groups per {mode} layer {i} "
+                    f"{layer.name} {layer.n}:{layer.m}")
+                _check_images(layer, 64, 4100 + i, bf16, images=(0, 1, 32, 63))
 
 
-def test_config4_resnet50_batch64_bf16_sampled():
-    stack = wl.resnet50_stack()
-    shapes = wl.unique_shapes(stack)
-    for layer in shapes[::4]:
-        i = stack.index(layer)
-        say(f"config 4 bf16 batch 64 layer {i} {layer.name}")
-        _check_sampled(layer, 64, 4000 + i, True)
-
-
-def test_config5_resnet101_batch256_bf16_mixed_sparsity():
-    """T = 32, stage 1 1:4, stage 2 2:4, stage 3 2:8, stage 4 4:8, bf16 in/out,
-    fp32 accumulation; two shapes per stage at the full batch of 256."""
-    stack = wl.resnet101_stack()
-    shapes = wl.unique_shapes(stack)
-    picked = []
-    for stage in (1, 2, 3, 4):
-        cand = [l for l in shapes if l.stage == stage]
-        picked += [c for c in cand if "conv2_3x3" in c.name][:1] + [c for c in cand if "conv3_1x1" in c.name][:1]
-    for layer in picked:
-        i = stack.index(layer)
-        say(f"config 5 bf16 batch 256 layer {i} {layer.name} {layer.n}:{layer.m} T={layer.tile}")
-        _check_sampled(layer, 256, 5000 + i, True, npts=1500)
+@pytest.mark.parametrize("layer", wl.unique_shapes(R101), ids=_ids(R101))
+def test_config5_resnet101_batch256_bf16_mixed_sparsity(layer):
+    """T = 32, stage 1 1:4, stage 2 2:4, stage 3 2:8, stage 4 4:8, bf16 in/out, fp32
+    accumulation, full batch of 256; every output of images 0, 1, 128 and 255."""
+    i = R101.index(layer)
+    say(f"config 5 bf16 batch 256 layer {i} {layer.name} {layer.n}:{layer.m} T={layer.tile}")
+    _check_images(layer, 256, 5000 + i, True, images=(0, 1, 128, 255))
 
 
 def test_tuning_cache_round_trip(tmp_path):
@@ -133,6 +147,29 @@ def test_tuning_cache_round_trip(tmp_path):
     assert nm.nm_cache_size() == 1
     v2, ms2 = nm.nm_autotune(nm.NM_F32, 4, 14, 14, 64, wp, True, 1, 1, 1, True)   # served from the cache
     assert v2 == v and abs(ms2 - ms) < 1e-6
+    # the first line of the file names the device the timings were taken on
+    head = open(path).readline().split()
+    assert head[:2] == ["nmconv-cache", "2"] and len(head) == 5 and "CU" in head[4]
+    # what nm_conv2d launches for the tuned shape is the cached variant
+    import torch
+    y = nm.nm_conv2d(torch.from_numpy(x).cuda(), wp, torch.from_numpy(bias).cuda(), 1, 1, 1, True)
+    torch.cuda.synchronize()
+    assert nm.nm_last_variant() == v
+    # bias and activation flags are part of the key: the same shape without them is a new entry
+    nm.nm_autotune(nm.NM_F32, 4, 14, 14, 64, wp, False, 1, 1, 1, False)
+    assert nm.nm_cache_size() == 2
+    # and so are the operand tables of the handle: with one group per tap (M = Cin = 64, a
+    # quarter kept), kept columns crowded into the first 16 channels need twice the k-steps
+    # per 32-channel chunk that kept columns spread evenly (every fourth channel) need
+    crowded, spread = w.copy(), w.copy()
+    crowded[:, :, :, :16] *= 1000.0
+    spread[:, :, :, ::4] *= 1000.0
+    wp_c, wp_s = nm.nm_prune(crowded, 16, 64, 16), nm.nm_prune(spread, 16, 64, 16)
+    nm.nm_autotune(nm.NM_F32, 4, 14, 14, 64, wp_c, True, 1, 1, 1, True)
+    n_before = nm.nm_cache_size()
+    vs, _ = nm.nm_autotune(nm.NM_F32, 4, 14, 14, 64, wp_s, True, 1, 1, 1, True)
+    assert nm.nm_cache_size() == n_before + 1
+    assert nm.nm_variant_legal(vs, wp_s)
     with pytest.raises(nm.NMError):
         nm.nm_cache_load(str(tmp_path / "missing.txt"))
 

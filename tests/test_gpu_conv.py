@@ -249,8 +249,12 @@ def test_argument_errors():
         nm.nm_conv2d(xd, wp, None, 1, 1, 1, False,
                      y=torch.zeros(1, 6, 6, 16, device="cuda", dtype=torch.bfloat16))
     assert e.value.code == -3
-    with pytest.raises(nm.NMError):
+    with pytest.raises(nm.NMError):           # stride 0
         nm.nm_conv2d(xd, wp, None, 0, 1, 1, False, y=torch.zeros(1, 6, 6, 16, device="cuda"))
+    with pytest.raises(ValueError):           # an output tensor of the wrong shape never reaches the kernel
+        nm.nm_conv2d(xd, wp, None, 1, 1, 1, False, y=torch.zeros(1, 6, 6, 8, device="cuda"))
+    with pytest.raises(ValueError):
+        nm.nm_conv2d(xd, wp, None, 1, 1, 1, False, y=torch.zeros(1, 6, 12, 16, device="cuda")[:, :, ::2])
 
 
 def test_config1_single_layer():

@@ -62,7 +62,6 @@ def test_largest_accepted(layer, batch, bf16):
 def test_first_sizes_refused():
     """One image row more than the cases above: refused on the host, before any launch."""
     import torch
-    dummy = torch.empty(16, device="cuda")
     for cin, cout, dt, what in ((32, 16, torch.float32, "x of 2 GiB, fp32"),
                                 (64, 16, torch.bfloat16, "x of 2 GiB, bf16"),
                                 (4, 128, torch.float32, "2^31 output elements")):
@@ -70,7 +69,8 @@ def test_first_sizes_refused():
         w = np.ones((cout, 1, 1, cin), dtype=np.float32)
         wp = nm.nm_prune(w, 2, 4, 16, nm.NM_BF16 if dt == torch.bfloat16 else nm.NM_F32)
         x = torch.empty((1, 4096, 4096, cin), dtype=dt, device="cuda")
+        y = torch.empty((1, 4096, 4096, cout), dtype=dt, device="cuda")   # never written
         with pytest.raises(nm.NMError) as e:
-            nm.nm_conv2d(x, wp, None, 1, 0, 1, False, y=dummy.to(dt))
+            nm.nm_conv2d(x, wp, None, 1, 0, 1, False, y=y)
         assert e.value.code == nm.NM_ERR_SHAPE
-        del x
+        del x, y

@@ -48,10 +48,7 @@ def _residual_case(layer, batch, bf16, seed, forced_prefixes=None):
                     continue
                 say(f"residual, forced {name} on {layer.name}")
                 nm.nm_force_variant(v)
-                try:
-                    y = nm.nm_conv2d_res(xd, wp, rd, bd, layer.stride, layer.pad, layer.dil, True)
-                except nm.NMError:
-                    continue
+                y = nm.nm_conv2d_res(xd, wp, rd, bd, layer.stride, layer.pad, layer.dil, True)
                 torch.cuda.synchronize()
                 assert norm_err(y.float().cpu().numpy(), ref) <= tol, name
                 seen.add(fam)
@@ -128,57 +125,57 @@ def test_pool_argument_errors():
     assert e.value.code == nm.NM_ERR_SHAPE
 
 
-def _oracle_forward(ops, x, seed0, bf16):
-    """The same network through the oracle, operator by operator."""
+def _oracle_op(op, params, i, src, residual, bf16):
+    """One operator of the network through the oracle, on the given input tensors."""
     rnd = oracle.round_bf16 if bf16 else (lambda a: a)
-    params = {i: (w, b) for i, w, b in wl.net_parameters(ops, seed0)}
-    t = {0: rnd(x)}
-    for i, op in enumerate(ops):
-        if op.kind == "conv":
-            l = op.layer
-            w, b = params[i]
-            _, _, wz = oracle.prune(w, l.n, l.m, l.tile)
-            wz = rnd(wz)
-            if op.residual >= 0:
-                t[op.dst] = oracle.conv2d_res(t[op.src], wz, t[op.residual], b, l.stride, l.pad, l.dil, op.relu,
-                                              out_bf16=bf16)
-            else:
-                t[op.dst] = oracle.conv2d(t[op.src], wz, b, l.stride, l.pad, l.dil, op.relu, out_bf16=bf16)
-        elif op.kind == "maxpool":
-            t[op.dst] = oracle.maxpool2d(t[op.src], op.k, op.stride, op.pad)
-        else:
-            a = oracle.avgpool_global(t[op.src], out_bf16=bf16)
-            t[op.dst] = a.reshape(a.shape[0], 1, 1, a.shape[1])
-    return t
+    if op.kind == "conv":
+        l = op.layer
+        w, b = params[i]
+        _, _, wz = oracle.prune(w, l.n, l.m, l.tile)
+        wz = rnd(wz)
+        if residual is not None:
+            return oracle.conv2d_res(src, wz, residual, b, l.stride, l.pad, l.dil, op.relu, out_bf16=bf16)
+        return oracle.conv2d(src, wz, b, l.stride, l.pad, l.dil, op.relu, out_bf16=bf16)
+    if op.kind == "maxpool":
+        return oracle.maxpool2d(src, op.k, op.stride, op.pad)
+    a = oracle.avgpool_global(src, out_bf16=bf16)
+    return a.reshape(a.shape[0], 1, 1, a.shape[1])
 
 
 @pytest.mark.parametrize("bottleneck", [True, False])
 @pytest.mark.parametrize("bf16", [False, True])
 def test_small_residual_network_end_to_end(bottleneck, bf16):
-    """A two-stage ResNet of either block type on a 40x40 input, every tensor of the
-    network against the oracle's.  Errors of earlier layers pass through later ones, so the
-    per-layer tolerances are widened by the depth: fp32 1e-4 -> 5e-4, bf16 2e-2 -> 6e-2
-    (each bf16 layer re-rounds its input; a rounding flip upstream moves a value by one
-    bf16 step, 2^-8 relative)."""
+    """A two-stage ResNet of either block type on a 40x40 input, run end to end on the GPU;
+    then every operator is checked on its own: the oracle is given the tensors the GPU
+    operator actually read (its input and residual, exact as floats) and must reproduce
+    the tensor the GPU wrote within the per-layer tolerance.  Errors of earlier layers
+    therefore do not accumulate into the bound, and every tensor of the network is covered."""
     import torch
     from paper_2507_17301_amd.network import Network
     ops = wl.resnet_graph((1, 2), (16, 32), bottleneck, 40, [(2, 4), (1, 4)], 16, stem_width=16, num_classes=10)
     batch, seed0 = 2, 900
     rng = np.random.default_rng(77)
     x = rng.random((batch, 40, 40, 3), dtype=np.float32)
-    ref = _oracle_forward(ops, x, seed0, bf16)
     net = Network(ops, batch, 40, nm.NM_BF16 if bf16 else nm.NM_F32, seed0)
     xd = torch.from_numpy(x).cuda().to(net.tdt)
     out = net.forward(xd)
     torch.cuda.synchronize()
-    tol = 6e-2 if bf16 else 5e-4
-    for k, r in ref.items():
-        if k == 0:
-            continue
-        got = net.t[k].float().cpu().numpy()
-        assert got.shape == r.shape
-        assert norm_err(got, r) <= tol, f"tensor {k}"
     assert out.shape == (batch, 1, 1, 10)
+    got = {k: t.float().cpu().numpy() for k, t in net.t.items()}
+    params = {i: (w, b) for i, w, b in wl.net_parameters(ops, seed0)}
+    tol = BF16_TOL if bf16 else FP32_TOL
+    written = {0}
+    for i, op in enumerate(ops):
+        assert op.src in written and (op.residual < 0 or op.residual in written)
+        res = got[op.residual] if op.residual >= 0 else None
+        ref = _oracle_op(op, params, i, got[op.src], res, bf16)
+        assert got[op.dst].shape == ref.shape
+        if op.kind == "maxpool":
+            assert np.array_equal(got[op.dst], ref), f"operator {i} (max pooling is a selection)"
+        else:
+            assert norm_err(got[op.dst], ref) <= tol, f"operator {i} {op.kind}"
+        written.add(op.dst)
+    assert written == set(net.t.keys())
 
 
 @pytest.mark.parametrize("layer,batch", [(L("i2c_3x3", 13, 11, 32, 48, 3, 3, 1, 1, 1, 2, 4, 16), 2),
