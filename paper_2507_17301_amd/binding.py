@@ -182,6 +182,8 @@ def out_shape(x_shape, wp: Packed, stride, pad, dil):
     sh, sw = _pair(stride)
     ph, pw = _pair(pad)
     dh, dw = _pair(dil)
+    if sh < 1 or sw < 1:
+        raise NMError(NM_ERR_ARG, "stride must be >= 1")
     ho = (h + 2 * ph - dh * (wp.kh - 1) - 1) // sh + 1
     wo = (w + 2 * pw - dw * (wp.kw - 1) - 1) // sw + 1
     return (b, ho, wo, wp.cout)
