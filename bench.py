@@ -32,6 +32,231 @@ def log(*a):
     print(*a, file=sys.stderr, flush=True)
 
 
+class Stack:
+    """The resident state of one conv stack: pruned + packed weights, one synthetic input
+    and one output tensor per layer, biases, and (after tune()) the chosen variants."""
+
+    def __init__(self, layers, B, dtype, seed0, cand_tiles=None):
+        import torch
+        from paper_2507_17301_amd import binding as nm
+        from paper_2507_17301_amd import workloads as wl
+        self.nm, self.torch = nm, torch
+        self.layers, self.B, self.dtype = list(layers), B, dtype
+        self.bf16 = dtype == "bf16"
+        self.tdt = torch.bfloat16 if self.bf16 else torch.float32
+        self.ndt = nm.NM_BF16 if self.bf16 else nm.NM_F32
+        self.esize = 2 if self.bf16 else 4
+        dev = torch.device("cuda:0")
+        gen = torch.Generator(device=dev)
+        gen.manual_seed(1234)
+        self.packed, self.xs, self.ys, self.biases = [], [], [], []
+        self.prune_s = self.tune_s = 0.0
+        for i, l in enumerate(self.layers):
+            _, w, bias = wl.make_tensors(l, B, seed0 + i, with_input=False)
+            tp = time.time()
+            if cand_tiles and l.n < l.m:
+                import dataclasses
+                wp, best_t, t_ms = nm.nm_autotune_tile(w, l.n, l.m, cand_tiles, self.ndt, B, l.H, l.W, True,
+                                                       l.stride, l.pad, l.dil, True)
+                log(f"{l.name:>22s}  T -> {best_t:2d}   " +
+                    "  ".join(f"T{t}: {v * 1e3:7.1f} us" for t, v in zip(cand_tiles, t_ms)))
+                self.layers[i] = l = dataclasses.replace(l, tile=best_t)
+            else:
+                wp = nm.nm_prune(w, l.n, l.m, l.tile, self.ndt)
+            self.prune_s += time.time() - tp
+            self.packed.append(wp)
+            self.xs.append(torch.rand((B, l.H, l.W, l.Cin), generator=gen, device=dev,
+                                      dtype=torch.float32).to(self.tdt))
+            self.ys.append(torch.empty((B, l.Ho, l.Wo, l.Cout), device=dev, dtype=self.tdt))
+            self.biases.append(torch.from_numpy(bias).to(dev))
+        self.launched = [None] * len(self.layers)
+        self.graph = None
+
+    def tune(self):
+        tp = time.time()
+        for i, l in enumerate(self.layers):
+            self.nm.nm_autotune(self.ndt, self.B, l.H, l.W, l.Cin, self.packed[i], True, l.stride, l.pad,
+                                l.dil, True)
+        self.torch.cuda.synchronize()
+        self.tune_s += time.time() - tp
+
+    def enqueue(self, stream, marks=None):
+        nm = self.nm
+        for i, l in enumerate(self.layers):
+            nm.nm_conv2d(self.xs[i], self.packed[i], self.biases[i], l.stride, l.pad, l.dil, True,
+                         y=self.ys[i], stream=stream)
+            self.launched[i] = nm.nm_last_variant()     # what actually ran (cache, or the default)
+            if marks is not None:
+                marks[i + 1].record(stream)
+
+    def time_steps(self, steps, warmup, use_graph=True):
+        """(ms per step from HIP events on the launch stream, ms per step on the host clock).
+        The launch-bound sequence of a step is captured once into a HIP graph (the library
+        only enqueues kernels, so it can be captured) and replayed per step."""
+        torch = self.torch
+        stream = torch.cuda.current_stream()
+        self.enqueue(stream)
+        torch.cuda.synchronize()
+        self.graph = None
+        if use_graph:
+            self.graph = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(self.graph):
+                self.enqueue(torch.cuda.current_stream())
+        run_step = self.graph.replay if self.graph is not None else (lambda: self.enqueue(stream))
+        for _ in range(warmup):
+            run_step()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        t_host0 = time.time()
+        e0.record(stream)
+        for _ in range(steps):
+            run_step()
+        e1.record(stream)
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / steps, (time.time() - t_host0) * 1e3 / steps
+
+    def per_layer(self, inst_steps=3):
+        """Per-layer kernel durations in the stack (HIP events on the launch stream): an event
+        after every layer of a few extra steps, so that each layer is timed with the caches in
+        the state the stack leaves them in."""
+        torch, nm = self.torch, self.nm
+        stream = torch.cuda.current_stream()
+        marks = [[torch.cuda.Event(enable_timing=True) for _ in range(len(self.layers) + 1)]
+                 for _ in range(inst_steps)]
+        for k in range(inst_steps):
+            marks[k][0].record(stream)
+            self.enqueue(stream, marks[k])
+        torch.cuda.synchronize()
+        rows = []
+        for i, l in enumerate(self.layers):
+            ms = sorted(marks[k][i].elapsed_time(marks[k][i + 1]) for k in range(inst_steps))[inst_steps // 2]
+            eff = l.effective_flops(self.B)
+            byts = l.algorithmic_bytes(self.B, self.esize, self.esize)
+            t_flop = eff / (PEAK_TFLOPS[self.dtype] * 1e12) * 1e3
+            t_mem = byts / (PEAK_HBM_GBS * 1e9) * 1e3
+            rows.append({
+                "layer": l.name, "variant": nm.nm_variant_name(self.launched[i]),
+                "ms": ms, "dense_gflops": l.dense_flops(self.B) / ms / 1e6, "eff_gflops": eff / ms / 1e6,
+                "alg_bytes": byts, "gbs": byts / ms / 1e6, "t_flop_ms": t_flop, "t_mem_ms": t_mem,
+                "t_min_ms": max(t_flop, t_mem),
+                "bound": "mfma" if t_flop >= t_mem else "hbm", "frac": max(t_flop, t_mem) / ms,
+            })
+        return rows
+
+    def totals(self):
+        B, es = self.B, self.esize
+        return (sum(l.dense_flops(B) for l in self.layers), sum(l.effective_flops(B) for l in self.layers),
+                sum(l.algorithmic_bytes(B, es, es) for l in self.layers))
+
+    def free(self):
+        for wp in self.packed:
+            wp.free()
+        self.packed, self.xs, self.ys, self.biases, self.graph = [], [], [], [], None
+        self.torch.cuda.empty_cache()
+
+
+def profiled_traffic(dtype):
+    """HBM bytes per launch of the headline workload as the rocprofv3 counter runs recorded them
+    (FETCH_SIZE + WRITE_SIZE, each scaled by what it reads for a 1 GiB device copy): read from
+    the tracked summary under profiles/, never measured by this process.  (value, source)."""
+    import re
+    name = {"f32": "nm_conv_kernel_resnet50_b64_f32.txt", "bf16": "nm_conv_sp16_kernel_resnet50_b64_bf16.txt"}[dtype]
+    path = os.path.join(ROOT, "profiles", name)
+    try:
+        m = re.search(r"HBM traffic per step\s+[\d.]+ GB \(([\d.]+) MB per launch\)", open(path).read())
+    except OSError:
+        m = None
+    if not m:
+        return None, None
+    return float(m.group(1)) * 1e6, f"profiles/{name} (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE of an earlier run of this command)"
+
+
+def stack_roofline(st, ms_step, rows, headline):
+    """The convolution kernel, all launches of a step taken together, against the roofline that
+    binds the workload: each layer's lower bound is max(effective flops / matrix-core peak,
+    algorithmic bytes / HBM peak); the workload is bound by whichever side has the larger sum.
+    The average launch duration comes from the timed region itself: the launches of a step run
+    back to back on one stream, so step time / launches is the kernel's duration plus whatever
+    gap the launches leave (an upper bound on the duration; the kernel trace shows no gap)."""
+    dense, eff, byts = st.totals()
+    kern_ms = sum(r["ms"] for r in rows)
+    tmin_ms = sum(r["t_min_ms"] for r in rows)
+    hbm_bound = sum(r["t_mem_ms"] for r in rows) >= sum(r["t_flop_ms"] for r in rows)
+    if hbm_bound:
+        roofline = {"bound": "hbm", "achieved": byts / ms_step / 1e6, "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                    "frac": byts / ms_step / 1e6 / PEAK_HBM_GBS}
+    else:
+        roofline = {"bound": "mfma", "achieved": eff / ms_step / 1e9, "peak": PEAK_TFLOPS[st.dtype],
+                    "unit": "TFLOP/s", "frac": eff / ms_step / 1e9 / PEAK_TFLOPS[st.dtype]}
+    traffic, source = profiled_traffic(st.dtype) if headline else (None, None)
+    families = sorted({(r["variant"] or "?").split("_")[0] for r in rows})
+    roofline.update({
+        "traffic": traffic, "traffic_source": source,
+        "kernel": "nm_conv_sp16_kernel" if st.bf16 else "nm_conv_kernel", "variant_families": families,
+        "launches_per_step": len(rows), "avg_launch_ms": ms_step / len(rows),
+        # with an event after every layer of three extra steps (adds the events' own cost)
+        "avg_launch_ms_event_per_layer": kern_ms / len(rows),
+        # sum of the per-layer lower bounds over the step time: the fraction of the roofline
+        # that binds each layer
+        "frac_of_binding_roofline_per_layer": tmin_ms / ms_step,
+        "effective_tflops": eff / ms_step / 1e9,
+        "algorithmic_gbytes_per_step": byts / 1e9, "achieved_gbs": byts / ms_step / 1e6,
+    })
+    return roofline
+
+
+def log_rows(rows, ms_step, ms_host):
+    kern_ms = sum(r["ms"] for r in rows)
+    tmin_ms = sum(r["t_min_ms"] for r in rows)
+    for r in rows:
+        log(f"{r['layer']:>18s} {r['variant']:>34s} {r['ms'] * 1e3:9.1f} us  "
+            f"{r['eff_gflops'] / 1e3:7.1f} eff TF/s {r['gbs']:8.0f} GB/s  {r['bound']:4s} {r['frac'] * 100:5.1f}%")
+    log(f"sum of kernel times {kern_ms:.3f} ms, step {ms_step:.3f} ms (host {ms_host:.3f} ms), "
+        f"sum of per-layer lower bounds {tmin_ms:.3f} ms -> {tmin_ms / ms_step * 100:.1f}% of binding roofline")
+
+
+def sweep_speedups(steps, warmup):
+    """Sparse over dense per N:M ratio and tile size on the ResNet-50 stage-3 3x3 layer
+    (14x14x256 -> 256, batch 32, fp32): every cell and the dense (N = M) form of the same layer
+    at the same T, each through its tuned variant, launched in turn inside one graph so that
+    no cell finds its tensors warmer than another's; median over the replays."""
+    import torch
+    from paper_2507_17301_amd import workloads as wl
+    cells = wl.sweep_config2()
+    tiles = sorted({c.tile for c in cells})
+    dense = [wl.dense_form(next(c for c in cells if c.tile == t), f"cfg2_dense_T{t}") for t in tiles]
+    st = Stack(cells + dense, 32, "f32", 0)
+    st.tune()
+    stream = torch.cuda.current_stream()
+    st.enqueue(stream)
+    torch.cuda.synchronize()
+    reps = max(5, steps)
+    times = [[] for _ in st.layers]
+    for r in range(warmup + reps):
+        marks = [torch.cuda.Event(enable_timing=True) for _ in range(len(st.layers) + 1)]
+        marks[0].record(stream)
+        st.enqueue(stream, marks)
+        torch.cuda.synchronize()
+        if r >= warmup:
+            for i in range(len(st.layers)):
+                times[i].append(marks[i].elapsed_time(marks[i + 1]))
+    med = [sorted(t)[len(t) // 2] for t in times]
+    t_dense = {l.tile: med[len(cells) + k] for k, l in enumerate(dense)}
+    out, vs_best = {}, {}
+    best_dense = min(t_dense.values())
+    for i, c in enumerate(cells):
+        out.setdefault(f"{c.n}:{c.m}", {})[f"T{c.tile}"] = round(t_dense[c.tile] / med[i], 3)
+        vs_best.setdefault(f"{c.n}:{c.m}", {})[f"T{c.tile}"] = round(best_dense / med[i], 3)
+    detail = {"layer": "3x3 14x14x256->256 batch 32 fp32", "baseline": "per_ratio divides by the dense form at the "
+              "same T; over_fastest_dense by the fastest dense form of any T", "over_fastest_dense": vs_best,
+              "dense_us": {f"T{t}": round(v * 1e3, 2) for t, v in t_dense.items()},
+              "sparse_us": {c.name: round(med[i] * 1e3, 2) for i, c in enumerate(cells)}}
+    for k, v in out.items():
+        log(f"sparse over dense {k:>4s}: " + "  ".join(f"{t} x{s:.2f}" for t, s in v.items()))
+    st.free()
+    return out, detail
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -58,9 +283,14 @@ def main():
                     help="experiment: comma-separated tile sizes; the tuner prunes every pruned layer at each and "
                          "keeps the fastest per layer (nm_autotune_tile), e.g. 8,16,32")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--no-tune", action="store_true", help="use the untuned default variant")
+    ap.add_argument("--no-extras", action="store_true",
+                    help="headline run only: skip the bf16 stack, the dense stack and the N:M sweep that the "
+                         "default run measures besides the fp32 headline")
+    ap.add_argument("--no-tune", action="store_true",
+                    help="time the untuned default variants, then tune and time again: reports how far the "
+                         "cost-model default is from the tuned pick")
     ap.add_argument("--no-graph", action="store_true",
-                    help="launch the 53 kernels of a step one by one instead of replaying a HIP graph")
+                    help="launch the kernels of a step one by one instead of replaying a HIP graph")
     ap.add_argument("--cache", default=None, help="tuning cache file to load/save")
     ap.add_argument("--report", default=None, help="write the per-layer table (JSON) here")
     args = ap.parse_args()
@@ -70,7 +300,6 @@ def main():
               "use --gpus 1", file=sys.stderr)
         sys.exit(2)
 
-    import numpy as np
     import torch
     from paper_2507_17301_amd import binding as nm
     from paper_2507_17301_amd import workloads as wl
@@ -114,53 +343,13 @@ def main():
         wname += "_T_per_layer_of_" + "_".join(str(t) for t in cand_tiles)
     headline = (args.workload == "resnet50" and B == 64 and not args.group and (n_, m_, t_) == (2, 4, 16)
                 and not cand_tiles)
-    bf16 = args.dtype == "bf16"
-    tdt = torch.bfloat16 if bf16 else torch.float32
-    ndt = nm.NM_BF16 if bf16 else nm.NM_F32
-    esize = 2 if bf16 else 4
 
     # ---- one-time set-up: weights, pruning, tuning, resident inputs ---------
     if args.cache and os.path.exists(args.cache):
         nm.nm_cache_load(args.cache)
-    gen = torch.Generator(device=dev)
-    gen.manual_seed(1234)
     t0 = time.time()
-    packed, xs, ys, biases, variants = [], [], [], [], []
-    prune_s = 0.0
-    for i, l in enumerate(layers):
-        _, w, bias = wl.make_tensors(l, B, seed0 + i, with_input=False)
-        tp = time.time()
-        if cand_tiles and l.n < l.m:
-            import dataclasses
-            wp, best_t, t_ms = nm.nm_autotune_tile(w, l.n, l.m, cand_tiles, ndt, B, l.H, l.W, True,
-                                                   l.stride, l.pad, l.dil, True)
-            log(f"{l.name:>22s}  T -> {best_t:2d}   " +
-                "  ".join(f"T{t}: {v * 1e3:7.1f} us" for t, v in zip(cand_tiles, t_ms)))
-            layers[i] = l = dataclasses.replace(l, tile=best_t)
-        else:
-            wp = nm.nm_prune(w, l.n, l.m, l.tile, ndt)
-        prune_s += time.time() - tp
-        packed.append(wp)
-        x = torch.rand((B, l.H, l.W, l.Cin), generator=gen, device=dev, dtype=torch.float32).to(tdt)
-        xs.append(x)
-        ys.append(torch.empty((B, l.Ho, l.Wo, l.Cout), device=dev, dtype=tdt))
-        biases.append(torch.from_numpy(bias).to(dev))
-    tune_s = 0.0
-    for i, l in enumerate(layers):
-        if args.no_tune:
-            variants.append(None)
-            continue
-        tp = time.time()
-        v, ms = nm.nm_autotune(ndt, B, l.H, l.W, l.Cin, packed[i], True, l.stride, l.pad, l.dil, True)
-        tune_s += time.time() - tp
-        variants.append(v)
-    torch.cuda.synchronize()
-    if args.cache:
-        nm.nm_cache_save(args.cache)
-    log(f"set-up {time.time() - t0:.1f}s (prune+pack {prune_s:.2f}s, tune {tune_s:.2f}s), "
-        f"{len(layers)} layers, {nm.nm_cache_size()} tuned shapes")
-
-    stream = torch.cuda.current_stream()
+    st = Stack(layers, B, args.dtype, seed0, cand_tiles)
+    layers = st.layers
 
     # a plain device copy of known size (1 GiB read + 1 GiB written): the yardstick
     # for the FETCH_SIZE / WRITE_SIZE counters when this command runs under rocprofv3 --pmc
@@ -170,103 +359,31 @@ def main():
     torch.cuda.synchronize()
     del cal_src, cal_dst
 
-    def step():
-        for i, l in enumerate(layers):
-            nm.nm_conv2d(xs[i], packed[i], biases[i], l.stride, l.pad, l.dil, True, y=ys[i],
-                         stream=stream)
+    untuned = None
+    if args.no_tune:
+        # the cost-model default first, on an empty cache, then the tuned pick of the same layers
+        ms_def, _ = st.time_steps(args.steps, args.warmup, not args.no_graph)
+        rows_def = st.per_layer()
+        untuned = {"ms_per_step": ms_def, "variants": [r["variant"] for r in rows_def]}
+    st.tune()
+    if args.cache:
+        nm.nm_cache_save(args.cache)
+    log(f"set-up {time.time() - t0:.1f}s (prune+pack {st.prune_s:.2f}s, tune {st.tune_s:.2f}s), "
+        f"{len(layers)} layers, {nm.nm_cache_size()} tuned shapes")
 
-    # The launch-bound sequence of a step is captured once into a HIP graph (the
-    # library only enqueues kernels, so it can be captured) and replayed per step.
-    step()
-    torch.cuda.synchronize()
-    graph = None
-    if not args.no_graph:
-        graph = torch.cuda.CUDAGraph()
-        with torch.cuda.graph(graph):
-            nonlocal_stream = torch.cuda.current_stream()
-            for i, l in enumerate(layers):
-                nm.nm_conv2d(xs[i], packed[i], biases[i], l.stride, l.pad, l.dil, True, y=ys[i],
-                             stream=nonlocal_stream)
-    run_step = graph.replay if graph is not None else step
-
-    for _ in range(args.warmup):
-        run_step()
-    torch.cuda.synchronize()
-    e0 = torch.cuda.Event(enable_timing=True)
-    e1 = torch.cuda.Event(enable_timing=True)
-    t_host0 = time.time()
-    e0.record(stream)
-    for _ in range(args.steps):
-        run_step()
-    e1.record(stream)
-    torch.cuda.synchronize()
-    t_host = time.time() - t_host0
-    ms_step = e0.elapsed_time(e1) / args.steps
-    ms_step_host = t_host * 1e3 / args.steps
-
-    # ---- per-layer kernel durations, in the stack (HIP events on the launch stream):
-    # an event after every layer of a few extra steps, so that each layer is timed
-    # with the caches in the state the stack leaves them in
-    inst_steps = 3
-    marks = [[torch.cuda.Event(enable_timing=True) for _ in range(len(layers) + 1)]
-             for _ in range(inst_steps)]
-    for k in range(inst_steps):
-        marks[k][0].record(stream)
-        for i, l in enumerate(layers):
-            nm.nm_conv2d(xs[i], packed[i], biases[i], l.stride, l.pad, l.dil, True, y=ys[i],
-                         stream=stream)
-            marks[k][i + 1].record(stream)
-    torch.cuda.synchronize()
-    per_layer = []
-    for i, l in enumerate(layers):
-        ms = sorted(marks[k][i].elapsed_time(marks[k][i + 1]) for k in range(inst_steps))[inst_steps // 2]
-        eff = l.effective_flops(B)
-        byts = l.algorithmic_bytes(B, esize, esize)
-        t_flop = eff / (PEAK_TFLOPS[args.dtype] * 1e12) * 1e3
-        t_mem = byts / (PEAK_HBM_GBS * 1e9) * 1e3
-        per_layer.append({
-            "layer": l.name, "variant": nm.nm_variant_name(variants[i]) if variants[i] is not None else "default",
-            "ms": ms, "dense_gflops": l.dense_flops(B) / ms / 1e6, "eff_gflops": eff / ms / 1e6,
-            "alg_bytes": byts, "gbs": byts / ms / 1e6, "t_min_ms": max(t_flop, t_mem),
-            "bound": "mfma" if t_flop >= t_mem else "hbm", "frac": max(t_flop, t_mem) / ms,
-        })
-
-    dense = sum(l.dense_flops(B) for l in layers)
-    eff = sum(l.effective_flops(B) for l in layers)
-    byts = sum(l.algorithmic_bytes(B, esize, esize) for l in layers)
-    kern_ms = sum(r["ms"] for r in per_layer)
-    tmin_ms = sum(r["t_min_ms"] for r in per_layer)
-    for r in per_layer:
-        log(f"{r['layer']:>18s} {r['variant']:>34s} {r['ms'] * 1e3:9.1f} us  "
-            f"{r['eff_gflops'] / 1e3:7.1f} eff TF/s {r['gbs']:8.0f} GB/s  {r['bound']:4s} {r['frac'] * 100:5.1f}%")
-    log(f"sum of kernel times {kern_ms:.3f} ms, step {ms_step:.3f} ms (host {ms_step_host:.3f} ms), "
-        f"sum of per-layer lower bounds {tmin_ms:.3f} ms -> {tmin_ms / kern_ms * 100:.1f}% of binding roofline")
-
-    # The convolution kernel, all launches of a step taken together.  fp32 is bound by the
-    # fp32 matrix cores (2*P*K'*Cout flops per launch); with bf16 tensors nearly every layer
-    # sits below the ridge, so the bound is HBM (algorithmic bytes per launch).  The average
-    # launch duration comes from the timed region itself: the launches of a step run back to
-    # back on one stream, so step time / launches is the kernel's duration plus whatever gap
-    # the launches leave (an upper bound on the duration; the kernel trace shows no gap).
-    avg_ms = ms_step / len(layers)
-    if bf16:
-        roofline = {"bound": "hbm", "achieved": byts / ms_step / 1e6, "peak": PEAK_HBM_GBS, "unit": "GB/s",
-                    "frac": byts / ms_step / 1e6 / PEAK_HBM_GBS}
-    else:
-        roofline = {"bound": "mfma", "achieved": eff / ms_step / 1e9, "peak": PEAK_TFLOPS["f32"],
-                    "unit": "TFLOP/s", "frac": eff / ms_step / 1e9 / PEAK_TFLOPS["f32"]}
-    roofline.update({
-        # HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled by what the same
-        # counters read for the 1 GiB device copy above (profiles/); measured for the default workload only
-        "traffic": {"f32": 112.5e6, "bf16": 54.7e6}[args.dtype] if headline else None,
-        "kernel": "nm_conv_sp16_kernel" if bf16 else "nm_conv_kernel", "launches_per_step": len(layers),
-        "avg_launch_ms": avg_ms,
-        # with an event after every layer of three extra steps (adds the events' own cost)
-        "avg_launch_ms_event_per_layer": kern_ms / len(layers),
-        "frac_of_binding_roofline_per_layer": tmin_ms / kern_ms,
-        "effective_tflops": eff / ms_step / 1e9,
-        "algorithmic_gbytes_per_step": byts / 1e9, "achieved_gbs": byts / ms_step / 1e6,
-    })
+    ms_step, ms_step_host = st.time_steps(args.steps, args.warmup, not args.no_graph)
+    per_layer = st.per_layer()
+    log_rows(per_layer, ms_step, ms_step_host)
+    dense, eff, byts = st.totals()
+    roofline = stack_roofline(st, ms_step, per_layer, headline)
+    launch = "hip_graph_replay" if st.graph is not None else "one_launch_per_layer"
+    if untuned:
+        same = sum(a == r["variant"] for a, r in zip(untuned["variants"], per_layer))
+        untuned.update({"tuned_ms_per_step": ms_step, "default_over_tuned": untuned["ms_per_step"] / ms_step,
+                        "layers_where_default_is_the_tuned_pick": same, "layers": len(per_layer)})
+        del untuned["variants"]
+        log(f"untuned default {untuned['ms_per_step']:.3f} ms per step = x{untuned['default_over_tuned']:.2f} "
+            f"of the tuned {ms_step:.3f} ms; the default is the tuned pick on {same} of {len(per_layer)} layers")
 
     if args.workload == "sweep":
         # sparse-over-dense speedup per cell: the dense form of the same layer through the same kernel family
@@ -275,9 +392,37 @@ def main():
             r["speedup_over_dense"] = t_dense / r["ms"]
             log(f"{r['layer']:>18s}  {r['ms'] * 1e3:7.1f} us   x{r['speedup_over_dense']:.2f} over dense ({t_dense * 1e3:.1f} us)")
 
+    # ---- what the headline run reports besides the fp32 figure: the same stack with bf16
+    # tensors, and sparse over dense -- for the stack (its N = M form through the same kernels)
+    # and per N:M ratio and tile size on the stage-3 3x3 layer
+    extras = {}
+    if headline and args.dtype == "f32" and not args.no_extras and not args.no_tune:
+        st.free()
+        sb = Stack(wl.resnet50_stack(2, 4, 16), B, "bf16", seed0)
+        sb.tune()
+        ms_b, ms_b_host = sb.time_steps(args.steps, args.warmup, not args.no_graph)
+        rows_b = sb.per_layer()
+        log("--- bf16 tensors, same stack")
+        log_rows(rows_b, ms_b, ms_b_host)
+        d_b, e_b, by_b = sb.totals()
+        rf_b = stack_roofline(sb, ms_b, rows_b, True)
+        extras["bf16"] = {"ms_per_step": ms_b, "ms_per_img": ms_b / B, "dense_equiv_gflops": d_b / ms_b / 1e6,
+                          "effective_gflops": e_b / ms_b / 1e6, "launches": len(rows_b),
+                          "algorithmic_gbs": by_b / ms_b / 1e6, "setup": {"prune_pack_s": sb.prune_s, "autotune_s": sb.tune_s},
+                          "roofline": rf_b}
+        sb.free()
+        sd = Stack(wl.resnet50_stack(1, 1, 16), B, "f32", seed0)
+        sd.tune()
+        ms_d, _ = sd.time_steps(args.steps, args.warmup, not args.no_graph)
+        sd.free()
+        log(f"--- dense (N = M) form of the stack, fp32: {ms_d:.3f} ms per step -> 2:4 is x{ms_d / ms_step:.2f} faster")
+        sweep, detail = sweep_speedups(args.steps, args.warmup)
+        extras["speedup_over_dense"] = {"resnet50_stack_2:4_T16_batch64_f32": round(ms_d / ms_step, 3),
+                                        "dense_stack_ms_per_step": ms_d, "per_ratio": sweep, "per_ratio_detail": detail}
+
     cpu = None
     if not args.no_cpu_baseline:
-        cpu = cpu_baseline(layers, B, bf16, seed0)
+        cpu = cpu_baseline(layers, B, args.dtype == "bf16", seed0)
 
     out = {
         "metric": ("dense-equiv GFLOP/s, ResNet-50 conv stack 2:4 @batch 64" if headline
@@ -289,11 +434,13 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": args.dtype, "data": "synthetic",
         "config": {"workload": f"{wname}_batch{B}_{args.dtype}",
-                   "batch": B, "layers": len(layers), "tuned": not args.no_tune,
-                   "launch": "hip_graph_replay" if graph is not None else "one_launch_per_layer"},
-        "setup": {"prune_pack_s": prune_s, "autotune_s": tune_s},
+                   "batch": B, "layers": len(layers), "tuned": True, "launch": launch},
+        "setup": {"prune_pack_s": st.prune_s, "autotune_s": st.tune_s},
         "roofline": roofline, "cpu_baseline": cpu,
     }
+    out.update(extras)
+    if untuned:
+        out["untuned_default"] = untuned
     if args.report:
         with open(args.report, "w") as f:
             json.dump({"summary": out, "layers": per_layer}, f, indent=1)
@@ -470,13 +617,30 @@ def fusion_ablation(args, n_, m_, t_):
     print(json.dumps(out), flush=True)
 
 
+def host_cores():
+    """Cores this process may use: the CPU affinity mask, cut down to the cgroup's CPU quota
+    where one is set (a box may show every core of the host and still grant a share)."""
+    try:
+        n = len(os.sched_getaffinity(0))
+    except AttributeError:
+        n = os.cpu_count() or 1
+    try:
+        quota, period = open("/sys/fs/cgroup/cpu.max").read().split()
+        if quota != "max":
+            n = max(1, min(n, int(int(quota) / int(period))))
+    except (OSError, ValueError):
+        pass
+    return n
+
+
 def cpu_baseline(layers, B, bf16, seed0):
-    """The CPU oracle, as it stands, on the first images of the same workload."""
+    """The CPU oracle, as it stands, on the first images of the same workload, on every core
+    this process may use; plus the single 3x3 layer of configuration 1 on one thread."""
     import numpy as np
     import oracle
     from paper_2507_17301_amd import workloads as wl
 
-    cores = min(16, os.cpu_count() or 1)
+    cores = host_cores()
     prepared = []
     for i, l in enumerate(layers):
         _, w, bias = wl.make_tensors(l, 1, seed0 + i, with_input=False)
@@ -496,14 +660,27 @@ def cpu_baseline(layers, B, bf16, seed0):
         return total
 
     t1 = run(1)
-    nimg = int(max(2, min(B, round(15.0 / max(t1, 1e-3)))))
+    nimg = int(max(2, min(B, round(12.0 / max(t1, 1e-3)))))
     t = run(nimg)
     dense_per_img = sum(l.dense_flops(1) for l, _, _ in prepared)
-    log(f"cpu oracle: {nimg} images in {t:.2f}s on {cores} threads")
+    log(f"cpu oracle: {nimg} images in {t:.2f}s on {cores} threads (host shows {os.cpu_count()} cores)")
+
+    c1 = wl.single_conv_config1()
+    x1, w1, b1 = wl.make_tensors(c1, 1, 0, weight_sigma=0.05)
+    _, _, wz1 = oracle.prune(w1, c1.n, c1.m, c1.tile)
+    ts = []
+    for _ in range(3):
+        tt = time.time()
+        oracle.conv2d(x1, wz1, b1, c1.stride, c1.pad, c1.dil, True, nthreads=1)
+        ts.append(time.time() - tt)
+    t_c1 = sorted(ts)[1]
+    log(f"cpu oracle, configuration 1 (one 3x3 layer, batch 1) on one thread: {t_c1 * 1e3:.1f} ms")
     return {"value": dense_per_img * nimg / t / 1e9, "unit": "GFLOP/s", "cores": cores,
-            "kind": "oracle", "ms_per_img": t * 1e3 / nimg,
+            "host_cores": os.cpu_count(), "kind": "oracle", "ms_per_img": t * 1e3 / nimg,
             "sample": f"first {nimg} of {B} images through all {len(prepared)} layers "
-                      f"(direct convolution on zero-filled weights, fp64 accumulate)"}
+                      f"(direct convolution on zero-filled weights, fp64 accumulate)",
+            "config1_one_thread": {"value": c1.dense_flops(1) / t_c1 / 1e9, "unit": "GFLOP/s", "cores": 1,
+                                   "ms": t_c1 * 1e3, "sample": "the single 3x3 layer 56x56x64->64, batch 1, whole output"}}
 
 
 if __name__ == "__main__":
