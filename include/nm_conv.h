@@ -41,7 +41,10 @@ typedef enum {
     NM_ERR_IO = -6           /* cache file could not be read or written */
 } nm_status_t;
 
-typedef enum { NM_F32 = 0, NM_BF16 = 1 } nm_dtype_t;
+/* Element types.  A plain int at the boundary, so that a caller's out-of-range
+ * value is an NM_ERR_ARG and not undefined behaviour inside the library. */
+typedef int nm_dtype_t;
+enum { NM_F32 = 0, NM_BF16 = 1 };
 
 /* Packed, pruned weights of one layer.  Opaque, owned by the library, immutable
  * after creation, bound to the device that was current in nm_prune. */

@@ -111,8 +111,8 @@ int oracle_prune(const float* w, int cout, int K, int N, int M, int T,
 }
 
 /*
- * Compressed weight format (section 2.1 "compressed weight format and an index
- * array"; Alg. 1 inputs W[T,N], Idx[N], repeated over groups):
+ * The compressed weights and their index array (section 2.1; the inputs W[T,N]
+ * and Idx[N] of Alg. 1, repeated over groups):
  *   vals[j][kk][t] = w[j*T + t][ idx[j][kk] ],  kk = g*N + n,  zero when the
  *   row j*T + t does not exist.
  */
