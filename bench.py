@@ -115,6 +115,46 @@ class Stack:
         torch.cuda.synchronize()
         return e0.elapsed_time(e1) / steps, (time.time() - t_host0) * 1e3 / steps
 
+    def time_floor(self, steps, warmup, use_graph=True):
+        """ms per step of the same launch sequence with every convolution replaced by a kernel
+        that only reads the layer's input and writes its output (nm_stream_floor): what the
+        stack's own traffic costs on this device, launch for launch."""
+        torch, nm = self.torch, self.nm
+        stream = torch.cuda.current_stream()
+
+        def enqueue(s):
+            for x, y in zip(self.xs, self.ys):
+                nm.nm_stream_floor(x, y, stream=s)
+        enqueue(stream)
+        torch.cuda.synchronize()
+        graph = None
+        if use_graph:
+            graph = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(graph):
+                enqueue(torch.cuda.current_stream())
+        run = graph.replay if graph is not None else (lambda: enqueue(stream))
+        for _ in range(warmup):
+            run()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record(stream)
+        for _ in range(steps):
+            run()
+        e1.record(stream)
+        torch.cuda.synchronize()
+        ms = e0.elapsed_time(e1) / steps
+        # per layer, with an event after every launch of a few extra eager passes
+        n = len(self.layers)
+        marks = [[torch.cuda.Event(enable_timing=True) for _ in range(n + 1)] for _ in range(3)]
+        for k in range(3):
+            marks[k][0].record(stream)
+            for i, (x, y) in enumerate(zip(self.xs, self.ys)):
+                nm.nm_stream_floor(x, y, stream=stream)
+                marks[k][i + 1].record(stream)
+        torch.cuda.synchronize()
+        self.floor_ms = [sorted(marks[k][i].elapsed_time(marks[k][i + 1]) for k in range(3))[1] for i in range(n)]
+        return ms
+
     def per_layer(self, inst_steps=3):
         """Per-layer kernel durations in the stack (HIP events on the launch stream): an event
         after every layer of a few extra steps, so that each layer is timed with the caches in
@@ -171,7 +211,7 @@ def profiled_traffic(dtype):
     return float(m.group(1)) * 1e6, f"profiles/{name} (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE of an earlier run of this command)"
 
 
-def stack_roofline(st, ms_step, rows, headline):
+def stack_roofline(st, ms_step, rows, headline, floor_ms=None):
     """The convolution kernel, all launches of a step taken together, against the roofline that
     binds the workload: each layer's lower bound is max(effective flops / matrix-core peak,
     algorithmic bytes / HBM peak); the workload is bound by whichever side has the larger sum.
@@ -202,6 +242,11 @@ def stack_roofline(st, ms_step, rows, headline):
         "effective_tflops": eff / ms_step / 1e9,
         "algorithmic_gbytes_per_step": byts / 1e9, "achieved_gbs": byts / ms_step / 1e6,
     })
+    if floor_ms:
+        # the same launches moving only each layer's input and output (nm_stream_floor), timed in
+        # this run: the step time a stack of perfect copy kernels reaches on this device
+        roofline["traffic_only_ms_per_step"] = floor_ms
+        roofline["traffic_only_over_step"] = floor_ms / ms_step
     return roofline
 
 
@@ -210,7 +255,8 @@ def log_rows(rows, ms_step, ms_host):
     tmin_ms = sum(r["t_min_ms"] for r in rows)
     for r in rows:
         log(f"{r['layer']:>18s} {r['variant']:>34s} {r['ms'] * 1e3:9.1f} us  "
-            f"{r['eff_gflops'] / 1e3:7.1f} eff TF/s {r['gbs']:8.0f} GB/s  {r['bound']:4s} {r['frac'] * 100:5.1f}%")
+            f"{r['eff_gflops'] / 1e3:7.1f} eff TF/s {r['gbs']:8.0f} GB/s  {r['bound']:4s} {r['frac'] * 100:5.1f}%"
+            + (f"   traffic only {r['traffic_only_ms'] * 1e3:6.1f} us" if "traffic_only_ms" in r else ""))
     log(f"sum of kernel times {kern_ms:.3f} ms, step {ms_step:.3f} ms (host {ms_host:.3f} ms), "
         f"sum of per-layer lower bounds {tmin_ms:.3f} ms -> {tmin_ms / ms_step * 100:.1f}% of binding roofline")
 
@@ -373,9 +419,14 @@ def main():
 
     ms_step, ms_step_host = st.time_steps(args.steps, args.warmup, not args.no_graph)
     per_layer = st.per_layer()
+    floor_ms = st.time_floor(args.steps, args.warmup, not args.no_graph)
+    for r, f in zip(per_layer, st.floor_ms):
+        r["traffic_only_ms"] = f
     log_rows(per_layer, ms_step, ms_step_host)
     dense, eff, byts = st.totals()
-    roofline = stack_roofline(st, ms_step, per_layer, headline)
+    log(f"traffic only (every layer's input read and output written by a plain streaming kernel, same "
+        f"launch sequence): {floor_ms:.3f} ms per step = {floor_ms / ms_step * 100:.0f}% of the step")
+    roofline = stack_roofline(st, ms_step, per_layer, headline, floor_ms)
     launch = "hip_graph_replay" if st.graph is not None else "one_launch_per_layer"
     if untuned:
         same = sum(a == r["variant"] for a, r in zip(untuned["variants"], per_layer))
@@ -402,10 +453,14 @@ def main():
         sb.tune()
         ms_b, ms_b_host = sb.time_steps(args.steps, args.warmup, not args.no_graph)
         rows_b = sb.per_layer()
+        floor_b = sb.time_floor(args.steps, args.warmup, not args.no_graph)
+        for r, f in zip(rows_b, sb.floor_ms):
+            r["traffic_only_ms"] = f
         log("--- bf16 tensors, same stack")
         log_rows(rows_b, ms_b, ms_b_host)
         d_b, e_b, by_b = sb.totals()
-        rf_b = stack_roofline(sb, ms_b, rows_b, True)
+        log(f"traffic only, bf16: {floor_b:.3f} ms per step = {floor_b / ms_b * 100:.0f}% of the step")
+        rf_b = stack_roofline(sb, ms_b, rows_b, True, floor_b)
         extras["bf16"] = {"ms_per_step": ms_b, "ms_per_img": ms_b / B, "dense_equiv_gflops": d_b / ms_b / 1e6,
                           "effective_gflops": e_b / ms_b / 1e6, "launches": len(rows_b),
                           "algorithmic_gbs": by_b / ms_b / 1e6, "setup": {"prune_pack_s": sb.prune_s, "autotune_s": sb.tune_s},

@@ -178,6 +178,17 @@ int nm_im2col(const void* x_dev, nm_dtype_t dtype, int b, int h, int w, int cin,
               void* a_dev, void* hip_stream);
 
 /*
+ * nm_stream_floor -- a measuring stick, not part of the method: one kernel that reads the
+ * first x_bytes of x_dev and writes the first y_bytes of y_dev (whole 16-byte units; a
+ * remainder below 16 bytes is left alone), and computes nothing.  Launched with a layer's
+ * input and output sizes it shows what the layer's own traffic costs on this device in the
+ * same launch sequence -- the part of a layer's time that no convolution kernel can remove
+ * (section 3.2 argues from memory traffic; this puts a measured number under it).
+ * The contents written to y are unspecified.  Pointers 16-byte aligned; enqueue-only.
+ */
+int nm_stream_floor(const void* x_dev, size_t x_bytes, void* y_dev, size_t y_bytes, void* hip_stream);
+
+/*
  * nm_autotune -- per-layer choice of the fastest kernel variant (section 3.3:
  * every candidate is run on the target and the fastest kept).  Runs each legal
  * variant for this shape on library-allocated scratch tensors (pseudo-random
@@ -188,6 +199,8 @@ int nm_im2col(const void* x_dev, nm_dtype_t dtype, int b, int h, int w, int cin,
  * count, and which operand tables the handle carries -- layers of one shape whose
  * kept sets need different k-steps per chunk do not share an entry) and returns it.
  * Synchronous.  A cached shape returns immediately with the cached result.
+ * With the environment variable NM_TUNE_VERBOSE set, the time of every candidate
+ * is printed to stderr, fastest first.
  *   chosen_variant, best_ms   may be NULL
  */
 int nm_autotune(nm_dtype_t x_dtype, int b, int h, int w, int cin,

@@ -57,6 +57,7 @@ def lib():
         L.nm_maxpool2d.argtypes = [vp, ci, ci, ci, ci, ci, ci, ci, ci, vp, vp]
         L.nm_avgpool_global.argtypes = [vp, ci, ci, ci, ci, ci, vp, vp]
         L.nm_im2col.argtypes = [vp] + [ci] * 13 + [vp, vp]
+        L.nm_stream_floor.argtypes = [vp, ctypes.c_size_t, vp, ctypes.c_size_t, vp]
         L.nm_autotune.argtypes = [ci, ci, ci, ci, ci, vp, ci, ci, ci, ci, ci, ci, ci, ci, ci, vp,
                                   pi, ctypes.POINTER(cf)]
         L.nm_autotune_tile.argtypes = ([vp] + [ci] * 6 + [pi, ci, ci] + [ci] * 13 +
@@ -67,7 +68,7 @@ def lib():
         L.nm_variant_legal.argtypes = [ci, vp, ci, ci]
         for name in ("nm_prune", "nm_packed_free", "nm_packed_dims", "nm_packed_indices",
                      "nm_packed_values", "nm_packed_mask", "nm_conv2d", "nm_conv2d_res", "nm_maxpool2d",
-                     "nm_avgpool_global", "nm_im2col", "nm_autotune",
+                     "nm_avgpool_global", "nm_im2col", "nm_stream_floor", "nm_autotune",
                      "nm_cache_save", "nm_cache_load", "nm_cache_clear", "nm_cache_size",
                      "nm_force_variant", "nm_variant_legal"):
             getattr(L, name).restype = ci
@@ -308,6 +309,15 @@ def nm_im2col(x, kh: int, kw: int, stride=1, pad=0, dil=1, a=None, stream=None):
     _check(lib().nm_im2col(x.data_ptr(), _dtype_code(x), b, h, w, c, kh, kw, sh, sw, ph, pw, dh, dw,
                            a.data_ptr(), _stream_ptr(stream)))
     return a
+
+
+def nm_stream_floor(x, y, stream=None):
+    """Reads all of x and overwrites all of y (contents unspecified) with one plain
+    streaming kernel: the cost of a layer's traffic alone."""
+    if not (x.is_cuda and y.is_cuda and x.is_contiguous() and y.is_contiguous()):
+        raise ValueError("x and y must be contiguous device tensors")
+    _check(lib().nm_stream_floor(x.data_ptr(), x.numel() * x.element_size(), y.data_ptr(),
+                                 y.numel() * y.element_size(), _stream_ptr(stream)))
 
 
 def nm_autotune(x_dtype: int, b: int, h: int, w: int, cin: int, wp: Packed, has_bias=True,

@@ -4,6 +4,7 @@
 #include <math.h>
 #include <stdarg.h>
 #include <stdio.h>
+#include <stdlib.h>
 #include <string.h>
 
 #include <algorithm>
@@ -761,6 +762,15 @@ int nm_im2col(const void* x, nm_dtype_t dt, int b, int h, int w, int cin, int kh
     return run_im2col(x, dt, b, h, w, cin, kh, kw, sh, sw, ph, pw, dh, dw, ho, wo, a_out, (hipStream_t)stream);
 }
 
+int nm_stream_floor(const void* x, size_t x_bytes, void* y, size_t y_bytes, void* stream)
+{
+    if (!x || !y || ((uintptr_t)x % 16) || ((uintptr_t)y % 16)) {
+        set_error("x and y must be non-null and 16-byte aligned");
+        return NM_ERR_ARG;
+    }
+    return run_stream_floor(x, x_bytes, y, y_bytes, (hipStream_t)stream);
+}
+
 int nm_avgpool_global(const void* x, nm_dtype_t dt, int b, int h, int w, int c, void* y, void* stream)
 {
     if (!x || !y || b < 1 || h < 1 || w < 1 || c < 1 || (dt != NM_F32 && dt != NM_BF16)) {
@@ -884,6 +894,11 @@ int nm_autotune(nm_dtype_t xdt, int b, int h, int w, int cin, const nm_packed_t*
         first.push_back(std::make_pair(t[1], v));
     }
     std::sort(first.begin(), first.end());
+    if (getenv("NM_TUNE_VERBOSE")) {   // the whole field, fastest first: what the choice was made from
+        fprintf(stderr, "nm_autotune %dx%dx%d -> %d, %dx%d, b %d, %d:%d T%d: %zu candidates\n", h, w, cin, wp->cout,
+                wp->kh, wp->kw, b, wp->n, wp->m, wp->tile, first.size());
+        for (const auto& c : first) fprintf(stderr, "  %9.2f us  %s\n", c.first * 1e3f, variant_desc(c.second).name);
+    }
     const int finalists = (int)std::min<size_t>(5, first.size());
     std::vector<std::vector<float>> again(finalists);
     for (int r = 0; r < 7 && finalists > 1; ++r)

@@ -186,6 +186,7 @@ int run_fill_random(void* d, size_t n_elems, nm_dtype_t dt, uint32_t seed, hipSt
 int run_maxpool(const void* x, nm_dtype_t dt, int B, int H, int W, int C, int k, int stride, int pad,
                 int Ho, int Wo, void* y, hipStream_t s);
 int run_avgpool(const void* x, nm_dtype_t dt, int B, int HW, int C, void* y, hipStream_t s);
+int run_stream_floor(const void* x, size_t x_bytes, void* y, size_t y_bytes, hipStream_t s);
 int run_im2col(const void* x, nm_dtype_t dt, int B, int H, int W, int C, int Kh, int Kw, int sh, int sw,
                int ph, int pw, int dh, int dw, int Ho, int Wo, void* a, hipStream_t s);
 

@@ -102,7 +102,41 @@ __global__ __launch_bounds__(256) void im2col_kernel(const T* __restrict__ x, T*
     }
 }
 
+// The traffic of a layer and nothing else: read nx 16-byte units, write ny, both spread over
+// every thread of the grid in grid-stride order (whole 1 KB runs per wavefront), four loads in
+// flight per thread before the first use.  What is read only steers a store that never happens.
+__global__ __launch_bounds__(256) void stream_floor_kernel(const u4v* __restrict__ x, size_t nx,
+                                                           u4v* __restrict__ y, size_t ny)
+{
+    const size_t step = (size_t)gridDim.x * blockDim.x;
+    const size_t i0 = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    unsigned acc = 0;
+    size_t i = i0;
+    for (; i + 3 * step < nx; i += 4 * step) {
+        const u4v a = x[i], b = x[i + step], c = x[i + 2 * step], d = x[i + 3 * step];
+        acc += (a.x ^ b.y) + (c.z ^ d.w);
+    }
+    for (; i < nx; i += step) acc += x[i].x;
+    const u4v v = {1u, 2u, 3u, 4u};
+    for (size_t j = i0; j < ny; j += step) y[j] = v;
+    if (acc == 0x9e3779b9u && ny > 0 && i0 == 0) y[0].x = acc;   // keeps the loads alive
+}
+
 }  // namespace
+
+int run_stream_floor(const void* x, size_t x_bytes, void* y, size_t y_bytes, hipStream_t s)
+{
+    const size_t nx = x_bytes / 16, ny = y_bytes / 16;
+    const size_t most = nx > ny ? nx : ny;
+    // enough workgroups to fill every CU several times over, never more threads than units
+    int grid = (int)((most + 255) / 256);
+    if (grid > 256 * 8) grid = 256 * 8;
+    if (grid < 1) grid = 1;
+    hipLaunchKernelGGL(stream_floor_kernel, dim3(grid), dim3(256), 0, s, reinterpret_cast<const u4v*>(x), nx,
+                       reinterpret_cast<u4v*>(y), ny);
+    NM_HIP_CHECK(hipGetLastError());
+    return NM_OK;
+}
 
 int run_im2col(const void* x, nm_dtype_t dt, int B, int H, int W, int C, int Kh, int Kw, int sh, int sw,
                int ph, int pw, int dh, int dw, int Ho, int Wo, void* a, hipStream_t s)

@@ -181,6 +181,11 @@ int run_maxpool(const void*, nm_dtype_t, int, int, int, int, int, int, int, int,
 int run_avgpool(const void*, nm_dtype_t, int, int, int, void*, hipStream_t) { return NM_OK; }
 int run_im2col(const void*, nm_dtype_t, int, int, int, int, int, int, int, int, int, int, int, int, int, int, void*,
                hipStream_t) { return NM_OK; }
+int run_stream_floor(const void* x, size_t xb, void* y, size_t yb, hipStream_t)
+{
+    CHECK(inside(x, xb) && inside(y, yb));
+    return NM_OK;
+}
 }  // namespace nm
 
 // ------------------------------------------------------------------- driver
@@ -274,6 +279,15 @@ int main(int argc, char** argv)
     CHECK(nm_force_variant(-2) == NM_ERR_ARG && nm_force_variant(nm_variant_count()) == NM_ERR_ARG);
     CHECK(nm_conv2d(nullptr, NM_F32, 1, 1, 1, 1, nullptr, nullptr, 1, 1, 0, 0, 1, 1, 0, nullptr, NM_F32, nullptr) == NM_ERR_ARG);
     CHECK(nm_autotune(NM_F32, 1, 1, 1, 1, nullptr, 0, 1, 1, 0, 0, 1, 1, 0, NM_F32, nullptr, nullptr, nullptr) == NM_ERR_ARG);
+
+    {
+        void* a = dev_alloc(100);
+        void* b = dev_alloc(64);
+        CHECK(nm_stream_floor(a, 100, b, 64, nullptr) == NM_OK);
+        CHECK(nm_stream_floor(nullptr, 100, b, 64, nullptr) == NM_ERR_ARG);
+        CHECK(nm_stream_floor((char*)a + 4, 96, b, 64, nullptr) == NM_ERR_ARG);
+        CHECK(hipFree(a) == hipSuccess && hipFree(b) == hipSuccess);
+    }
 
     // ---- planning, launching, tuning over a grid of layers (ragged tiles, strides, dilation,
     // few input channels, groups wider than a chunk, T = 8 / 32, both tensor types)

@@ -209,3 +209,18 @@ def test_im2col_and_the_unfused_pipeline(layer, batch, bf16):
     assert norm_err(y_unfused.float().cpu().numpy(), ref) <= tol
     assert norm_err(y_fused.float().cpu().numpy(), ref) <= tol
     assert np.array_equal(nm.nm_packed_indices(wp1), nm.nm_packed_indices(wp))   # same kept columns either way
+
+
+def test_stream_floor_touches_exactly_its_ranges():
+    """The measuring kernel: every 16-byte unit of y is overwritten, nothing beyond y's
+    whole units is, x is left alone; sizes that are not multiples of the grid or of 16."""
+    import torch
+    for nx, ny in ((1 << 20, 3 << 18), (1000, 17), (16, 16 * 5000 + 8), (32, 4096), (4096 * 33, 16)):
+        x = torch.full((nx + 16,), 7, dtype=torch.uint8, device="cuda")
+        y = torch.zeros((ny + 64,), dtype=torch.uint8, device="cuda")
+        nm.nm_stream_floor(x[:nx], y[:ny])
+        torch.cuda.synchronize()
+        whole = ny // 16 * 16
+        assert bool((y[:whole].view(torch.int32).view(-1, 4) != 0).all()) if whole else True
+        assert int(y[whole:].sum()) == 0
+        assert int((x != 7).sum()) == 0
