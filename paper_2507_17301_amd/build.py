@@ -68,6 +68,14 @@ def _shapes_spw():
     return [tuple(int(v) for v in m) for m in re.findall(r"X\((\d+),\s*(\d+),\s*(\d+)\)", body)]
 
 
+def _shapes_spr():
+    """(NBLK, WP, NJ) of NMSPR_SHAPES in nm_variants.h."""
+    text = open(os.path.join(CSRC, "nm_variants.h")).read()
+    body = text[text.index("#define NMSPR_SHAPES(X)"):]
+    body = body[:body.index("// Y(")]
+    return [tuple(int(v) for v in m) for m in re.findall(r"X\((\d+),\s*(\d+),\s*(\d+)\)", body)]
+
+
 def _shapes_run():
     """(NBLK, WP, NJ) of NMRUN_SHAPES in nm_variants.h."""
     text = open(os.path.join(CSRC, "nm_variants.h")).read()
@@ -108,6 +116,9 @@ def _jobs():
     for nb, wp, nj in _shapes_spw():
         jobs.append((instsp, os.path.join(OBJDIR, f"nm_conv_sp16_inst_spw_{nb}_{wp}_{nj}.o"),
                      ["-DNM_INST_SPW", f"-DNM_INST_NBLK={nb}", f"-DNM_INST_WP={wp}", f"-DNM_INST_NJ={nj}"]))
+    for nb, wp, nj in _shapes_spr():
+        jobs.append((instsp, os.path.join(OBJDIR, f"nm_conv_sp16_inst_spr_{nb}_{wp}_{nj}.o"),
+                     ["-DNM_INST_SPR", f"-DNM_INST_NBLK={nb}", f"-DNM_INST_WP={wp}", f"-DNM_INST_NJ={nj}"]))
     instrun = os.path.join(CSRC, "nm_conv_run16_inst.hip")
     for nb, wp, nj in _shapes_run():
         jobs.append((instrun, os.path.join(OBJDIR, f"nm_conv_run16_inst_{nb}_{wp}_{nj}.o"),

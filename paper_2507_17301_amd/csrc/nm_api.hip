@@ -129,8 +129,8 @@ size_t lds_bytes(const VariantDesc& d, const nm_packed* wp)
         return std::max(otile, (size_t)d.BP * d.SPC * 128 + (size_t)(4 / d.WP) * d.NJ * d.SPC * 2048);
     if (d.kind >= 2 && d.kind <= 4) {   // up to three stages of the strip [BP][CK] bf16 plus each wave's operands
         const int nchunks = wp->kh * wp->kw * ((wp->cin + d.CK - 1) / d.CK);
-        return std::max(otile, (size_t)std::min(3, nchunks) *
-                                   (d.BP * d.CK * 2 + 4 * d.NJ * (d.CK / 64) * (d.kind == 2 ? 1024 + 256 : 2048)));
+        const size_t ops = d.areg ? 0 : (size_t)4 * d.NJ * (d.CK / 64) * (d.kind == 2 ? 1024 + 256 : 2048);
+        return std::max(otile, (size_t)std::min(3, nchunks) * ((size_t)d.BP * d.CK * 2 + ops));
     }
     if (d.kind == 1) {
         const int opr = d.CK / 8, pstep = 256 / opr, nit = (d.BP * opr + 255) / 256;

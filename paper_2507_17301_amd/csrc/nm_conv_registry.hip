@@ -12,41 +12,47 @@ struct Entry {
 };
 
 #define NM_ENTRY(NB, WP, NJ, CK, SPC, VEC)                                                     \
-    {{"NB" #NB "_WP" #WP "_NJ" #NJ "_CK" #CK "_SPC" #SPC "_V" #VEC, 16 * NB * WP, NB, WP, NJ, CK, SPC, VEC, 0, 1}, \
+    {{"NB" #NB "_WP" #WP "_NJ" #NJ "_CK" #CK "_SPC" #SPC "_V" #VEC, 16 * NB * WP, NB, WP, NJ, CK, SPC, VEC, 0, 1, 0}, \
      &launch_t<NB, WP, NJ, CK, SPC, (VEC) != 0 ? 1 : 0, float, float>,                                 \
      &launch_t<NB, WP, NJ, CK, SPC, (VEC) != 0 ? 1 : 0, bf16_t, bf16_t>},
 #define NM_SHAPE_ENTRIES(NB, WP, NJ) NM_VEC_CHUNKS(NM_ENTRY, NB, WP, NJ)
 
 #define NM_ENTRY16(NB, WP, NJ, SH, CK, SPC)                                                     \
-    {{"B16_NB" #NB "_WP" #WP "_NJ" #NJ "_SH" #SH "_CK" #CK "_SPC" #SPC, 16 * NB * WP, NB, WP, NJ, CK, SPC, 1, 1, SH}, \
+    {{"B16_NB" #NB "_WP" #WP "_NJ" #NJ "_SH" #SH "_CK" #CK "_SPC" #SPC, 16 * NB * WP, NB, WP, NJ, CK, SPC, 1, 1, SH, 0}, \
      nullptr, &launch16_t<NB, WP, NJ, CK, SPC, SH>},
 #define NM_SHAPE_ENTRIES16(NB, WP, NJ, SH) NM16_CHUNKS(NM_ENTRY16, NB, WP, NJ, SH)
 
 // kind 2: sparse matrix instruction, kind 3: dense instruction on zero-filled weights
 #define NM_ENTRYSP(NB, WP, NJ, CK, SP)                                                          \
-    {{"SP" #SP "_NB" #NB "_WP" #WP "_NJ" #NJ "_CK" #CK, 16 * NB * WP, NB, WP, NJ, CK, CK / 64, 1, (SP) ? 2 : 3, 1}, \
+    {{"SP" #SP "_NB" #NB "_WP" #WP "_NJ" #NJ "_CK" #CK, 16 * NB * WP, NB, WP, NJ, CK, CK / 64, 1, (SP) ? 2 : 3, 1, 0}, \
      nullptr, &launch_sp16_t<NB, WP, NJ, CK, (SP) != 0, false>},
 #define NM_SHAPE_ENTRIESSP(NB, WP, NJ) NMSP_CHUNKS(NM_ENTRYSP, NB, WP, NJ)
 // the same with producer wavefronts (same operand tables, same LDS footprint)
 #define NM_ENTRYSPW(NB, WP, NJ, CK, SP)                                                         \
-    {{"SPW" #SP "_NB" #NB "_WP" #WP "_NJ" #NJ "_CK" #CK, 16 * NB * WP, NB, WP, NJ, CK, CK / 64, 1, (SP) ? 2 : 3, 1}, \
+    {{"SPW" #SP "_NB" #NB "_WP" #WP "_NJ" #NJ "_CK" #CK, 16 * NB * WP, NB, WP, NJ, CK, CK / 64, 1, (SP) ? 2 : 3, 1, 0}, \
      nullptr, &launch_sp16_t<NB, WP, NJ, CK, (SP) != 0, true>},
 #define NM_SHAPE_ENTRIESSPW(NB, WP, NJ) NMSPW_CHUNKS(NM_ENTRYSPW, NB, WP, NJ)
 
+// producer wavefronts and register operands
+#define NM_ENTRYSPR(NB, WP, NJ, CK, SP)                                                         \
+    {{"SPR" #SP "_NB" #NB "_WP" #WP "_NJ" #NJ "_CK" #CK, 16 * NB * WP, NB, WP, NJ, CK, CK / 64, 1, (SP) ? 2 : 3, 1, 1}, \
+     nullptr, &launch_sp16_t<NB, WP, NJ, CK, (SP) != 0, true, true>},
+#define NM_SHAPE_ENTRIESSPR(NB, WP, NJ) NMSPR_CHUNKS(NM_ENTRYSPR, NB, WP, NJ)
+
 // kind 4: contiguous kernel-row runs
 #define NM_ENTRYRUN(NB, WP, NJ, KS)                                                             \
-    {{"RUN_NB" #NB "_WP" #WP "_NJ" #NJ "_KS" #KS, 16 * NB * WP, NB, WP, NJ, 64 * KS, KS, 1, 4, 1}, \
+    {{"RUN_NB" #NB "_WP" #WP "_NJ" #NJ "_KS" #KS, 16 * NB * WP, NB, WP, NJ, 64 * KS, KS, 1, 4, 1, 0}, \
      nullptr, &launch_run16_t<NB, WP, NJ, KS>},
 #define NM_SHAPE_ENTRIESRUN(NB, WP, NJ) NMRUN_CHUNKS(NM_ENTRYRUN, NB, WP, NJ)
 
 // kind 5: fp32 MFMA kernel, per-(tile, chunk) number of k-steps (fp32 tensors only)
 #define NM_ENTRYVAR(NB, WP, NJ, CK, SPC)                                                        \
-    {{"VAR_NB" #NB "_WP" #WP "_NJ" #NJ "_CK" #CK "_SPC" #SPC, 16 * NB * WP, NB, WP, NJ, CK, SPC, 1, 5, 1}, \
+    {{"VAR_NB" #NB "_WP" #WP "_NJ" #NJ "_CK" #CK "_SPC" #SPC, 16 * NB * WP, NB, WP, NJ, CK, SPC, 1, 5, 1, 0}, \
      &launch_t<NB, WP, NJ, CK, SPC, 2, float, float>, nullptr},
 #define NM_SHAPE_ENTRIESVAR(NB, WP, NJ) NMVAR_CHUNKS(NM_ENTRYVAR, NB, WP, NJ)
 
 const Entry kEntries[] = {NM_SHAPES(NM_SHAPE_ENTRIES) NM_SCALAR_VARIANTS(NM_ENTRY)
-                          NM16_SHAPES(NM_SHAPE_ENTRIES16) NMSP_SHAPES(NM_SHAPE_ENTRIESSP) NMSPW_SHAPES(NM_SHAPE_ENTRIESSPW)
+                          NM16_SHAPES(NM_SHAPE_ENTRIES16) NMSP_SHAPES(NM_SHAPE_ENTRIESSP) NMSPW_SHAPES(NM_SHAPE_ENTRIESSPW) NMSPR_SHAPES(NM_SHAPE_ENTRIESSPR)
                           NMRUN_SHAPES(NM_SHAPE_ENTRIESRUN) NMVAR_SHAPES(NM_SHAPE_ENTRIESVAR)};
 constexpr int kCount = (int)(sizeof(kEntries) / sizeof(kEntries[0]));
 }  // namespace

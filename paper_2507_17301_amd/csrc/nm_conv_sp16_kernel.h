@@ -50,9 +50,9 @@ typedef __bf16 bf16x __attribute__((ext_vector_type(16)));
 // into registers inside the loop.
 constexpr int kSp16Stages = 3;
 // one stage: the strip [BP][CK] bf16, then per wave the weights (and index words) of its row blocks
-constexpr int sp16_stage_bytes(int BP, int CK, int NJ, bool sparse)
+constexpr int sp16_stage_bytes(int BP, int CK, int NJ, bool sparse, bool areg = false)
 {
-    return BP * CK * 2 + 4 * NJ * (CK / 64) * ((sparse ? 1 : 2) * 1024 + (sparse ? 256 : 0));
+    return BP * CK * 2 + (areg ? 0 : 4 * NJ * (CK / 64) * ((sparse ? 1 : 2) * 1024 + (sparse ? 256 : 0)));
 }
 // (8 consecutive lanes of a 16-byte LDS read are served together: their granules must differ
 // modulo 128 bytes; the extra bit keeps rows r and r + 8 apart modulo 256 bytes as well)
@@ -70,9 +70,18 @@ typedef __attribute__((address_space(3))) void* lds_ptr_t;
 // until the epilogue.  A wave-wide load into LDS occupies the CU's memory path for 16 clocks
 // and stalls its wavefront while the path is backed up, so a wavefront that does both jobs
 // alternates between them; split, the two overlap.  Both roles execute the same barriers.
-template <int NBLK, int WP, int NJ, int CK, bool SPARSE, bool SPEC>
+//
+// AREG = true (only with SPEC): the weights and index words do not pass through LDS.  Each
+// contracting wavefront loads the operands of its own row blocks straight into registers,
+// one chunk ahead (they are laid out in lane order by nm_prune, so these are plain
+// coalesced 16-byte loads, and the compiler counts them itself: a contracting wavefront
+// issues no other vector-memory load inside the loop).  A stage is then the strip alone,
+// which halves the LDS traffic of tiles whose wavefronts hold four row blocks, and the
+// strip reads run four deep instead of two.
+template <int NBLK, int WP, int NJ, int CK, bool SPARSE, bool SPEC, bool AREG = false>
 __global__ __launch_bounds__(SPEC ? 512 : 256) void nm_conv_sp16_kernel(const ConvParams p)
 {
+    static_assert(!AREG || SPEC, "register operands need the producer wavefronts");
     constexpr int BPW = 16 * NBLK;
     constexpr int BP = BPW * WP;
     constexpr int WC = 4 / WP;
@@ -80,7 +89,7 @@ __global__ __launch_bounds__(SPEC ? 512 : 256) void nm_conv_sp16_kernel(const Co
     constexpr int AH = SPARSE ? 1 : 2;           // 16-byte A operands per k-step and row block
     constexpr int RB = CK * 2;                   // bytes per pixel row of a stage
     const int D = p.nchunks < kSp16Stages ? p.nchunks : kSp16Stages;   // stages in use (and allocated)
-    constexpr int STAGE = sp16_stage_bytes(BP, CK, NJ, SPARSE);
+    constexpr int STAGE = sp16_stage_bytes(BP, CK, NJ, SPARSE, AREG);
     static_assert(CK % 64 == 0, "a chunk is a whole number of 64-channel k-steps");
 
     extern __shared__ __attribute__((aligned(16))) char lds8[];   // [D][BP][RB]
@@ -176,7 +185,7 @@ __global__ __launch_bounds__(SPEC ? 512 : 256) void nm_conv_sp16_kernel(const Co
     constexpr unsigned WCH = KS * AH * 1024;     // weight bytes per (row block, chunk)
     constexpr unsigned ICH = KS * 16;            // index bytes per (tile, chunk)
     constexpr int AW = NJ * KS * (AH * 1024 + (SPARSE ? 256 : 0));   // operand bytes per wave and stage
-    constexpr int NOPS = NJ * KS * (AH + (SPARSE ? 1 : 0));          // operand loads per wave and stage
+    constexpr int NOPS = AREG ? 0 : NJ * KS * (AH + (SPARSE ? 1 : 0));   // operand loads (into LDS) per wave and stage
     constexpr int NL = NIT + NOPS;                                   // loads per wave and stage
     static_assert(NL <= 63, "a stage's loads must fit the memory counter");
     const unsigned wvoff = (unsigned)lane * 16;
@@ -227,7 +236,7 @@ __global__ __launch_bounds__(SPEC ? 512 : 256) void nm_conv_sp16_kernel(const Co
 #pragma unroll
         for (int it = 0; it < NIT; ++it) fetch_item(it, stage);
         fetch_advance();
-        fetch_ops(stage);
+        if constexpr (!AREG) fetch_ops(stage);
     };
     // bias of this lane's rows, requested first: the accumulators start from it
     const bool fast = (p.tile % 4 == 0) && (p.Cout % 4 == 0);
@@ -388,7 +397,88 @@ __global__ __launch_bounds__(SPEC ? 512 : 256) void nm_conv_sp16_kernel(const Co
         wstage = wstage + 1 == D ? 0 : wstage + 1;
     };
 
-    for (int c = 0; c < p.nchunks; ++c) chunk(c);
+    if constexpr (AREG) {
+        // ---- operands in registers, two sets, one chunk ahead ------------------------
+        struct Ops {
+            u4v a[NJ][KS][AH];
+            unsigned idx[NJ][KS];
+        };
+        auto load_ops = [&](Ops& o, int c) {
+            const int cc = c < p.nchunks ? c : p.nchunks - 1;   // past the end: a valid chunk, never used
+#pragma unroll
+            for (int jj = 0; jj < NJ; ++jj)
+#pragma unroll
+                for (int s2 = 0; s2 < KS; ++s2) {
+#pragma unroll
+                    for (int h = 0; h < AH; ++h)
+                        o.a[jj][s2][h] = __builtin_amdgcn_raw_buffer_load_b128(
+                            wr, wvoff + wsoff[jj] + (unsigned)cc * WCH + (unsigned)(s2 * AH + h) * 1024, 0, 0);
+                    if constexpr (SPARSE)
+                        o.idx[jj][s2] = __builtin_amdgcn_raw_buffer_load_b32(
+                            rr, (unsigned)(q * KS + s2) * 4 + isoff[jj] + (unsigned)cc * ICH, 0, 0);
+                }
+        };
+        constexpr int RD = NM < 4 ? NM : 4;          // strip reads in flight
+        auto chunk_r = [&](const Ops& o) {
+            __builtin_amdgcn_s_barrier();            // the producers' loads of this chunk have landed
+            const unsigned sbase = lds0 + (unsigned)(rstage * STAGE);
+            unsigned raddr[KS][2];
+#pragma unroll
+            for (int s2 = 0; s2 < KS; ++s2)
+#pragma unroll
+                for (int h = 0; h < 2; ++h) raddr[s2][h] = sbase + roff[s2][h];
+            auto read_b = [&](int m, u4v (&dst)[2]) {
+                const int s2 = m / NBLK, b = m % NBLK;
+                asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(dst[0]) : "v"(raddr[s2][0]), "n"(b * 16 * RB) : "memory");
+                asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(dst[1]) : "v"(raddr[s2][1]), "n"(b * 16 * RB) : "memory");
+            };
+            u4v ring[RD][2];
+#pragma unroll
+            for (int m = 0; m < RD - 1; ++m) read_b(m, ring[m]);
+#pragma unroll
+            for (int m = 0; m < NM; ++m) {
+                const int s2 = m / NBLK, b = m % NBLK;
+                if (m + RD - 1 < NM) read_b(m + RD - 1, ring[(m + RD - 1) % RD]);
+                // reads m .. min(m + RD, NM) - 1 are outstanding, two instructions each; the oldest must be back
+                const int ahead = (m + RD - 1 < NM ? RD : NM - m) - 1;
+                if (ahead == 3) asm volatile("s_waitcnt lgkmcnt(6)" : "+v"(ring[m % RD][0]), "+v"(ring[m % RD][1]));
+                else if (ahead == 2) asm volatile("s_waitcnt lgkmcnt(4)" : "+v"(ring[m % RD][0]), "+v"(ring[m % RD][1]));
+                else if (ahead == 1) asm volatile("s_waitcnt lgkmcnt(2)" : "+v"(ring[m % RD][0]), "+v"(ring[m % RD][1]));
+                else asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(ring[m % RD][0]), "+v"(ring[m % RD][1]));
+                const u4v(&bo)[2] = ring[m % RD];
+#pragma unroll
+                for (int jj = 0; jj < NJ; ++jj) {
+                    if constexpr (SPARSE) {
+                        const bf16x bv = __builtin_shufflevector(__builtin_bit_cast(bf8x, bo[0]),
+                                                                 __builtin_bit_cast(bf8x, bo[1]), 0, 1, 2, 3, 4,
+                                                                 5, 6, 7, 8, 9, 10, 11, 12, 13, 14, 15);
+                        acc[jj][b] = __builtin_amdgcn_smfmac_f32_16x16x64_bf16(
+                            __builtin_bit_cast(bf8x, o.a[jj][s2][0]), bv, acc[jj][b], (int)o.idx[jj][s2], 0, 0);
+                    } else {
+#pragma unroll
+                        for (int h = 0; h < 2; ++h)
+                            acc[jj][b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
+                                __builtin_bit_cast(bf8x, o.a[jj][s2][h]), __builtin_bit_cast(bf8x, bo[h]),
+                                acc[jj][b], 0, 0, 0);
+                    }
+                }
+                __builtin_amdgcn_sched_barrier(0);
+            }
+            rstage = rstage + 1 == D ? 0 : rstage + 1;
+        };
+        Ops oa, ob;
+        load_ops(oa, 0);
+        int c = 0;
+        for (; c + 1 < p.nchunks; c += 2) {
+            load_ops(ob, c + 1);
+            chunk_r(oa);
+            load_ops(oa, c + 2);
+            chunk_r(ob);
+        }
+        if (c < p.nchunks) chunk_r(oa);
+    } else {
+        for (int c = 0; c < p.nchunks; ++c) chunk(c);
+    }
 
     // ---- epilogue: bias, ReLU, round to bf16, NHWC store ------------------------
     bf16_t* __restrict__ y = reinterpret_cast<bf16_t*>(p.y);
@@ -447,11 +537,11 @@ __global__ __launch_bounds__(SPEC ? 512 : 256) void nm_conv_sp16_kernel(const Co
     }
 }
 
-template <int NBLK, int WP, int NJ, int CK, bool SPARSE, bool SPEC>
+template <int NBLK, int WP, int NJ, int CK, bool SPARSE, bool SPEC, bool AREG>
 int launch_sp16_t(const ConvParams& p, hipStream_t s)
 {
-    auto kern = nm_conv_sp16_kernel<NBLK, WP, NJ, CK, SPARSE, SPEC>;
-    constexpr size_t stage = sp16_stage_bytes(16 * NBLK * WP, CK, NJ, SPARSE);
+    auto kern = nm_conv_sp16_kernel<NBLK, WP, NJ, CK, SPARSE, SPEC, AREG>;
+    constexpr size_t stage = sp16_stage_bytes(16 * NBLK * WP, CK, NJ, SPARSE, AREG);
     // the most this kernel may ever be launched with: the full ring, or what the CU has
     constexpr size_t ring = kSp16Stages * stage > out_tile_bytes(16 * NBLK * WP, (4 / WP) * NJ * 16, 2)
                                 ? kSp16Stages * stage : out_tile_bytes(16 * NBLK * WP, (4 / WP) * NJ * 16, 2);

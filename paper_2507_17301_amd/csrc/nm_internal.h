@@ -165,6 +165,7 @@ struct VariantDesc {
                // 4 = bf16 dense kernel on contiguous kernel-row runs (very few input channels),
                // 5 = fp32 MFMA kernel that runs only the k-steps holding kept columns of each (tile, chunk)
     int share; // kind 1: row blocks fed from one gathered operand
+    int areg;  // kinds 2, 3: 1 = weights and index words go straight to registers, the LDS stages hold the strip alone
 };
 
 // Allows kernel `fn` more than 64 KB of dynamic LDS on the current device; done once per

@@ -67,6 +67,15 @@
     Y(NB, WP, NJ, 64, 1) Y(NB, WP, NJ, 128, 1) Y(NB, WP, NJ, 256, 1) \
     Y(NB, WP, NJ, 64, 0) Y(NB, WP, NJ, 128, 0) Y(NB, WP, NJ, 256, 0)
 
+// Producer wavefronts, and the weights loaded straight into the contracting wavefronts'
+// registers (the LDS stages hold the strip alone).
+// X(NBLK, WP, NJ)
+#define NMSPR_SHAPES(X) X(4, 2, 4) X(8, 1, 2) X(4, 1, 4) X(2, 2, 4) X(8, 2, 4) X(4, 2, 2) X(8, 1, 4) X(6, 1, 2)
+// Y(NBLK, WP, NJ, CK, SP)
+#define NMSPR_CHUNKS(Y, NB, WP, NJ)             \
+    Y(NB, WP, NJ, 64, 1) Y(NB, WP, NJ, 128, 1) \
+    Y(NB, WP, NJ, 64, 0) Y(NB, WP, NJ, 128, 0)
+
 // bf16 kernel for layers with very few input channels (contiguous kernel-row
 // runs, one chunk of KS 64-element k-steps).
 // X(NBLK, WP, NJ)

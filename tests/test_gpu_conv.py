@@ -136,7 +136,7 @@ def test_every_variant_bf16(n, m, tile, cin, ksize):
     wp = nm.nm_prune(w, n, m, tile, nm.NM_BF16)
     xd = torch.from_numpy(x).cuda().to(torch.bfloat16)
     bd = torch.from_numpy(bias).cuda()
-    ran = ran16 = ran_sp = ran_dn = ran_pw = 0
+    ran = ran16 = ran_sp = ran_dn = ran_pw = ran_pr = 0
     try:
         for v in range(nm.nm_variant_count()):
             if not nm.nm_variant_legal(v, wp, nm.NM_BF16, nm.NM_BF16):
@@ -151,14 +151,15 @@ def test_every_variant_bf16(n, m, tile, cin, ksize):
             ran_sp += nm.nm_variant_name(v).startswith("SP1")
             ran_dn += nm.nm_variant_name(v).startswith("SP0")
             ran_pw += nm.nm_variant_name(v).startswith("SPW")   # the same kernels with producer wavefronts
+            ran_pr += nm.nm_variant_name(v).startswith("SPR")   # ... and the weights loaded straight into registers
     finally:
         nm.nm_force_variant(-1)
     assert ran >= 9 and ran16 >= 5
     if cin % 64 == 0:
-        assert ran_dn >= 14 and ran_pw >= 8
+        assert ran_dn >= 14 and ran_pw >= 8 and ran_pr >= 6
         assert (ran_sp >= 14) == (n <= 2 and m % 4 == 0)
     else:
-        assert ran_sp == 0 and ran_dn == 0 and ran_pw == 0
+        assert ran_sp == 0 and ran_dn == 0 and ran_pw == 0 and ran_pr == 0
 
 
 # name, H, W, Cin, Cout, Kh, Kw, stride, pad, dil, n, m, tile  | batch | the kernel-row-run kernel applies

@@ -64,7 +64,7 @@ def test_residual_fp32():
 
 def test_residual_bf16_every_kernel_family():
     # 64 channels, 2:4: fp32-MFMA kernel on bf16 data, gather kernel, sparse and dense instruction, both also with producer wavefronts
-    _residual_case(L("res16_3x3", 12, 10, 64, 80, 3, 3, 1, 1, 1, 2, 4, 16), 3, True, 52, {"NB4", "B16", "SP1", "SP0", "SPW1", "SPW0"})
+    _residual_case(L("res16_3x3", 12, 10, 64, 80, 3, 3, 1, 1, 1, 2, 4, 16), 3, True, 52, {"NB4", "B16", "SP1", "SP0", "SPW1", "SPW0", "SPR1", "SPR0"})
     _residual_case(L("res16_stem", 20, 20, 3, 32, 7, 7, 2, 3, 1, 1, 1, 16), 2, True, 53, {"RUN"})
     _residual_case(L("res16_cout37", 9, 9, 64, 37, 1, 1, 1, 0, 1, 2, 4, 16), 2, True, 54)
 
