@@ -118,8 +118,14 @@ int nm_packed_mask(const nm_packed_t* wp, uint8_t* mask_host);
  * fp32 inputs are multiplied in fp32 on the matrix cores with fp32
  * accumulation; bf16 inputs are multiplied exactly and accumulated in fp32;
  * bf16 outputs are rounded to nearest even once.  The call only enqueues work
- * on the stream and never synchronises.  The kernel variant is the one
- * nm_autotune cached for this shape, else nm_force_variant's, else a
+ * on the stream and never synchronises -- with one exception: a K-split variant
+ * (name ending in "_S<n>", only ever chosen by the tuner or the test hook) keeps
+ * its partial sums in a library-owned workspace per device, and the first call
+ * that needs a larger one than exists allocates it (nm_autotune sizes it for the
+ * shapes it tunes; under stream capture such a call fails with NM_ERR_ALLOC
+ * instead).  Calls that overlap on one device
+ * and both run a K-split variant race on that workspace.  The kernel variant is
+ * the one nm_autotune cached for this shape, else nm_force_variant's, else a
  * deterministic default.  Errors: NM_ERR_ARG, NM_ERR_SHAPE, NM_ERR_UNSUPPORTED,
  * NM_ERR_HIP.
  */
@@ -233,6 +239,10 @@ int nm_autotune_tile(const float* w_host, int cout, int kh, int kw, int cin, int
                      int stride_h, int stride_w, int pad_h, int pad_w, int dil_h, int dil_w,
                      int relu, nm_dtype_t y_dtype, void* hip_stream,
                      nm_packed_t** out, int* best_tile, float* ms_per_candidate);
+
+/* Frees the workspaces that K-split variants grew (one per device that ran one); the next
+ * call that needs one allocates it again.  Waits for the kernels still using them. */
+int nm_workspace_free(void);
 
 /* Tuning cache: text file, one line per entry; the first line names the device it was
  * written on.  Loading merges into the cache; entries made on another kind of device

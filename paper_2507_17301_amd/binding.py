@@ -69,7 +69,7 @@ def lib():
         for name in ("nm_prune", "nm_packed_free", "nm_packed_dims", "nm_packed_indices",
                      "nm_packed_values", "nm_packed_mask", "nm_conv2d", "nm_conv2d_res", "nm_maxpool2d",
                      "nm_avgpool_global", "nm_im2col", "nm_stream_floor", "nm_autotune",
-                     "nm_cache_save", "nm_cache_load", "nm_cache_clear", "nm_cache_size",
+                     "nm_cache_save", "nm_cache_load", "nm_cache_clear", "nm_cache_size", "nm_workspace_free",
                      "nm_force_variant", "nm_variant_legal"):
             getattr(L, name).restype = ci
         _lib = L
@@ -360,6 +360,10 @@ def nm_cache_save(path: str):
 
 def nm_cache_load(path: str):
     _check(lib().nm_cache_load(path.encode()))
+
+
+def nm_workspace_free():
+    _check(lib().nm_workspace_free())
 
 
 def nm_cache_clear():

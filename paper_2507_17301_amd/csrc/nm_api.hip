@@ -175,6 +175,13 @@ bool variant_legal(int v, const nm_packed* wp, nm_dtype_t xdt, const RunArgs* ra
         if (xdt != NM_BF16 || wp->value_dtype != NM_BF16) return false;
         if (d.share != 1 && d.share != wp->rbpt) return false;
     }
+    if (d.ksplit > 1) {
+        // every split must own at least one chunk of the K axis
+        const Prepack* pp = find_prepack(wp, d);
+        if (!pp) return false;
+        const int cps = (pp->geom.nchunks + d.ksplit - 1) / d.ksplit;
+        if ((d.ksplit - 1) * cps >= pp->geom.nchunks) return false;
+    }
     if (d.kind == 4 && ra) {
         // a kernel row must be one contiguous, 4-byte aligned run of every pixel
         if (ra->dw != 1 || (ra->sw * wp->cin) % 2 != 0 || (ra->w * wp->cin) % 2 != 0) return false;
@@ -267,7 +274,10 @@ void fill_params(ConvParams& p, const VariantDesc& d, const Prepack& pp, const n
     const int rb_per_wg = (4 / d.WP) * d.NJ;
     p.n_ptiles = (g.P + d.BP - 1) / d.BP;
     p.n_cblocks = (wp->n_rowblocks + rb_per_wg - 1) / rb_per_wg;
-    p.n_wg = p.n_ptiles * p.n_cblocks;
+    p.ksplit = d.ksplit > 1 ? d.ksplit : 1;
+    p.cps = (pp.geom.nchunks + p.ksplit - 1) / p.ksplit;
+    p.partial = nullptr;   // the caller points it at a workspace of split_bytes()
+    p.n_wg = p.n_ptiles * p.n_cblocks * p.ksplit;
     p.wg_per_xcd = (p.n_wg + 7) / 8;
     magic_div((unsigned)(g.Ho * g.Wo), &p.howo_mul, &p.howo_shift);
     magic_div((unsigned)g.Wo, &p.wo_mul, &p.wo_shift);
@@ -289,6 +299,7 @@ int heuristic_variant(const nm_packed* wp, int P, nm_dtype_t xdt, const RunArgs*
     for (int v = 0; v < variant_count(); ++v) {
         if (!variant_legal(v, wp, xdt, ra)) continue;
         const VariantDesc& d = variant_desc(v);
+        if (d.ksplit > 1) continue;   // a K split needs a workspace: only where the tuner has shown that it pays
         const int rb_per_wg = (4 / d.WP) * d.NJ;
         const long n_pt = (P + d.BP - 1) / d.BP;
         const long n_cb = (wp->n_rowblocks + rb_per_wg - 1) / rb_per_wg;
@@ -307,6 +318,50 @@ int heuristic_variant(const nm_packed* wp, int P, nm_dtype_t xdt, const RunArgs*
         }
     }
     return best;
+}
+
+// ---- workspace for the partial sums of K-split variants -----------------------------------
+// One grow-only device buffer per device, shared by every call on that device (calls that
+// overlap on different streams and both run a K-split variant would race on it: such variants
+// are chosen only by the tuner or the test hook, and a serving loop that overlaps convolutions
+// should not tune with them).  Growing it allocates, which a stream under capture cannot do.
+size_t split_bytes(const VariantDesc& d, const Geometry& g, const nm_packed* wp)
+{
+    return d.ksplit > 1 ? (size_t)d.ksplit * (size_t)g.P * (size_t)wp->cout * sizeof(float) : 0;
+}
+
+struct Workspace {
+    float* ptr = nullptr;
+    size_t bytes = 0;
+};
+std::mutex g_ws_mu;
+std::map<int, Workspace> g_ws;
+
+// rc NM_OK and *out = a buffer of at least `bytes`, or an error; with may_alloc false the
+// buffer must already be large enough
+int get_workspace(int dev, size_t bytes, bool may_alloc, float** out)
+{
+    std::lock_guard<std::mutex> lk(g_ws_mu);
+    Workspace& w = g_ws[dev];
+    if (w.bytes < bytes) {
+        if (!may_alloc) {
+            set_error("the K-split workspace holds %zu bytes, this call needs %zu and may not allocate", w.bytes, bytes);
+            return NM_ERR_ALLOC;
+        }
+        (void)hipFree(w.ptr);   // waits for the kernels still using it
+        w.ptr = nullptr;
+        w.bytes = 0;
+        const size_t want = (bytes + ((size_t)1 << 20) - 1) & ~(((size_t)1 << 20) - 1);
+        const hipError_t e = hipMalloc(reinterpret_cast<void**>(&w.ptr), want);
+        if (e != hipSuccess) {
+            w.ptr = nullptr;
+            set_error("hipMalloc(%zu) for the K-split workspace failed: %s", want, hipGetErrorString(e));
+            return NM_ERR_ALLOC;
+        }
+        w.bytes = want;
+    }
+    *out = w.ptr;
+    return NM_OK;
 }
 
 int check_conv_args(const void* x, nm_dtype_t xdt, int cin, const nm_packed* wp, void* y,
@@ -698,7 +753,18 @@ static int conv2d_impl(const void* x, nm_dtype_t xdt, int b, int h, int w, int c
     fill_params(p, d, *find_prepack(wp, d, (pw * wp->cin) % 2), wp, x, y, bias, b, h, w, g, sh, sw, ph, pw,
                 dh, dw, relu, xdt == NM_F32 ? 4 : 2);
     p.res = res;
+    if (d.ksplit > 1) {
+        const size_t need = split_bytes(d, g, wp);
+        {
+            // growing the workspace allocates, which a stream under capture must not do
+            hipStreamCaptureStatus cs = hipStreamCaptureStatusNone;
+            (void)hipStreamIsCapturing((hipStream_t)stream, &cs);
+            rc = get_workspace(wp->device, need, cs == hipStreamCaptureStatusNone, &p.partial);
+        }
+        if (rc != NM_OK) return rc;
+    }
     rc = launch_conv(v, xdt, ydt, p, (hipStream_t)stream);
+    if (rc == NM_OK && d.ksplit > 1) rc = run_splitk_reduce(p, ydt, (hipStream_t)stream);
     if (rc == NM_OK) g_last_variant = v;
     return rc;
 }
@@ -863,11 +929,18 @@ int nm_autotune(nm_dtype_t xdt, int b, int h, int w, int cin, const nm_packed_t*
         const VariantDesc& d = variant_desc(v);
         const Prepack* pp = find_prepack(wp, d, (pw * wp->cin) % 2);
         ConvParams p;
+        float* partial = nullptr;
+        if (d.ksplit > 1) {   // sized here, once: nm_conv2d then finds the workspace large enough
+            rc_t = get_workspace(wp->device, split_bytes(d, g, wp), true, &partial);
+            if (rc_t != NM_OK) return -1.f;
+        }
         if (hipEventRecord(e0, s) != hipSuccess) { rc_t = NM_ERR_HIP; return -1.f; }
         for (int i = 0; i < reps; ++i) {
             char* set = dpool + (xbytes + ybytes) * (turn++ % nbuf);
             fill_params(p, d, *pp, wp, set, set + xbytes, dbias, b, h, w, g, sh, sw, ph, pw, dh, dw, relu, es);
+            p.partial = partial;
             rc_t = launch_conv(v, xdt, ydt, p, s);
+            if (rc_t == NM_OK && d.ksplit > 1) rc_t = run_splitk_reduce(p, ydt, s);
             if (rc_t != NM_OK) return -1.f;
         }
         float ms = 0.f;
@@ -886,6 +959,12 @@ int nm_autotune(nm_dtype_t xdt, int b, int h, int w, int cin, const nm_packed_t*
     std::vector<std::pair<float, int>> first;
     for (int v = 0; v < variant_count(); ++v) {
         if (!variant_legal(v, wp, xdt, &ra)) continue;
+        {   // a K split is worth its second kernel only where the output tiles alone leave most CUs idle
+            const VariantDesc& d = variant_desc(v);
+            const long tiles = (long)((g.P + d.BP - 1) / d.BP) *
+                               ((wp->n_rowblocks + (4 / d.WP) * d.NJ - 1) / ((4 / d.WP) * d.NJ));
+            if (d.ksplit > 1 && (tiles > kNumCU / 2 || tiles * d.ksplit > 4 * kNumCU)) continue;
+        }
         if (time_group(v, 1) < 0.f) { cleanup(); return rc_t; }
         float t[3];
         for (int r = 0; r < 3; ++r)
@@ -969,6 +1048,16 @@ int nm_autotune_tile(const float* w, int cout, int kh, int kw, int cin, int n, i
         }
     }
     *out = best;
+    return NM_OK;
+}
+
+int nm_workspace_free(void)
+{
+    std::lock_guard<std::mutex> lk(g_ws_mu);
+    for (auto& kv : g_ws) {
+        (void)hipFree(kv.second.ptr);   // waits for the kernels still using it
+        kv.second = Workspace();
+    }
     return NM_OK;
 }
 

@@ -235,8 +235,15 @@ __global__ __launch_bounds__(256) void nm_conv_kernel(const ConvParams p)
     const int bid = blockIdx.x;
     const int logical = (bid & 7) * p.wg_per_xcd + (bid >> 3);
     if (logical >= p.n_wg) return;
-    const int cblock = logical % p.n_cblocks;
-    const int ptile = logical / p.n_cblocks;
+    // K split (p.ksplit > 1): the workgroups of one output tile share the K axis, split
+    // `ks` contracts chunks [c_begin, c_end) and leaves its partial sums in p.partial
+    const int n_out_tiles = p.n_ptiles * p.n_cblocks;
+    const int ks = p.ksplit > 1 ? logical / n_out_tiles : 0;
+    const int otile = logical - ks * n_out_tiles;
+    const int c_begin = p.ksplit > 1 ? ks * p.cps : 0;
+    const int c_end = p.ksplit > 1 ? (c_begin + p.cps < p.nchunks ? c_begin + p.cps : p.nchunks) : p.nchunks;
+    const int cblock = otile % p.n_cblocks;
+    const int ptile = otile / p.n_cblocks;
     const int p0 = ptile * BP;
 
     const int wpx = wave % WP;            // position along pixels
@@ -287,7 +294,13 @@ __global__ __launch_bounds__(256) void nm_conv_kernel(const ConvParams p)
     // Fetch iterator: the chunk that the next fetch brings in, as (chunk id, tap
     // row, tap column, first channel); it runs two chunks ahead of the
     // contraction and stays on the last chunk once it gets there.
-    int f_c = 0, f_kh = 0, f_kw = 0, f_ci0 = 0;
+    int f_c = c_begin, f_kh = 0, f_kw = 0, f_ci0 = 0;
+    if (VEC && c_begin > 0) {   // a later split starts inside the K axis
+        const int tap = c_begin / p.ncpt;
+        f_ci0 = (c_begin - tap * p.ncpt) * CK;
+        f_kh = tap / p.Kw;
+        f_kw = tap - f_kh * p.Kw;
+    }
     auto retap = [&]() {   // per-pixel offsets of the tap (f_kh, f_kw)
         const int dhh = f_kh * p.dh, dww = f_kw * p.dw;
         const unsigned tapoff = (unsigned)((dhh * p.W + dww) * p.Cin) * ES;
@@ -318,7 +331,7 @@ __global__ __launch_bounds__(256) void nm_conv_kernel(const ConvParams p)
         }
     };
     auto fetch_advance = [&]() {
-        const int adv = f_c + 1 < p.nchunks ? 1 : 0;
+        const int adv = f_c + 1 < c_end ? 1 : 0;
         f_c += adv;
         if constexpr (VEC) {
             const int nci = f_ci0 + CK;
@@ -385,11 +398,11 @@ __global__ __launch_bounds__(256) void nm_conv_kernel(const ConvParams p)
         const int j = rb / p.rbpt;
         const int rit = (rb - j * p.rbpt) * 16 + q * 4;
         const int co = j * p.tile + rit;
-        if (bias_first && p.bias && rb < p.n_rowblocks && rit < p.tile && co < p.Cout)
-            bb0[jj] = *reinterpret_cast<const f4*>(p.bias + co);
+        if (bias_first && p.bias && p.ksplit <= 1 && rb < p.n_rowblocks && rit < p.tile && co < p.Cout)
+            bb0[jj] = *reinterpret_cast<const f4*>(p.bias + co);   // (with a K split the bias is added when the partial sums meet)
     }
 #pragma unroll
-    for (int jj = 0; jj < NJ; ++jj) load_ops(opsA[jj], jj, 0);
+    for (int jj = 0; jj < NJ; ++jj) load_ops(opsA[jj], jj, c_begin);
     if constexpr (VEC) retap();
 #pragma unroll
     for (int it = 0; it < NST; ++it) fetch_item(it);
@@ -435,7 +448,7 @@ __global__ __launch_bounds__(256) void nm_conv_kernel(const ConvParams p)
     // one.  Past the last chunk the same code re-fetches the last chunk and
     // writes it to the buffer nobody reads.
     auto chunk = [&](int c, const int parity, StepOps<SPC> (&cur)[NJ], StepOps<SPC> (&nxt)[NJ]) {
-        const int cn = c + 1 < p.nchunks ? c + 1 : c;
+        const int cn = c + 1 < c_end ? c + 1 : c;
         float* const wbuf = lds + (parity ^ 1) * (CK * SP);
         const unsigned rbuf = (unsigned)(parity * (CK * SP) * 4);
         const unsigned l128 = lane128 + rbuf, l64 = lane64 + rbuf, l32 = lane32 + rbuf;
@@ -522,20 +535,20 @@ __global__ __launch_bounds__(256) void nm_conv_kernel(const ConvParams p)
 
     // The loop branch costs about as much as two MFMAs, so short chunk bodies are
     // unrolled four times, long ones twice.
-    int c = 0;
+    int c = c_begin;
     if constexpr (NM <= 32) {
-        for (; c + 3 < p.nchunks; c += 4) {
+        for (; c + 3 < c_end; c += 4) {
             chunk(c, 0, opsA, opsB);
             chunk(c + 1, 1, opsB, opsA);
             chunk(c + 2, 0, opsA, opsB);
             chunk(c + 3, 1, opsB, opsA);
         }
     }
-    for (; c + 1 < p.nchunks; c += 2) {
+    for (; c + 1 < c_end; c += 2) {
         chunk(c, 0, opsA, opsB);
         chunk(c + 1, 1, opsB, opsA);
     }
-    if (c < p.nchunks) chunk(c, 0, opsA, opsB);
+    if (c < c_end) chunk(c, 0, opsA, opsB);
 
     // ---- epilogue: bias, ReLU, cast, NHWC store ------------------------------
     TOUT* __restrict__ y = reinterpret_cast<TOUT*>(p.y);
@@ -546,6 +559,33 @@ __global__ __launch_bounds__(256) void nm_conv_kernel(const ConvParams p)
         return OFF1 + n;
     };
     constexpr int WGC = WC * NJ * 16;     // output channels of the workgroup
+    if (p.ksplit > 1) {
+        // partial sums of this split, fp32, laid out like the output: [split][pixel][channel];
+        // bias, residual and activation are applied where the splits are added up
+        float* __restrict__ part = p.partial + (size_t)ks * (size_t)p.P * (size_t)p.Cout;
+#pragma unroll
+        for (int jj = 0; jj < NJ; ++jj) {
+            const int rb = rb0 + jj;
+            if (rb >= p.n_rowblocks) continue;
+            const int j = rb / p.rbpt;
+            const int rit = (rb - j * p.rbpt) * 16 + q * 4;
+            const int co = j * p.tile + rit;
+#pragma unroll
+            for (int b = 0; b < NBLK; ++b) {
+                const int pp = p0 + wpix + pixel_of(b);
+                if (pp >= p.P) continue;
+                float* dst = part + (size_t)pp * (size_t)p.Cout + co;
+                if (fast) {
+                    if (rit < p.tile && co < p.Cout) *reinterpret_cast<f4*>(dst) = acc[jj][b];
+                } else {
+#pragma unroll
+                    for (int r = 0; r < 4; ++r)
+                        if (rit + r < p.tile && co + r < p.Cout) dst[r] = acc[jj][b][r];
+                }
+            }
+        }
+        return;
+    }
     if (WGC * (int)sizeof(TOUT) >= 128 && tile_out_ok<TOUT>(p)) {
         // through the LDS tile (every wavefront is past its last strip read: the chunk ends with a barrier)
         constexpr int PITCH = tile_pitch<TOUT>(WGC);

@@ -149,6 +149,11 @@ struct ConvParams {
     unsigned x_elems;  // elements of x
     unsigned x_bytes;  // size of x in bytes (< 2 GiB), the range of the buffer descriptor
     unsigned wfrag_bytes, rows_bytes;
+    // K split (fp32 MFMA kernel): ksplit workgroups share one output tile, each contracts cps
+    // chunks and writes its partial sums to partial[split][P][Cout] (fp32); a second kernel adds
+    // them up and applies bias, residual and activation.  ksplit <= 1: no split, partial unused.
+    float* partial;
+    int ksplit, cps;
 };
 
 struct VariantDesc {
@@ -165,6 +170,7 @@ struct VariantDesc {
                // 4 = bf16 dense kernel on contiguous kernel-row runs (very few input channels),
                // 5 = fp32 MFMA kernel that runs only the k-steps holding kept columns of each (tile, chunk)
     int share; // kind 1: row blocks fed from one gathered operand
+    int ksplit; // kinds 0, 5: workgroups that share the K axis of one output tile (1 = no split)
     int areg;  // kinds 2, 3: 1 = weights and index words go straight to registers, the LDS stages hold the strip alone
 };
 
@@ -187,6 +193,8 @@ int run_fill_random(void* d, size_t n_elems, nm_dtype_t dt, uint32_t seed, hipSt
 int run_maxpool(const void* x, nm_dtype_t dt, int B, int H, int W, int C, int k, int stride, int pad,
                 int Ho, int Wo, void* y, hipStream_t s);
 int run_avgpool(const void* x, nm_dtype_t dt, int B, int HW, int C, void* y, hipStream_t s);
+// adds up the partial sums of a K split: y = act(sum_s partial[s] + bias + residual)
+int run_splitk_reduce(const ConvParams& p, nm_dtype_t ydt, hipStream_t s);
 int run_stream_floor(const void* x, size_t x_bytes, void* y, size_t y_bytes, hipStream_t s);
 int run_im2col(const void* x, nm_dtype_t dt, int B, int H, int W, int C, int Kh, int Kw, int sh, int sw,
                int ph, int pw, int dh, int dw, int Ho, int Wo, void* a, hipStream_t s);

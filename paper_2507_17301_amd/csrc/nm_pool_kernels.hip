@@ -8,6 +8,13 @@
 namespace nm {
 namespace {
 
+inline int grid_for_items(size_t items)
+{
+    size_t g = (items + 255) / 256;
+    if (g > 256 * 16) g = 256 * 16;
+    return g < 1 ? 1 : (int)g;
+}
+
 template <typename T>
 __global__ __launch_bounds__(256) void maxpool_kernel(const T* __restrict__ x, T* __restrict__ y, int B,
                                                       int H, int W, int C, int k, int stride, int pad,
@@ -122,7 +129,46 @@ __global__ __launch_bounds__(256) void stream_floor_kernel(const u4v* __restrict
     if (acc == 0x9e3779b9u && ny > 0 && i0 == 0) y[0].x = acc;   // keeps the loads alive
 }
 
+// Where the partial sums of a K split meet: one thread per 4 consecutive channels of one
+// pixel (or per element when Cout is not a multiple of 4) adds the splits in ascending order,
+// then bias, residual, activation, one rounding.
+template <typename TOUT>
+__global__ __launch_bounds__(256) void splitk_reduce_kernel(const ConvParams p)
+{
+    const size_t total = (size_t)p.P * p.Cout;
+    TOUT* __restrict__ y = reinterpret_cast<TOUT*>(p.y);
+    if (p.Cout % 4 == 0) {
+        const size_t n4 = total / 4;
+        for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n4; i += (size_t)gridDim.x * blockDim.x) {
+            f4 v = *reinterpret_cast<const f4*>(p.partial + i * 4);
+            for (int s = 1; s < p.ksplit; ++s) v = v + *reinterpret_cast<const f4*>(p.partial + (size_t)s * total + i * 4);
+            if (p.bias) v = v + *reinterpret_cast<const f4*>(p.bias + (i * 4) % (size_t)p.Cout);
+            emit4(p, y, (unsigned)(i * 4), v);
+        }
+    } else {
+        for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += (size_t)gridDim.x * blockDim.x) {
+            float v = p.partial[i];
+            for (int s = 1; s < p.ksplit; ++s) v += p.partial[(size_t)s * total + i];
+            if (p.bias) v += p.bias[i % (size_t)p.Cout];
+            emit1(p, y, (unsigned)i, v);
+        }
+    }
+}
+
 }  // namespace
+
+int run_splitk_reduce(const ConvParams& p, nm_dtype_t ydt, hipStream_t s)
+{
+    const size_t total = (size_t)p.P * p.Cout;
+    const size_t items = p.Cout % 4 == 0 ? total / 4 : total;
+    const int grid = grid_for_items(items);
+    if (ydt == NM_F32)
+        hipLaunchKernelGGL(splitk_reduce_kernel<float>, dim3(grid), dim3(256), 0, s, p);
+    else
+        hipLaunchKernelGGL(splitk_reduce_kernel<bf16_t>, dim3(grid), dim3(256), 0, s, p);
+    NM_HIP_CHECK(hipGetLastError());
+    return NM_OK;
+}
 
 int run_stream_floor(const void* x, size_t x_bytes, void* y, size_t y_bytes, hipStream_t s)
 {

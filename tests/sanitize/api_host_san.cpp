@@ -75,6 +75,12 @@ hipError_t hipMemcpy(void* d, const void* s, size_t n, hipMemcpyKind) { memcpy(d
 hipError_t hipMemcpyAsync(void* d, const void* s, size_t n, hipMemcpyKind, hipStream_t) { memcpy(d, s, n); return hipSuccess; }
 hipError_t hipMemsetAsync(void* d, int v, size_t n, hipStream_t) { memset(d, v, n); return hipSuccess; }
 hipError_t hipStreamSynchronize(hipStream_t) { return hipSuccess; }
+static bool g_capturing = false;
+hipError_t hipStreamIsCapturing(hipStream_t, hipStreamCaptureStatus* st)
+{
+    *st = g_capturing ? hipStreamCaptureStatusActive : hipStreamCaptureStatusNone;
+    return hipSuccess;
+}
 hipError_t hipEventCreate(hipEvent_t* e) { *e = (hipEvent_t)malloc(1); return hipSuccess; }
 hipError_t hipEventDestroy(hipEvent_t e) { free(e); return hipSuccess; }
 hipError_t hipEventRecord(hipEvent_t, hipStream_t) { return hipSuccess; }
@@ -92,21 +98,27 @@ hipError_t hipEventElapsedTime(float* ms, hipEvent_t, hipEvent_t)
 namespace nm {
 
 static const VariantDesc kFake[] = {
-    // name, BP, NBLK, WP, NJ, CK, SPC, vec, kind, share
-    {"F_NB4_WP1_NJ1_CK32_SPC2", 64, 4, 1, 1, 32, 2, 1, 0, 1},
-    {"F_NB4_WP1_NJ1_CK32_SPC4", 64, 4, 1, 1, 32, 4, 1, 0, 1},
-    {"F_NB4_WP1_NJ1_CK32_SPC8", 64, 4, 1, 1, 32, 8, 1, 0, 1},
-    {"F_NB8_WP1_NJ2_CK64_SPC4", 128, 8, 1, 2, 64, 4, 1, 0, 1},
-    {"F_NB8_WP1_NJ2_CK64_SPC8", 128, 8, 1, 2, 64, 8, 1, 0, 1},
-    {"F_NB8_WP1_NJ2_CK64_SPC2", 128, 8, 1, 2, 64, 2, 1, 0, 1},
-    {"F_SCALAR_CK32_SPC8", 256, 4, 4, 4, 32, 8, 0, 0, 1},
-    {"F_VAR_NB4_CK32_SPC8", 64, 4, 1, 1, 32, 8, 1, 5, 1},
-    {"F_B16_NB4_CK64_SPC1", 64, 4, 1, 1, 64, 1, 1, 1, 1},
-    {"F_B16_NB4_CK64_SPC2", 64, 4, 1, 1, 64, 2, 1, 1, 1},
-    {"F_SP1_NB4_NJ2_CK64", 64, 4, 1, 2, 64, 1, 1, 2, 1},
-    {"F_SP0_NB4_NJ2_CK128", 64, 4, 1, 2, 128, 2, 1, 3, 1},
-    {"F_RUN_NB4_KS3", 64, 4, 1, 1, 192, 3, 1, 4, 1},
-    {"F_RUN_NB4_KS1", 64, 4, 1, 1, 64, 1, 1, 4, 1},
+    // name, BP, NBLK, WP, NJ, CK, SPC, vec, kind, share, ksplit, areg
+    {"F_NB4_WP1_NJ1_CK32_SPC2", 64, 4, 1, 1, 32, 2, 1, 0, 1, 1, 0},
+    {"F_NB4_WP1_NJ1_CK32_SPC4", 64, 4, 1, 1, 32, 4, 1, 0, 1, 1, 0},
+    {"F_NB4_WP1_NJ1_CK32_SPC8", 64, 4, 1, 1, 32, 8, 1, 0, 1, 1, 0},
+    {"F_NB8_WP1_NJ2_CK64_SPC4", 128, 8, 1, 2, 64, 4, 1, 0, 1, 1, 0},
+    {"F_NB8_WP1_NJ2_CK64_SPC8", 128, 8, 1, 2, 64, 8, 1, 0, 1, 1, 0},
+    {"F_NB8_WP1_NJ2_CK64_SPC2", 128, 8, 1, 2, 64, 2, 1, 0, 1, 1, 0},
+    {"F_SCALAR_CK32_SPC8", 256, 4, 4, 4, 32, 8, 0, 0, 1, 1, 0},
+    {"F_VAR_NB4_CK32_SPC8", 64, 4, 1, 1, 32, 8, 1, 5, 1, 1, 0},
+    {"F_B16_NB4_CK64_SPC1", 64, 4, 1, 1, 64, 1, 1, 1, 1, 1, 0},
+    {"F_B16_NB4_CK64_SPC2", 64, 4, 1, 1, 64, 2, 1, 1, 1, 1, 0},
+    {"F_SP1_NB4_NJ2_CK64", 64, 4, 1, 2, 64, 1, 1, 2, 1, 1, 0},
+    {"F_SP0_NB4_NJ2_CK128", 64, 4, 1, 2, 128, 2, 1, 3, 1, 1, 0},
+    {"F_SPR1_NB4_NJ2_CK64", 64, 4, 1, 2, 64, 1, 1, 2, 1, 1, 1},
+    {"F_RUN_NB4_KS3", 64, 4, 1, 1, 192, 3, 1, 4, 1, 1, 0},
+    {"F_RUN_NB4_KS1", 64, 4, 1, 1, 64, 1, 1, 4, 1, 1, 0},
+    // K-split forms of the fp32 kernel
+    {"F_NB4_WP1_NJ1_CK32_SPC4_S2", 64, 4, 1, 1, 32, 4, 1, 0, 1, 2, 0},
+    {"F_NB4_WP1_NJ1_CK32_SPC4_S4", 64, 4, 1, 1, 32, 4, 1, 0, 1, 4, 0},
+    {"F_NB4_WP1_NJ1_CK32_SPC2_S16", 64, 4, 1, 1, 32, 2, 1, 0, 1, 16, 0},
+    {"F_SCALAR_CK32_SPC8_S2", 256, 4, 4, 4, 32, 8, 0, 0, 1, 2, 0},
 };
 int variant_count() { return (int)(sizeof(kFake) / sizeof(kFake[0])); }
 const VariantDesc& variant_desc(int v) { return kFake[v]; }
@@ -123,7 +135,12 @@ int launch_conv(int v, nm_dtype_t xdt, nm_dtype_t ydt, const ConvParams& p, hipS
     const long eh = (long)p.H + 2L * p.ph - (long)p.dh * (p.Kh - 1) - 1, ew = (long)p.W + 2L * p.pw - (long)p.dw * (p.Kw - 1) - 1;
     CHECK(eh >= 0 && ew >= 0 && p.Ho == eh / p.sh + 1 && p.Wo == ew / p.sw + 1);
     CHECK(p.P == p.B * p.Ho * p.Wo && p.K == p.Kh * p.Kw * p.Cin);
-    CHECK(p.n_ptiles == (p.P + d.BP - 1) / d.BP && p.n_wg == p.n_ptiles * p.n_cblocks);
+    CHECK(p.n_ptiles == (p.P + d.BP - 1) / d.BP && p.n_wg == p.n_ptiles * p.n_cblocks * p.ksplit);
+    CHECK(p.ksplit == (d.ksplit > 1 ? d.ksplit : 1));
+    if (p.ksplit > 1) {   // every split owns chunks, together they cover the K axis, and the partial sums have a home
+        CHECK(p.cps >= 1 && (p.ksplit - 1) * p.cps < p.nchunks && p.ksplit * p.cps >= p.nchunks);
+        CHECK(inside(p.partial, (size_t)p.ksplit * p.P * p.Cout * 4));
+    }
     CHECK(p.n_cblocks * (4 / d.WP) * d.NJ >= p.n_rowblocks && (p.n_cblocks - 1) * (4 / d.WP) * d.NJ < p.n_rowblocks);
     CHECK(p.wg_per_xcd * 8 >= p.n_wg);
     CHECK((size_t)p.x_elems * es == p.x_bytes && p.x_bytes < 0x80000000u);
@@ -181,6 +198,11 @@ int run_maxpool(const void*, nm_dtype_t, int, int, int, int, int, int, int, int,
 int run_avgpool(const void*, nm_dtype_t, int, int, int, void*, hipStream_t) { return NM_OK; }
 int run_im2col(const void*, nm_dtype_t, int, int, int, int, int, int, int, int, int, int, int, int, int, int, void*,
                hipStream_t) { return NM_OK; }
+int run_splitk_reduce(const ConvParams& p, nm_dtype_t, hipStream_t)
+{
+    CHECK(p.ksplit > 1 && inside(p.partial, (size_t)p.ksplit * p.P * p.Cout * 4));
+    return NM_OK;
+}
 int run_stream_floor(const void* x, size_t xb, void* y, size_t yb, hipStream_t)
 {
     CHECK(inside(x, xb) && inside(y, yb));
@@ -236,6 +258,17 @@ static void conv_case(int b, int h, int w, int cin, int cout, int kh, int kw, in
         CHECK(legal ? (rc == NM_OK || rc == NM_ERR_UNSUPPORTED) : rc == NM_ERR_UNSUPPORTED);
     }
     CHECK(nm_force_variant(-1) == NM_OK);
+    // K-split variants: through the growable workspace, and under capture
+    for (int u = 0; u < nm_variant_count(); ++u) {
+        const char* nme = nm_variant_name(u);
+        if (!strstr(nme, "_S") || nm_variant_legal(u, wp, dt, dt) != 1) continue;
+        CHECK(nm_force_variant(u) == NM_OK);
+        CHECK(nm_conv2d(x, dt, b, h, w, cin, wp, bias, sh, sw, ph, pw, dh, dw, 1, y, dt, nullptr) == NM_OK);
+        g_capturing = true;   // large enough already: no allocation, so capture is fine
+        CHECK(nm_conv2d(x, dt, b, h, w, cin, wp, bias, sh, sw, ph, pw, dh, dw, 1, y, dt, nullptr) == NM_OK);
+        g_capturing = false;
+    }
+    CHECK(nm_force_variant(-1) == NM_OK);
     // argument and shape errors
     CHECK(nm_conv2d(x, dt, b, h, w, cin + 1, wp, bias, sh, sw, ph, pw, dh, dw, 1, y, dt, nullptr) == NM_ERR_ARG);
     CHECK(nm_conv2d((char*)x + 2, dt, b, h, w, cin, wp, bias, sh, sw, ph, pw, dh, dw, 1, y, dt, nullptr) == NM_ERR_ARG);
@@ -247,6 +280,28 @@ static void conv_case(int b, int h, int w, int cin, int cout, int kh, int kw, in
     CHECK(nm_conv2d(x, dt, 1 << 20, 4096, 4096, cin, wp, bias, sh, sw, ph, pw, dh, dw, 1, y, dt, nullptr) == NM_ERR_SHAPE);
     CHECK(hipFree(x) == hipSuccess && hipFree(y) == hipSuccess && hipFree(r) == hipSuccess && hipFree(bias) == hipSuccess);
     CHECK(nm_packed_free(wp) == NM_OK);
+}
+
+// a K split that would have to allocate under capture
+static void split_limits()
+{
+    const int cout = 64, cin = 64;
+    std::vector<float> wt((size_t)cout * 9 * cin, 0.5f);
+    nm_packed_t* wp = nullptr;
+    CHECK(nm_prune(wt.data(), cout, 3, 3, cin, 2, 4, 16, NM_F32, &wp) == NM_OK);
+    int forced = -1;
+    for (int u = 0; u < nm_variant_count(); ++u)
+        if (strstr(nm_variant_name(u), "_S4") && nm_variant_legal(u, wp, NM_F32, NM_F32) == 1) forced = u;
+    CHECK(forced >= 0 && nm_force_variant(forced) == NM_OK);
+    const int b = 8, h = 96, w = 96;   // 4 splits x 73728 pixels x 64 channels x 4 bytes = 75 MB
+    void* x = dev_alloc((size_t)b * h * w * cin * 4);
+    void* y = dev_alloc((size_t)b * h * w * cout * 4);
+    g_capturing = true;
+    CHECK(nm_conv2d(x, NM_F32, b, h, w, cin, wp, nullptr, 1, 1, 1, 1, 1, 1, 0, y, NM_F32, nullptr) == NM_ERR_ALLOC);
+    g_capturing = false;
+    CHECK(nm_conv2d(x, NM_F32, b, h, w, cin, wp, nullptr, 1, 1, 1, 1, 1, 1, 0, y, NM_F32, nullptr) == NM_OK);
+    CHECK(nm_force_variant(-1) == NM_OK);
+    CHECK(hipFree(x) == hipSuccess && hipFree(y) == hipSuccess && nm_packed_free(wp) == NM_OK);
 }
 
 int main(int argc, char** argv)
@@ -299,7 +354,9 @@ int main(int argc, char** argv)
     conv_case(1, 6, 10, 64, 64, 3, 3, 32, 64, 32, NM_F32, 1, 2, 2, 1, 2, 1);   // one group per tap
     conv_case(1, 5, 5, 128, 16, 1, 1, 4, 8, 16, NM_BF16, 1, 1, 0, 0, 1, 1);    // dense instruction only
     conv_case(1, 1, 1, 8, 5, 1, 1, 1, 2, 5, NM_F32, 1, 1, 0, 0, 1, 1);
-    CHECK(g_allocs.empty());                                                    // nothing leaked on the "device"
+    split_limits();
+    // nothing leaked on the "device": what is left is the K-split workspace
+    CHECK(g_allocs.size() <= 1);
     const int n_entries = nm_cache_size();
     CHECK(n_entries == 7);
 
@@ -333,6 +390,8 @@ int main(int argc, char** argv)
         CHECK(nm_cache_size() == before);          // nothing it holds names a real variant of a real shape
     }
     CHECK(nm_cache_clear() == NM_OK);
+    CHECK(nm_workspace_free() == NM_OK);
+    CHECK(g_allocs.empty());
     puts("host-layer sanitizer run: ok");
     return 0;
 }
