@@ -123,7 +123,7 @@ int nm_packed_mask(const nm_packed_t* wp, uint8_t* mask_host);
  * its partial sums in a library-owned workspace per device, and the first call
  * that needs a larger one than exists allocates it (nm_autotune sizes it for the
  * shapes it tunes; under stream capture such a call fails with NM_ERR_ALLOC
- * instead).  Calls that overlap on one device
+ * instead; nm_conv2d_static never allocates).  Calls that overlap on one device
  * and both run a K-split variant race on that workspace.  The kernel variant is
  * the one nm_autotune cached for this shape, else nm_force_variant's, else a
  * deterministic default.  Errors: NM_ERR_ARG, NM_ERR_SHAPE, NM_ERR_UNSUPPORTED,
@@ -149,6 +149,25 @@ int nm_conv2d_res(const void* x_dev, nm_dtype_t x_dtype, int b, int h, int w, in
                   const nm_packed_t* wp, const float* bias_dev, const void* residual_dev,
                   int stride_h, int stride_w, int pad_h, int pad_w, int dil_h, int dil_w,
                   int relu, void* y_dev, nm_dtype_t y_dtype, void* hip_stream);
+
+/*
+ * nm_conv2d_static -- nm_conv2d_res for callers that cannot allocate device memory: code
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same
+ * arguments, same results, same variant choice.  The one thing nm_conv2d may allocate is the
+ * workspace for the partial sums of a K-split variant (a variant whose name ends in "_S<n>":
+ * n workgroups share the K axis of an output tile; chosen by the tuner for layers with too
+ * few output tiles to fill the chip); this entry point keeps those sums in a fixed buffer of
+ * 16 MiB that is part of the library's device image instead, and calls no allocating routine.
+ * A K-split variant whose partial sums (n * P * cout * 4 bytes) exceed 16 MiB is refused
+ * with NM_ERR_SHAPE and a message that names both sizes.  Every call on a GPU shares that
+ * GPU's buffer: calls that overlap on one GPU (different streams) race; calls on one stream
+ * do not.  Nothing needs to be cleared between calls (every partial sum is written before it
+ * is read).
+ */
+int nm_conv2d_static(const void* x_dev, nm_dtype_t x_dtype, int b, int h, int w, int cin,
+                     const nm_packed_t* wp, const float* bias_dev, const void* residual_dev,
+                     int stride_h, int stride_w, int pad_h, int pad_w, int dil_h, int dil_w,
+                     int relu, void* y_dev, nm_dtype_t y_dtype, void* hip_stream);
 
 /*
  * The two pooling layers a ResNet needs around its convolutions, so that a whole

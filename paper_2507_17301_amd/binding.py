@@ -54,6 +54,7 @@ def lib():
         L.nm_packed_mask.argtypes = [vp, vp]
         L.nm_conv2d.argtypes = [vp, ci, ci, ci, ci, ci, vp, vp, ci, ci, ci, ci, ci, ci, ci, vp, ci, vp]
         L.nm_conv2d_res.argtypes = [vp, ci, ci, ci, ci, ci, vp, vp, vp, ci, ci, ci, ci, ci, ci, ci, vp, ci, vp]
+        L.nm_conv2d_static.argtypes = [vp, ci, ci, ci, ci, ci, vp, vp, vp, ci, ci, ci, ci, ci, ci, ci, vp, ci, vp]
         L.nm_maxpool2d.argtypes = [vp, ci, ci, ci, ci, ci, ci, ci, ci, vp, vp]
         L.nm_avgpool_global.argtypes = [vp, ci, ci, ci, ci, ci, vp, vp]
         L.nm_im2col.argtypes = [vp] + [ci] * 13 + [vp, vp]
@@ -67,7 +68,8 @@ def lib():
         L.nm_force_variant.argtypes = [ci]
         L.nm_variant_legal.argtypes = [ci, vp, ci, ci]
         for name in ("nm_prune", "nm_packed_free", "nm_packed_dims", "nm_packed_indices",
-                     "nm_packed_values", "nm_packed_mask", "nm_conv2d", "nm_conv2d_res", "nm_maxpool2d",
+                     "nm_packed_values", "nm_packed_mask", "nm_conv2d", "nm_conv2d_res", "nm_conv2d_static",
+                     "nm_maxpool2d",
                      "nm_avgpool_global", "nm_im2col", "nm_stream_floor", "nm_autotune",
                      "nm_cache_save", "nm_cache_load", "nm_cache_clear", "nm_cache_size", "nm_workspace_free",
                      "nm_force_variant", "nm_variant_legal"):
@@ -226,8 +228,13 @@ def nm_conv2d(x, wp: Packed, bias=None, stride=1, pad=0, dil=1, relu=False, y=No
     return y
 
 
+def nm_conv2d_static(x, wp: Packed, residual, bias, stride, pad, dil, relu, y, stream=None):
+    """nm_conv2d_res through the entry point that allocates nothing; y must be given."""
+    return nm_conv2d_res(x, wp, residual, bias, stride, pad, dil, relu, y=y, stream=stream, _entry="nm_conv2d_static")
+
+
 def nm_conv2d_res(x, wp: Packed, residual, bias=None, stride=1, pad=0, dil=1, relu=False, y=None,
-                  stream=None):
+                  stream=None, _entry="nm_conv2d_res"):
     """nm_conv2d with a residual (device tensor shaped and typed like the output, or None)
     added before the activation."""
     import torch
@@ -255,7 +262,7 @@ def nm_conv2d_res(x, wp: Packed, residual, bias=None, stride=1, pad=0, dil=1, re
         if bias.dtype != torch.float32 or not bias.is_cuda or not bias.is_contiguous():
             raise ValueError("bias must be a contiguous fp32 device tensor")
         bptr = bias.data_ptr()
-    _check(lib().nm_conv2d_res(x.data_ptr(), _dtype_code(x), b, h, w, cin, wp.handle, bptr, rptr,
+    _check(getattr(lib(), _entry)(x.data_ptr(), _dtype_code(x), b, h, w, cin, wp.handle, bptr, rptr,
                                sh, sw, ph, pw, dh, dw, int(bool(relu)), y.data_ptr(), _dtype_code(y),
                                _stream_ptr(stream)))
     return y

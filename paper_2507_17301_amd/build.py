@@ -94,7 +94,7 @@ def _shapes_var():
 
 def _jobs():
     jobs = []
-    for src in ("nm_api.hip", "nm_prune_kernels.hip", "nm_pool_kernels.hip", "nm_conv_registry.hip"):
+    for src in ("nm_api.hip", "nm_prune_kernels.hip", "nm_pool_kernels.hip", "nm_conv_registry.hip", "nm_scratch.hip"):
         jobs.append((os.path.join(CSRC, src), os.path.join(OBJDIR, src.replace(".hip", ".o")), []))
     inst = os.path.join(CSRC, "nm_conv_inst.hip")
     for nb, wp, nj in _shapes():

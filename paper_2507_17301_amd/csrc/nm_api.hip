@@ -702,7 +702,7 @@ int nm_variant_legal(int variant, const nm_packed_t* wp, nm_dtype_t xdt, nm_dtyp
 
 static int conv2d_impl(const void* x, nm_dtype_t xdt, int b, int h, int w, int cin, const nm_packed_t* wp,
                        const float* bias, const void* res, int sh, int sw, int ph, int pw, int dh, int dw,
-                       int relu, void* y, nm_dtype_t ydt, void* stream)
+                       int relu, void* y, nm_dtype_t ydt, void* stream, bool static_only = false)
 {
     int rc = check_conv_args(x, xdt, cin, wp, y, ydt);
     if (rc != NM_OK) return rc;
@@ -755,7 +755,14 @@ static int conv2d_impl(const void* x, nm_dtype_t xdt, int b, int h, int w, int c
     p.res = res;
     if (d.ksplit > 1) {
         const size_t need = split_bytes(d, g, wp);
-        {
+        if (static_only) {
+            if (need > kStaticScratchBytes) {
+                set_error("variant %s needs %zu bytes of scratch for its partial sums; the static buffer holds %u",
+                          d.name, need, (unsigned)kStaticScratchBytes);
+                return NM_ERR_SHAPE;
+            }
+            rc = static_scratch(wp->device, &p.partial);
+        } else {
             // growing the workspace allocates, which a stream under capture must not do
             hipStreamCaptureStatus cs = hipStreamCaptureStatusNone;
             (void)hipStreamIsCapturing((hipStream_t)stream, &cs);
@@ -781,6 +788,13 @@ int nm_conv2d_res(const void* x, nm_dtype_t xdt, int b, int h, int w, int cin, c
                   int relu, void* y, nm_dtype_t ydt, void* stream)
 {
     return conv2d_impl(x, xdt, b, h, w, cin, wp, bias, res, sh, sw, ph, pw, dh, dw, relu, y, ydt, stream);
+}
+
+int nm_conv2d_static(const void* x, nm_dtype_t xdt, int b, int h, int w, int cin, const nm_packed_t* wp,
+                     const float* bias, const void* res, int sh, int sw, int ph, int pw, int dh, int dw,
+                     int relu, void* y, nm_dtype_t ydt, void* stream)
+{
+    return conv2d_impl(x, xdt, b, h, w, cin, wp, bias, res, sh, sw, ph, pw, dh, dw, relu, y, ydt, stream, true);
 }
 
 int nm_maxpool2d(const void* x, nm_dtype_t dt, int b, int h, int w, int c, int k, int stride, int pad,

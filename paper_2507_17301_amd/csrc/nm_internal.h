@@ -195,6 +195,10 @@ int run_maxpool(const void* x, nm_dtype_t dt, int B, int H, int W, int C, int k,
 int run_avgpool(const void* x, nm_dtype_t dt, int B, int HW, int C, void* y, hipStream_t s);
 // adds up the partial sums of a K split: y = act(sum_s partial[s] + bias + residual)
 int run_splitk_reduce(const ConvParams& p, nm_dtype_t ydt, hipStream_t s);
+// Static scratch of nm_conv2d_static (nm_scratch.hip): device address of the current
+// device's copy, looked up once per device; never allocates.
+constexpr size_t kStaticScratchBytes = (size_t)16 << 20;
+int static_scratch(int dev, float** out);
 int run_stream_floor(const void* x, size_t x_bytes, void* y, size_t y_bytes, hipStream_t s);
 int run_im2col(const void* x, nm_dtype_t dt, int B, int H, int W, int C, int Kh, int Kw, int sh, int sw,
                int ph, int pw, int dh, int dw, int Ho, int Wo, void* a, hipStream_t s);

@@ -198,6 +198,16 @@ int run_maxpool(const void*, nm_dtype_t, int, int, int, int, int, int, int, int,
 int run_avgpool(const void*, nm_dtype_t, int, int, int, void*, hipStream_t) { return NM_OK; }
 int run_im2col(const void*, nm_dtype_t, int, int, int, int, int, int, int, int, int, int, int, int, int, int, void*,
                hipStream_t) { return NM_OK; }
+static char* fake = nullptr;
+int static_scratch(int, float** out)
+{
+    if (!fake) {   // this "device's" copy of the static scratch array; never freed
+        fake = (char*)malloc(kStaticScratchBytes);
+        g_allocs[fake] = kStaticScratchBytes;
+    }
+    *out = (float*)fake;
+    return NM_OK;
+}
 int run_splitk_reduce(const ConvParams& p, nm_dtype_t, hipStream_t)
 {
     CHECK(p.ksplit > 1 && inside(p.partial, (size_t)p.ksplit * p.P * p.Cout * 4));
@@ -258,11 +268,12 @@ static void conv_case(int b, int h, int w, int cin, int cout, int kh, int kw, in
         CHECK(legal ? (rc == NM_OK || rc == NM_ERR_UNSUPPORTED) : rc == NM_ERR_UNSUPPORTED);
     }
     CHECK(nm_force_variant(-1) == NM_OK);
-    // K-split variants: through the growable workspace, and under capture
+    // K-split variants: through the growable workspace, through the static scratch, and under capture
     for (int u = 0; u < nm_variant_count(); ++u) {
         const char* nme = nm_variant_name(u);
         if (!strstr(nme, "_S") || nm_variant_legal(u, wp, dt, dt) != 1) continue;
         CHECK(nm_force_variant(u) == NM_OK);
+        CHECK(nm_conv2d_static(x, dt, b, h, w, cin, wp, bias, r, sh, sw, ph, pw, dh, dw, 1, y, dt, nullptr) == NM_OK);
         CHECK(nm_conv2d(x, dt, b, h, w, cin, wp, bias, sh, sw, ph, pw, dh, dw, 1, y, dt, nullptr) == NM_OK);
         g_capturing = true;   // large enough already: no allocation, so capture is fine
         CHECK(nm_conv2d(x, dt, b, h, w, cin, wp, bias, sh, sw, ph, pw, dh, dw, 1, y, dt, nullptr) == NM_OK);
@@ -282,7 +293,7 @@ static void conv_case(int b, int h, int w, int cin, int cout, int kh, int kw, in
     CHECK(nm_packed_free(wp) == NM_OK);
 }
 
-// a K split that would have to allocate under capture
+// a K split whose partial sums outgrow the static scratch, and one that would have to allocate under capture
 static void split_limits()
 {
     const int cout = 64, cin = 64;
@@ -296,6 +307,8 @@ static void split_limits()
     const int b = 8, h = 96, w = 96;   // 4 splits x 73728 pixels x 64 channels x 4 bytes = 75 MB
     void* x = dev_alloc((size_t)b * h * w * cin * 4);
     void* y = dev_alloc((size_t)b * h * w * cout * 4);
+    CHECK(nm_conv2d_static(x, NM_F32, b, h, w, cin, wp, nullptr, nullptr, 1, 1, 1, 1, 1, 1, 0, y, NM_F32, nullptr) == NM_ERR_SHAPE);
+    CHECK(strstr(nm_last_error(), "static buffer"));
     g_capturing = true;
     CHECK(nm_conv2d(x, NM_F32, b, h, w, cin, wp, nullptr, 1, 1, 1, 1, 1, 1, 0, y, NM_F32, nullptr) == NM_ERR_ALLOC);
     g_capturing = false;
@@ -355,8 +368,8 @@ int main(int argc, char** argv)
     conv_case(1, 5, 5, 128, 16, 1, 1, 4, 8, 16, NM_BF16, 1, 1, 0, 0, 1, 1);    // dense instruction only
     conv_case(1, 1, 1, 8, 5, 1, 1, 1, 2, 5, NM_F32, 1, 1, 0, 0, 1, 1);
     split_limits();
-    // nothing leaked on the "device": what is left is the K-split workspace
-    CHECK(g_allocs.size() <= 1);
+    // nothing leaked on the "device": what is left is the K-split workspace and the static scratch
+    CHECK(g_allocs.size() <= 2);
     const int n_entries = nm_cache_size();
     CHECK(n_entries == 7);
 
@@ -391,6 +404,8 @@ int main(int argc, char** argv)
     }
     CHECK(nm_cache_clear() == NM_OK);
     CHECK(nm_workspace_free() == NM_OK);
+    g_allocs.erase(nm::fake);
+    free(nm::fake);
     CHECK(g_allocs.empty());
     puts("host-layer sanitizer run: ok");
     return 0;
