@@ -220,7 +220,7 @@ int nm_stream_floor(const void* x_dev, size_t x_bytes, void* y_dev, size_t y_byt
  * input; a ring of input/output sets of about 768 MB so that, as inside a
  * network, no launch finds its tensors in the last-level cache), times it with
  * HIP events on `hip_stream`, stores the winner in the process-wide cache keyed
- * by (shape, N:M, T, dtypes, bias / activation flags, the device's name and CU
+ * by (shape, N:M, T, dtypes, bias / activation flags, the device's architecture and CU
  * count, and which operand tables the handle carries -- layers of one shape whose
  * kept sets need different k-steps per chunk do not share an entry) and returns it.
  * Synchronous.  A cached shape returns immediately with the cached result.

@@ -71,7 +71,7 @@ unsigned fnv(unsigned h, const void* data, size_t n)
 }
 
 // Identity of a device for the tuning cache: a timing taken on one kind of GPU says
-// nothing about another.  Name, architecture string and CU count, hashed; kept per ordinal.
+// nothing about another.  Architecture string and CU count, hashed; kept per ordinal.
 struct DeviceId {
     int hash = 0;
     char name[128] = "";
@@ -86,7 +86,9 @@ const DeviceId* device_id(int dev)
     hipDeviceProp_t prop;
     if (hipGetDeviceProperties(&prop, dev) != hipSuccess) return nullptr;
     DeviceId id;
-    snprintf(id.name, sizeof(id.name), "%s|%s|%dCU", prop.name, prop.gcnArchName, prop.multiProcessorCount);
+    // (the marketing name is left out: it comes from a system file that may be missing, and then
+    //  differs from one process to the next)
+    snprintf(id.name, sizeof(id.name), "%s|%dCU", prop.gcnArchName, prop.multiProcessorCount);
     for (char* c = id.name; *c; ++c)
         if (*c == ' ' || *c == '\n') *c = '_';   // one token in the cache file
     id.hash = (int)(fnv(2166136261u, id.name, strlen(id.name)) & 0x7fffffffu);
