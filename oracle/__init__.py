@@ -44,6 +44,8 @@ def _load():
         L.oracle_pack.restype = ci
         L.oracle_round_bf16.argtypes = [fp, fp, ctypes.c_long]
         L.oracle_round_bf16.restype = None
+        L.oracle_round_e4m3.argtypes = [fp, fp, ctypes.c_long]
+        L.oracle_round_e4m3.restype = None
         conv_common = [fp, ci, ci, ci, ci, fp, ci, ci, ci, fp,
                        ci, ci, ci, ci, ci, ci, ci, ci]
         L.oracle_conv2d.argtypes = conv_common + [fp, ci]
@@ -134,6 +136,36 @@ def round_bf16(a):
     out = np.empty_like(a)
     _load().oracle_round_bf16(ap, out.ctypes.data_as(ctypes.POINTER(ctypes.c_float)), a.size)
     return out
+
+
+def round_e4m3(a):
+    """Round fp32 values to the nearest fp8 E4M3 value (OCP e4m3fn; ties to even, NaN beyond
+    the largest finite value 448), returned as fp32."""
+    a, ap = _f32(a)
+    out = np.empty_like(a)
+    _load().oracle_round_e4m3(ap, out.ctypes.data_as(ctypes.POINTER(ctypes.c_float)), a.size)
+    return out
+
+
+def fp8_weight_scale(w_kept):
+    """The power-of-two scale under which a layer's kept weights are stored as E4M3: the
+    largest 2^e with max|w| * 2^e <= 448 (1 for an all-zero layer).  Scaling by a power of
+    two is exact, so the stored value times 2^-e is the weight the convolution uses."""
+    m = float(np.max(np.abs(w_kept))) if np.size(w_kept) else 0.0
+    if m == 0.0:
+        return 1.0
+    f, e = np.frexp(448.0 / m)          # 448 / m = f * 2^e with 0.5 <= f < 1: floor(log2) = e - 1
+    s = float(np.ldexp(1.0, int(e) - 1))
+    while m * s > 448.0:                # the division above is rounded: step back if it rounded up across a power of two
+        s /= 2.0
+    return s
+
+
+def quantize_e4m3(w_kept):
+    """(dequantized weights, scale): w -> round_e4m3(w * s) / s with s = fp8_weight_scale(w)."""
+    s = fp8_weight_scale(w_kept)
+    w = np.ascontiguousarray(w_kept, dtype=np.float32)
+    return (round_e4m3(w * np.float32(s)) / np.float32(s)).astype(np.float32), s
 
 
 def _conv_args(x, w, bias, stride, pad, dil, relu, out_bf16):

@@ -155,6 +155,35 @@ static float round_to_bf16(float v)
     return r;
 }
 
+/* fp32 -> fp8 E4M3 (the OCP "e4m3fn" format: 4 exponent bits with bias 7, 3 mantissa bits,
+ * subnormals, no infinity, largest finite value 448), round to nearest, ties to even,
+ * returned as the exactly representable float.  Written from the format's definition: the
+ * spacing of representable values is 2^(E-3) in the binade 2^E <= |v| < 2^(E+1), E >= -6,
+ * and 2^-9 below 2^-6; rounding |v| to a multiple of that spacing with ties to the even
+ * multiple is round-to-nearest-even, because the multiples that are even are exactly the
+ * values with an even mantissa field.  Beyond the largest finite value the format has no
+ * number to round to: the result is NaN (no saturation), as in the reference conversion. */
+static float round_to_e4m3(float v)
+{
+    if (v != v) return v;
+    const double a = fabs((double)v);
+    if (a == 0.0) return v;
+    int e;
+    (void)frexp(a, &e);                 /* a = f * 2^e with 0.5 <= f < 1: leading bit at 2^(e-1) */
+    int E = e - 1;
+    if (E < -6) E = -6;
+    const double ulp = ldexp(1.0, E - 3);
+    const double r = nearbyint(a / ulp) * ulp;   /* default rounding mode: ties to even; a / ulp is exact */
+    if (r > 448.0) return (float)NAN;
+    return (float)(v < 0 ? -r : r);
+}
+
+/* elementwise rounding of n floats to E4M3-representable floats */
+void oracle_round_e4m3(const float* in, float* out, long n)
+{
+    for (long i = 0; i < n; ++i) out[i] = round_to_e4m3(in[i]);
+}
+
 /* elementwise RNE rounding of n floats to bf16-representable floats */
 void oracle_round_bf16(const float* in, float* out, long n)
 {

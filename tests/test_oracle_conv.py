@@ -223,3 +223,42 @@ def test_output_geometry():
     assert oracle.out_size(10, 12, 3, 3, 1, 2, 2) == (10, 12)
     with pytest.raises(ValueError):
         oracle.out_size(2, 2, 5, 5, 1, 0, 1)
+
+
+def test_e4m3_rounding_matches_the_reference_conversion():
+    """oracle.round_e4m3 against torch's float8_e4m3fn conversion: every representable value,
+    every midpoint between neighbours (ties to even), values just off the midpoints, the
+    subnormal range, the overflow boundary (464 is the last value that rounds to 448; beyond
+    that the format has nothing to round to and the result is NaN), random values."""
+    import torch
+    codes = torch.arange(256, dtype=torch.uint8)
+    vals = codes.view(torch.float8_e4m3fn).float().numpy()
+    finite = np.sort(vals[np.isfinite(vals)])
+    assert finite.size == 254 and finite[-1] == 448.0 and finite[0] == -448.0
+    assert np.array_equal(oracle.round_e4m3(finite), finite)                     # fixed points
+    mids = ((finite[:-1].astype(np.float64) + finite[1:].astype(np.float64)) / 2).astype(np.float32)
+    rng = np.random.default_rng(0)
+    probe = np.concatenate([
+        mids, np.nextafter(mids, np.float32(np.inf)), np.nextafter(mids, np.float32(-np.inf)),
+        np.float32([2.0 ** -9, 2.0 ** -10, 1.5 * 2.0 ** -10, 0.75 * 2.0 ** -9, 2.0 ** -6, 2.0 ** -7 * 1.0625]),
+        np.float32([448.0, 455.9, 463.99, 464.0, -464.0]),
+        rng.standard_normal(20000).astype(np.float32) * 3, rng.random(20000, dtype=np.float32),
+        (rng.standard_normal(5000) * 0.02).astype(np.float32), rng.uniform(-448, 448, 5000).astype(np.float32)])
+    want = torch.from_numpy(probe).to(torch.float8_e4m3fn).float().numpy()
+    got = oracle.round_e4m3(probe)
+    assert np.array_equal(got, want) and np.array_equal(np.signbit(got), np.signbit(want))
+    beyond = np.float32([464.0000305, 480.0, 1e6, -1e6])
+    assert np.all(np.isnan(oracle.round_e4m3(beyond)))
+    assert np.all(np.isnan(torch.from_numpy(beyond).to(torch.float8_e4m3fn).float().numpy()))
+
+
+def test_fp8_weight_scale_is_the_largest_power_of_two_that_fits():
+    for m in (1.0, 0.3, 447.9, 448.0, 448.1, 3.5e-4, 7.0, 224.0, 0.02734375):
+        s = oracle.fp8_weight_scale(np.float32([0.0, -m, m / 3]))
+        assert s == 2.0 ** round(np.log2(s))
+        assert np.float32(m) * s <= 448.0 < np.float32(m) * s * 2
+    assert oracle.fp8_weight_scale(np.zeros(4, dtype=np.float32)) == 1.0
+    w = (np.random.default_rng(1).standard_normal((8, 3, 3, 16)) * 0.05).astype(np.float32)
+    wq, s = oracle.quantize_e4m3(w)
+    assert np.array_equal(oracle.round_e4m3(wq * np.float32(s)), wq * np.float32(s))   # representable under the scale
+    assert np.max(np.abs(wq - w)) <= np.max(np.abs(w)) / 16 + 2.0 ** -9 / s            # within half a step of the top binade
