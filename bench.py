@@ -24,7 +24,7 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
-PEAK_TFLOPS = {"f32": 157.3, "bf16": 2500.0}   # dense MFMA peaks of MI355X
+PEAK_TFLOPS = {"f32": 157.3, "bf16": 2500.0, "f8": 5000.0}   # dense MFMA peaks of MI355X
 PEAK_HBM_GBS = 8000.0
 
 
@@ -43,9 +43,12 @@ class Stack:
         self.nm, self.torch = nm, torch
         self.layers, self.B, self.dtype = list(layers), B, dtype
         self.bf16 = dtype == "bf16"
-        self.tdt = torch.bfloat16 if self.bf16 else torch.float32
-        self.ndt = nm.NM_BF16 if self.bf16 else nm.NM_F32
-        self.esize = 2 if self.bf16 else 4
+        self.f8 = dtype == "f8"        # E4M3 activations and weights, bf16 output
+        self.tdt = torch.float8_e4m3fn if self.f8 else (torch.bfloat16 if self.bf16 else torch.float32)
+        self.tdt_out = torch.bfloat16 if self.f8 else self.tdt
+        self.ndt = nm.NM_F8E4M3 if self.f8 else (nm.NM_BF16 if self.bf16 else nm.NM_F32)
+        self.esize = 1 if self.f8 else (2 if self.bf16 else 4)
+        self.esize_out = 2 if self.f8 else self.esize
         dev = torch.device("cuda:0")
         gen = torch.Generator(device=dev)
         gen.manual_seed(1234)
@@ -67,7 +70,7 @@ class Stack:
             self.packed.append(wp)
             self.xs.append(torch.rand((B, l.H, l.W, l.Cin), generator=gen, device=dev,
                                       dtype=torch.float32).to(self.tdt))
-            self.ys.append(torch.empty((B, l.Ho, l.Wo, l.Cout), device=dev, dtype=self.tdt))
+            self.ys.append(torch.empty((B, l.Ho, l.Wo, l.Cout), device=dev, dtype=self.tdt_out))
             self.biases.append(torch.from_numpy(bias).to(dev))
         self.launched = [None] * len(self.layers)
         self.graph = None
@@ -171,7 +174,7 @@ class Stack:
         for i, l in enumerate(self.layers):
             ms = sorted(marks[k][i].elapsed_time(marks[k][i + 1]) for k in range(inst_steps))[inst_steps // 2]
             eff = l.effective_flops(self.B)
-            byts = l.algorithmic_bytes(self.B, self.esize, self.esize)
+            byts = l.algorithmic_bytes(self.B, self.esize, self.esize_out)
             t_flop = eff / (PEAK_TFLOPS[self.dtype] * 1e12) * 1e3
             t_mem = byts / (PEAK_HBM_GBS * 1e9) * 1e3
             rows.append({
@@ -184,9 +187,9 @@ class Stack:
         return rows
 
     def totals(self):
-        B, es = self.B, self.esize
+        B = self.B
         return (sum(l.dense_flops(B) for l in self.layers), sum(l.effective_flops(B) for l in self.layers),
-                sum(l.algorithmic_bytes(B, es, es) for l in self.layers))
+                sum(l.algorithmic_bytes(B, self.esize, self.esize_out) for l in self.layers))
 
     def free(self):
         for wp in self.packed:
@@ -200,7 +203,9 @@ def profiled_traffic(dtype):
     (FETCH_SIZE + WRITE_SIZE, each scaled by what it reads for a 1 GiB device copy): read from
     the tracked summary under profiles/, never measured by this process.  (value, source)."""
     import re
-    name = {"f32": "nm_conv_kernel_resnet50_b64_f32.txt", "bf16": "nm_conv_sp16_kernel_resnet50_b64_bf16.txt"}[dtype]
+    name = {"f32": "nm_conv_kernel_resnet50_b64_f32.txt", "bf16": "nm_conv_sp16_kernel_resnet50_b64_bf16.txt"}.get(dtype)
+    if name is None:
+        return None, None
     path = os.path.join(ROOT, "profiles", name)
     try:
         m = re.search(r"HBM traffic per step\s+[\d.]+ GB \(([\d.]+) MB per launch\)", open(path).read())
@@ -232,7 +237,8 @@ def stack_roofline(st, ms_step, rows, headline, floor_ms=None):
     families = sorted({(r["variant"] or "?").split("_")[0] for r in rows})
     roofline.update({
         "traffic": traffic, "traffic_source": source,
-        "kernel": "nm_conv_sp16_kernel" if st.bf16 else "nm_conv_kernel", "variant_families": families,
+        "kernel": "nm_conv_f8_kernel" if st.f8 else ("nm_conv_sp16_kernel" if st.bf16 else "nm_conv_kernel"),
+        "variant_families": families,
         "launches_per_step": len(rows), "avg_launch_ms": ms_step / len(rows),
         # with an event after every layer of three extra steps (adds the events' own cost)
         "avg_launch_ms_event_per_layer": kern_ms / len(rows),
@@ -308,7 +314,9 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--dtype", choices=["f32", "bf16"], default="f32")
+    ap.add_argument("--dtype", choices=["f32", "bf16", "f8"], default="f32",
+                    help="f8: E4M3 activations and weights with bf16 output, the fp8 second workload; layers whose "
+                         "input channels are not a multiple of 64 (the first layer) are left out of that stack")
     ap.add_argument("--batch", type=int, default=None, help="default: the workload's own batch")
     ap.add_argument("--workload", default="resnet50",
                     choices=["resnet50", "resnet18", "resnet101", "sweep", "single",
@@ -382,13 +390,18 @@ def main():
     if args.group:
         layers = wl.with_large_groups(layers, args.group)
         wname += "_groups_per_" + args.group
+    if args.dtype == "f8":
+        kept = [l for l in layers if l.Cin % 64 == 0]
+        if len(kept) != len(layers):
+            wname += f"_fp8_layers_only_{len(kept)}_of_{len(layers)}"
+        layers = kept
     if args.batch is not None:
         B = args.batch
     cand_tiles = [int(t) for t in args.tune_tile.split(",")] if args.tune_tile else None
     if cand_tiles:
         wname += "_T_per_layer_of_" + "_".join(str(t) for t in cand_tiles)
     headline = (args.workload == "resnet50" and B == 64 and not args.group and (n_, m_, t_) == (2, 4, 16)
-                and not cand_tiles)
+                and not cand_tiles and args.dtype != "f8")
 
     # ---- one-time set-up: weights, pruning, tuning, resident inputs ---------
     if args.cache and os.path.exists(args.cache):
@@ -466,6 +479,23 @@ def main():
                           "algorithmic_gbs": by_b / ms_b / 1e6, "setup": {"prune_pack_s": sb.prune_s, "autotune_s": sb.tune_s},
                           "roofline": rf_b}
         sb.free()
+        s8 = Stack([l for l in wl.resnet50_stack(2, 4, 16) if l.Cin % 64 == 0], B, "f8", seed0 + 1)
+        s8.tune()
+        ms_8, ms_8_host = s8.time_steps(args.steps, args.warmup, not args.no_graph)
+        rows_8 = s8.per_layer()
+        floor_8 = s8.time_floor(args.steps, args.warmup, not args.no_graph)
+        for r, f in zip(rows_8, s8.floor_ms):
+            r["traffic_only_ms"] = f
+        log("--- fp8 (E4M3 activations and weights, bf16 output), the 52 pruned layers of the stack")
+        log_rows(rows_8, ms_8, ms_8_host)
+        d_8, e_8, by_8 = s8.totals()
+        extras["fp8"] = {"workload": "resnet50_conv_stack_52_pruned_layers_2of4_T16_batch64_e4m3_in_bf16_out",
+                         "ms_per_step": ms_8, "ms_per_img": ms_8 / B, "dense_equiv_gflops": d_8 / ms_8 / 1e6,
+                         "effective_gflops": e_8 / ms_8 / 1e6, "launches": len(rows_8),
+                         "algorithmic_gbs": by_8 / ms_8 / 1e6,
+                         "setup": {"prune_pack_s": s8.prune_s, "autotune_s": s8.tune_s},
+                         "roofline": stack_roofline(s8, ms_8, rows_8, False, floor_8)}
+        s8.free()
         sd = Stack(wl.resnet50_stack(1, 1, 16), B, "f32", seed0)
         sd.tune()
         ms_d, _ = sd.time_steps(args.steps, args.warmup, not args.no_graph)

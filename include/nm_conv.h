@@ -44,7 +44,10 @@ typedef enum {
 /* Element types.  A plain int at the boundary, so that a caller's out-of-range
  * value is an NM_ERR_ARG and not undefined behaviour inside the library. */
 typedef int nm_dtype_t;
-enum { NM_F32 = 0, NM_BF16 = 1 };
+enum { NM_F32 = 0, NM_BF16 = 1,
+       NM_F8E4M3 = 2   /* fp8, 4 exponent bits (bias 7), 3 mantissa bits, subnormals, no infinity, largest
+                          value 448 (the OCP "e4m3fn" format); one byte per element */
+};
 
 /* Packed, pruned weights of one layer.  Opaque, owned by the library, immutable
  * after creation, bound to the device that was current in nm_prune. */
@@ -73,7 +76,12 @@ const char* nm_variant_name(int variant);
  *   w_ohwi_host  host pointer, [cout][kh][kw][cin] fp32, caller-owned, only read
  *   value_dtype  NM_F32: values kept as fp32.  NM_BF16: kept values are rounded
  *                to bf16 (nearest even) after selection; selection itself
- *                always uses the fp32 weights
+ *                always uses the fp32 weights.  NM_F8E4M3: kept values are stored
+ *                as E4M3 under one power-of-two scale per layer -- the largest
+ *                2^e with max|kept w| * 2^e <= 448 -- rounded to nearest even; the
+ *                weight the convolution uses is the stored value times 2^-e
+ *                (nm_packed_scale returns 2^e; needs cin % 64 == 0, tile % 16 == 0,
+ *                cout % 8 == 0)
  *   out          receives the handle; free it with nm_packed_free
  *
  * Errors: NM_ERR_ARG (null, sizes < 1, n > m, (kh*kw*cin) % m != 0, m > 16384,
@@ -95,6 +103,8 @@ int nm_packed_dims(const nm_packed_t* wp, int* n_tiles, int* groups, int* n, int
 int nm_packed_indices(const nm_packed_t* wp, int32_t* idx_host);
 int nm_packed_values(const nm_packed_t* wp, float* vals_host);
 int nm_packed_mask(const nm_packed_t* wp, uint8_t* mask_host);
+/* The power-of-two scale of an fp8 handle (1 for fp32 and bf16 handles). */
+int nm_packed_scale(const nm_packed_t* wp, float* scale);
 
 /*
  * nm_conv2d -- y = relu?( conv(x, W_pruned) + bias ), computed as the
@@ -117,7 +127,11 @@ int nm_packed_mask(const nm_packed_t* wp, uint8_t* mask_host);
  *
  * fp32 inputs are multiplied in fp32 on the matrix cores with fp32
  * accumulation; bf16 inputs are multiplied exactly and accumulated in fp32;
- * bf16 outputs are rounded to nearest even once.  The call only enqueues work
+ * bf16 outputs are rounded to nearest even once.  Dtype pairs: fp32 -> fp32,
+ * bf16 -> bf16, and E4M3 -> bf16 (x of NM_F8E4M3 with a handle whose values are
+ * NM_F8E4M3: products exact, fp32 accumulation, the accumulator scaled back by the
+ * handle's 2^-e before bias and activation, bf16 output; no residual dtype other
+ * than bf16).  The call only enqueues work
  * on the stream and never synchronises -- with one exception: a K-split variant
  * (name ending in "_S<n>", only ever chosen by the tuner or the test hook) keeps
  * its partial sums in a library-owned workspace per device, and the first call

@@ -13,7 +13,7 @@ from typing import Optional, Tuple
 
 import numpy as np
 
-NM_F32, NM_BF16 = 0, 1
+NM_F32, NM_BF16, NM_F8E4M3 = 0, 1, 2
 NM_OK = 0
 NM_ERR_ARG, NM_ERR_SHAPE, NM_ERR_UNSUPPORTED, NM_ERR_ALLOC, NM_ERR_HIP, NM_ERR_IO = -1, -2, -3, -4, -5, -6
 _STATUS = {0: "NM_OK", -1: "NM_ERR_ARG", -2: "NM_ERR_SHAPE", -3: "NM_ERR_UNSUPPORTED",
@@ -38,6 +38,10 @@ def lib():
             raise RuntimeError(
                 f"{LIB_PATH} is missing: build it with `python -m paper_2507_17301_amd.build` "
                 "(there is no fallback path)")
+        # PyTorch ships its own copy of the HIP runtime; a process must not end up with two.
+        # Importing torch first makes its copy the one libnmconv.so binds to as well (loaded
+        # the other way round, torch finds no GPU).
+        import torch  # noqa: F401
         L = ctypes.CDLL(LIB_PATH)
         ci, cf, vp = ctypes.c_int, ctypes.c_float, ctypes.c_void_p
         pi = ctypes.POINTER(ctypes.c_int)
@@ -52,6 +56,7 @@ def lib():
         L.nm_packed_indices.argtypes = [vp, vp]
         L.nm_packed_values.argtypes = [vp, vp]
         L.nm_packed_mask.argtypes = [vp, vp]
+        L.nm_packed_scale.argtypes = [vp, ctypes.POINTER(cf)]
         L.nm_conv2d.argtypes = [vp, ci, ci, ci, ci, ci, vp, vp, ci, ci, ci, ci, ci, ci, ci, vp, ci, vp]
         L.nm_conv2d_res.argtypes = [vp, ci, ci, ci, ci, ci, vp, vp, vp, ci, ci, ci, ci, ci, ci, ci, vp, ci, vp]
         L.nm_conv2d_static.argtypes = [vp, ci, ci, ci, ci, ci, vp, vp, vp, ci, ci, ci, ci, ci, ci, ci, vp, ci, vp]
@@ -68,7 +73,7 @@ def lib():
         L.nm_force_variant.argtypes = [ci]
         L.nm_variant_legal.argtypes = [ci, vp, ci, ci]
         for name in ("nm_prune", "nm_packed_free", "nm_packed_dims", "nm_packed_indices",
-                     "nm_packed_values", "nm_packed_mask", "nm_conv2d", "nm_conv2d_res", "nm_conv2d_static",
+                     "nm_packed_values", "nm_packed_mask", "nm_packed_scale", "nm_conv2d", "nm_conv2d_res", "nm_conv2d_static",
                      "nm_maxpool2d",
                      "nm_avgpool_global", "nm_im2col", "nm_stream_floor", "nm_autotune",
                      "nm_cache_save", "nm_cache_load", "nm_cache_clear", "nm_cache_size", "nm_workspace_free",
@@ -96,6 +101,8 @@ def _dtype_code(t) -> int:
         return NM_F32
     if t.dtype == torch.bfloat16:
         return NM_BF16
+    if t.dtype == torch.float8_e4m3fn:
+        return NM_F8E4M3
     raise TypeError(f"unsupported tensor dtype {t.dtype}")
 
 
@@ -174,6 +181,19 @@ def nm_packed_mask(wp: Packed) -> np.ndarray:
     return out
 
 
+def nm_packed_scale(wp: Packed) -> float:
+    """The power-of-two scale of an fp8 handle (stored value = weight * scale); 1 otherwise."""
+    v = ctypes.c_float(0)
+    _check(lib().nm_packed_scale(wp.handle, ctypes.byref(v)))
+    return v.value
+
+
+def _out_dtype(x):
+    """fp32 -> fp32, bf16 -> bf16, E4M3 -> bf16."""
+    import torch
+    return torch.bfloat16 if x.dtype == torch.float8_e4m3fn else x.dtype
+
+
 def _stream_ptr(stream) -> int:
     import torch
     s = torch.cuda.current_stream() if stream is None else stream
@@ -214,7 +234,7 @@ def nm_conv2d(x, wp: Packed, bias=None, stride=1, pad=0, dil=1, relu=False, y=No
     if min(shp) < 1:
         raise NMError(-2, "output would be empty")
     if y is None:
-        y = torch.empty(shp, dtype=x.dtype, device=x.device)
+        y = torch.empty(shp, dtype=_out_dtype(x), device=x.device)
     else:
         _check_out(y, shp, x)
     bptr = None
@@ -248,7 +268,7 @@ def nm_conv2d_res(x, wp: Packed, residual, bias=None, stride=1, pad=0, dil=1, re
     if min(shp) < 1:
         raise NMError(-2, "output would be empty")
     if y is None:
-        y = torch.empty(shp, dtype=x.dtype, device=x.device)
+        y = torch.empty(shp, dtype=_out_dtype(x), device=x.device)
     else:
         _check_out(y, shp, x)
     rptr = None
@@ -335,7 +355,8 @@ def nm_autotune(x_dtype: int, b: int, h: int, w: int, cin: int, wp: Packed, has_
     dh, dw = _pair(dil)
     v, ms = ctypes.c_int(-1), ctypes.c_float(0)
     _check(lib().nm_autotune(x_dtype, b, h, w, cin, wp.handle, int(bool(has_bias)), sh, sw, ph, pw,
-                             dh, dw, int(bool(relu)), x_dtype if y_dtype is None else y_dtype,
+                             dh, dw, int(bool(relu)),
+                             (NM_BF16 if x_dtype == NM_F8E4M3 else x_dtype) if y_dtype is None else y_dtype,
                              _stream_ptr(stream), ctypes.byref(v), ctypes.byref(ms)))
     return v.value, ms.value
 

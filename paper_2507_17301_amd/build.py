@@ -92,6 +92,13 @@ def _shapes_var():
     return [tuple(int(v) for v in m) for m in re.findall(r"X\((\d+),\s*(\d+),\s*(\d+)\)", body)]
 
 
+def _shapes_f8():
+    """(NBLK, WP, NJ) of NMF8_SHAPES in nm_variants.h."""
+    text = open(os.path.join(CSRC, "nm_variants.h")).read()
+    body = text[text.index("#define NMF8_SHAPES(X)"):]
+    return [tuple(int(v) for v in m) for m in re.findall(r"X\((\d+),\s*(\d+),\s*(\d+)\)", body)]
+
+
 def _jobs():
     jobs = []
     for src in ("nm_api.hip", "nm_prune_kernels.hip", "nm_pool_kernels.hip", "nm_conv_registry.hip", "nm_scratch.hip"):
@@ -122,6 +129,10 @@ def _jobs():
     instrun = os.path.join(CSRC, "nm_conv_run16_inst.hip")
     for nb, wp, nj in _shapes_run():
         jobs.append((instrun, os.path.join(OBJDIR, f"nm_conv_run16_inst_{nb}_{wp}_{nj}.o"),
+                     [f"-DNM_INST_NBLK={nb}", f"-DNM_INST_WP={wp}", f"-DNM_INST_NJ={nj}"]))
+    instf8 = os.path.join(CSRC, "nm_conv_f8_inst.hip")
+    for nb, wp, nj in _shapes_f8():
+        jobs.append((instf8, os.path.join(OBJDIR, f"nm_conv_f8_inst_{nb}_{wp}_{nj}.o"),
                      [f"-DNM_INST_NBLK={nb}", f"-DNM_INST_WP={wp}", f"-DNM_INST_NJ={nj}"]))
     return jobs
 

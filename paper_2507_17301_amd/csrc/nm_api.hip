@@ -45,6 +45,14 @@ int allow_lds(const void* fn, size_t bytes, unsigned long long* done)
 
 namespace {
 
+inline size_t elem_size(nm_dtype_t dt) { return dt == NM_F32 ? 4 : (dt == NM_BF16 ? 2 : 1); }
+// the pairs the kernels exist for: fp32 -> fp32, bf16 -> bf16, E4M3 -> bf16
+inline bool dtype_pair_ok(nm_dtype_t xdt, nm_dtype_t ydt)
+{
+    return (xdt == NM_F32 && ydt == NM_F32) || (xdt == NM_BF16 && ydt == NM_BF16) ||
+           (xdt == NM_F8E4M3 && ydt == NM_BF16);
+}
+
 constexpr int kMaxLdsBytes = 160 * 1024;
 constexpr int kNumCU = 256;
 
@@ -127,6 +135,8 @@ size_t lds_bytes(const VariantDesc& d, const nm_packed* wp)
 {
     // the epilogue's output tile [BP][channels of the workgroup] plus 16 bytes per pixel
     const size_t otile = (size_t)d.BP * ((size_t)(4 / d.WP) * d.NJ * 16 * (d.kind == 0 || d.kind == 5 ? 4 : 2) + 16);
+    if (d.kind == 6)   // only the wavefront-private output tiles [16 NBLK][16 NJ] bf16 with 16 bytes of padding per row
+        return (size_t)4 * 16 * d.NBLK * (d.NJ * 32 + 16);
     if (d.kind == 4)   // the strip [BP][64 SPC] bf16 plus the dense weights of the workgroup's row blocks
         return std::max(otile, (size_t)d.BP * d.SPC * 128 + (size_t)(4 / d.WP) * d.NJ * d.SPC * 2048);
     if (d.kind >= 2 && d.kind <= 4) {   // up to three stages of the strip [BP][CK] bf16 plus each wave's operands
@@ -171,6 +181,8 @@ bool variant_legal(int v, const nm_packed* wp, nm_dtype_t xdt, const RunArgs* ra
     const VariantDesc& d = variant_desc(v);
     if (lds_bytes(d, wp) > (size_t)kMaxLdsBytes) return false;
     if (d.kind == 5 && xdt != NM_F32) return false;   // instantiated for fp32 tensors only
+    // fp8: E4M3 tensors with an E4M3 handle run the fp8 kernel and nothing else does
+    if ((d.kind == 6) != (xdt == NM_F8E4M3) || (d.kind == 6) != (wp->value_dtype == NM_F8E4M3)) return false;
     if (d.kind >= 1 && d.kind <= 4) {
         // bf16 matrix cores: bf16 tensors, weights already rounded to bf16, and a
         // shared operand only for column tiles made of exactly two row blocks
@@ -276,6 +288,7 @@ void fill_params(ConvParams& p, const VariantDesc& d, const Prepack& pp, const n
     const int rb_per_wg = (4 / d.WP) * d.NJ;
     p.n_ptiles = (g.P + d.BP - 1) / d.BP;
     p.n_cblocks = (wp->n_rowblocks + rb_per_wg - 1) / rb_per_wg;
+    p.oscale = 1.0f / wp->scale;
     p.ksplit = d.ksplit > 1 ? d.ksplit : 1;
     p.cps = (pp.geom.nchunks + p.ksplit - 1) / p.ksplit;
     p.partial = nullptr;   // the caller points it at a workspace of split_bytes()
@@ -312,7 +325,7 @@ int heuristic_variant(const nm_packed* wp, int P, nm_dtype_t xdt, const RunArgs*
         const double mfma = (double)d.BP * rb_per_wg;            // per chunk step, relative
         const double stage = (double)d.BP * 2.0;                 // staging cost per chunk, relative
         // the bf16 matrix-core kernel contracts several times faster where it applies
-        const double speed[6] = {1.0, 0.3, 0.1, 0.2, 0.1, 0.7};   // relative cost of a unit of contraction
+        const double speed[7] = {1.0, 0.3, 0.1, 0.2, 0.1, 0.7, 0.1};   // relative cost of a unit of contraction
         const double cost = (double)rounds * occ * (mfma + stage) * speed[d.kind];
         if (best < 0 || cost < best_cost * 0.999) {
             best = v;
@@ -377,12 +390,16 @@ int check_conv_args(const void* x, nm_dtype_t xdt, int cin, const nm_packed* wp,
         set_error("cin %d does not match the packed weights (%d)", cin, wp->cin);
         return NM_ERR_ARG;
     }
-    if ((xdt != NM_F32 && xdt != NM_BF16) || (ydt != NM_F32 && ydt != NM_BF16)) {
+    if ((xdt != NM_F32 && xdt != NM_BF16 && xdt != NM_F8E4M3) || (ydt != NM_F32 && ydt != NM_BF16 && ydt != NM_F8E4M3)) {
         set_error("unknown dtype");
         return NM_ERR_ARG;
     }
-    if (xdt != ydt) {
-        set_error("unsupported dtype pair: input and output must both be fp32 or both bf16");
+    if (!dtype_pair_ok(xdt, ydt)) {
+        set_error("unsupported dtype pair: fp32 -> fp32, bf16 -> bf16 or E4M3 -> bf16");
+        return NM_ERR_UNSUPPORTED;
+    }
+    if ((xdt == NM_F8E4M3) != (wp->value_dtype == NM_F8E4M3)) {
+        set_error("E4M3 activations need weights packed as E4M3 (and the other way round)");
         return NM_ERR_UNSUPPORTED;
     }
     if (((uintptr_t)x % 16) || ((uintptr_t)y % 16)) {
@@ -440,9 +457,14 @@ int nm_prune(const float* w, int cout, int kh, int kw, int cin, int n, int m, in
         set_error("bad sizes: cout %d kh %d kw %d cin %d n %d m %d tile %d", cout, kh, kw, cin, n, m, tile);
         return NM_ERR_ARG;
     }
-    if (value_dtype != NM_F32 && value_dtype != NM_BF16) {
+    if (value_dtype != NM_F32 && value_dtype != NM_BF16 && value_dtype != NM_F8E4M3) {
         set_error("unknown value dtype");
         return NM_ERR_ARG;
+    }
+    if (value_dtype == NM_F8E4M3 && (cin % 64 != 0 || tile % 16 != 0 || cout % 8 != 0)) {
+        set_error("E4M3 weights need cin %% 64 == 0, tile %% 16 == 0 and cout %% 8 == 0 (cin %d, tile %d, cout %d)",
+                  cin, tile, cout);
+        return NM_ERR_UNSUPPORTED;
     }
     const long long K = (long long)kh * kw * cin;
     if (K % m != 0) {
@@ -504,10 +526,49 @@ int nm_prune(const float* w, int cout, int kh, int kw, int cin, int n, int m, in
                               hipMemcpyDeviceToHost, s), NM_ERR_HIP);
     NM_TRY_HIP(hipStreamSynchronize(s), NM_ERR_HIP);
 
+    if (value_dtype == NM_F8E4M3) {
+        // one power-of-two scale per layer: the largest 2^e that keeps every kept weight within
+        // the format (|w| 2^e <= 448); the kept values become the E4M3 numbers they are stored as
+        float most = 0.f;
+        for (int j = 0; j < wp->n_tiles; ++j)
+            for (int kk = 0; kk < wp->kprime; ++kk) {
+                const size_t k = (size_t)wp->h_idx[(size_t)j * wp->kprime + kk];
+                const int r1 = std::min(cout, (j + 1) * tile);
+                for (int r = j * tile; r < r1; ++r) most = std::max(most, fabsf(w[(size_t)r * K + k]));
+            }
+        float scale = 1.f;
+        if (most > 0.f) {
+            int e = 0;
+            (void)frexpf(448.0f / most, &e);       // 448 / most = f 2^e with 0.5 <= f < 1
+            scale = ldexpf(1.0f, e - 1);
+            while (most * scale > 448.0f) scale *= 0.5f;   // the quotient above is rounded
+        }
+        wp->scale = scale;
+        rc = run_quantize_e4m3(wp, s);
+        if (rc != NM_OK) return fail(rc);
+    }
+
     // Operand tables for every chunk geometry a kernel variant may ask for.
     const bool vec_ok = cin % 4 == 0;
     for (int v = 0; v < variant_count(); ++v) {
         const VariantDesc& d = variant_desc(v);
+        if ((d.kind == 6) != (value_dtype == NM_F8E4M3)) continue;   // E4M3 handles feed the fp8 kernel only
+        if (d.kind == 6) {
+            if (find_prepack(wp, d)) continue;
+            Prepack pp;
+            pp.kind = 6;
+            pp.geom = make_chunk_geom(cin, wp->K, 64, 1);
+            pp.SPC = d.SPC;
+            pp.rows_bytes = 0;
+            pp.wfrag_bytes = (size_t)wp->n_rowblocks * pp.geom.nchunks * 64 * 16;
+            if (pp.wfrag_bytes >= 0x80000000ull) continue;
+            wp->prepacks.push_back(pp);
+            Prepack& ref = wp->prepacks.back();
+            NM_TRY_HIP(hipMalloc(reinterpret_cast<void**>(&ref.d_wfrag), ref.wfrag_bytes), NM_ERR_ALLOC);
+            rc = run_build_prepack(wp, ref, s);
+            if (rc != NM_OK) return fail(rc);
+            continue;
+        }
         if (d.kind == 4) {
             // kernel-row runs: only where channel runs are too short for the other bf16 kernels
             if (value_dtype != NM_BF16 || cin % 8 == 0) continue;
@@ -679,6 +740,16 @@ int nm_packed_mask(const nm_packed_t* wp, uint8_t* mask_host)
     return rc;
 }
 
+int nm_packed_scale(const nm_packed_t* wp, float* scale)
+{
+    if (!wp || !scale) {
+        set_error("null pointer argument");
+        return NM_ERR_ARG;
+    }
+    *scale = wp->scale;
+    return NM_OK;
+}
+
 int nm_force_variant(int v)
 {
     if (v < -1 || v >= variant_count()) {
@@ -698,7 +769,7 @@ int nm_variant_legal(int variant, const nm_packed_t* wp, nm_dtype_t xdt, nm_dtyp
         set_error("bad arguments");
         return NM_ERR_ARG;
     }
-    if (xdt != ydt) return 0;
+    if (!dtype_pair_ok(xdt, ydt)) return 0;
     return variant_legal(variant, wp, xdt) ? 1 : 0;
 }
 
@@ -713,10 +784,10 @@ static int conv2d_impl(const void* x, nm_dtype_t xdt, int b, int h, int w, int c
         return NM_ERR_ARG;
     }
     Geometry g;
-    rc = conv_geometry(b, h, w, wp, sh, sw, ph, pw, dh, dw, xdt == NM_F32 ? 4 : 2, &g);
+    rc = conv_geometry(b, h, w, wp, sh, sw, ph, pw, dh, dw, elem_size(xdt), &g);
     if (rc != NM_OK) return rc;
     if (res) {
-        const size_t ybytes = (size_t)g.P * wp->cout * (ydt == NM_F32 ? 4 : 2);
+        const size_t ybytes = (size_t)g.P * wp->cout * elem_size(ydt);
         const uintptr_t r0 = (uintptr_t)res, y0 = (uintptr_t)y;
         if (r0 < y0 + ybytes && y0 < r0 + ybytes) {
             set_error("residual must not overlap y");
@@ -753,7 +824,7 @@ static int conv2d_impl(const void* x, nm_dtype_t xdt, int b, int h, int w, int c
     const VariantDesc& d = variant_desc(v);
     ConvParams p;
     fill_params(p, d, *find_prepack(wp, d, (pw * wp->cin) % 2), wp, x, y, bias, b, h, w, g, sh, sw, ph, pw,
-                dh, dw, relu, xdt == NM_F32 ? 4 : 2);
+                dh, dw, relu, elem_size(xdt));
     p.res = res;
     if (d.ksplit > 1) {
         const size_t need = split_bytes(d, g, wp);
@@ -878,12 +949,12 @@ int nm_autotune(nm_dtype_t xdt, int b, int h, int w, int cin, const nm_packed_t*
         set_error("cin %d does not match the packed weights (%d)", cin, wp->cin);
         return NM_ERR_ARG;
     }
-    if (xdt != ydt || (xdt != NM_F32 && xdt != NM_BF16)) {
-        set_error("unsupported dtype pair: input and output must both be fp32 or both bf16");
+    if (!dtype_pair_ok(xdt, ydt) || (xdt == NM_F8E4M3) != (wp->value_dtype == NM_F8E4M3)) {
+        set_error("unsupported dtype pair: fp32 -> fp32, bf16 -> bf16 or E4M3 -> bf16 (E4M3 with E4M3 weights)");
         return NM_ERR_UNSUPPORTED;
     }
     Geometry g;
-    int rc = conv_geometry(b, h, w, wp, sh, sw, ph, pw, dh, dw, xdt == NM_F32 ? 4 : 2, &g);
+    int rc = conv_geometry(b, h, w, wp, sh, sw, ph, pw, dh, dw, elem_size(xdt), &g);
     if (rc != NM_OK) return rc;
     const ShapeKey key = make_key(xdt, ydt, b, h, w, wp, sh, sw, ph, pw, dh, dw, has_bias, relu);
     const RunArgs ra = {w, sw, pw, dw};
@@ -897,13 +968,13 @@ int nm_autotune(nm_dtype_t xdt, int b, int h, int w, int cin, const nm_packed_t*
         }
     }
     hipStream_t s = (hipStream_t)stream;
-    const size_t es = xdt == NM_F32 ? 4 : 2;
+    const size_t es = elem_size(xdt), yes = elem_size(ydt);
     const size_t xn = (size_t)b * h * w * cin, yn = (size_t)g.P * wp->cout;
     // Cold-cache protocol: in a network every layer finds the 256 MB last-level
     // cache full of other layers' data, so the candidates are timed on a ring
     // of input/output sets (about 768 MB in total) and no launch reuses the
     // set of a recent one.
-    const size_t xbytes = (xn * es + 255) & ~(size_t)255, ybytes = (yn * es + 255) & ~(size_t)255;
+    const size_t xbytes = (xn * es + 255) & ~(size_t)255, ybytes = (yn * yes + 255) & ~(size_t)255;
     const size_t pool = (size_t)768 << 20;
     int nbuf = (int)std::min<size_t>(64, std::max<size_t>(1, pool / (xbytes + ybytes)));
     char* dpool = nullptr;

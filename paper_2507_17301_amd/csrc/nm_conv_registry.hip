@@ -54,9 +54,14 @@ struct Entry {
      &launch_t<NB, WP, NJ, CK, SPC, 2, float, float>, nullptr},
 #define NM_SHAPE_ENTRIESVAR(NB, WP, NJ) NMVAR_CHUNKS(NM_ENTRYVAR, NB, WP, NJ)
 
+// kind 6: fp8 E4M3 in, bf16 out (the launcher sits in the bf16-output slot; x is E4M3)
+#define NM_ENTRYF8(NB, WP, NJ)                                                                  \
+    {{"F8_NB" #NB "_WP" #WP "_NJ" #NJ, 16 * NB * WP, NB, WP, NJ, 64, 1, 1, 6, 1, 1, 0}, nullptr, &launch_f8_t<NB, WP, NJ>},
+
 const Entry kEntries[] = {NM_SHAPES(NM_SHAPE_ENTRIES) NM_SCALAR_VARIANTS(NM_ENTRY)
                           NM16_SHAPES(NM_SHAPE_ENTRIES16) NMSP_SHAPES(NM_SHAPE_ENTRIESSP) NMSPW_SHAPES(NM_SHAPE_ENTRIESSPW) NMSPR_SHAPES(NM_SHAPE_ENTRIESSPR)
-                          NMRUN_SHAPES(NM_SHAPE_ENTRIESRUN) NMVAR_SHAPES(NM_SHAPE_ENTRIESVAR)};
+                          NMRUN_SHAPES(NM_SHAPE_ENTRIESRUN) NMVAR_SHAPES(NM_SHAPE_ENTRIESVAR)
+                          NMF8_SHAPES(NM_ENTRYF8)};
 constexpr int kCount = (int)(sizeof(kEntries) / sizeof(kEntries[0]));
 
 // The fp32 MFMA kernel also runs with its K axis split over several workgroups per output
@@ -105,9 +110,11 @@ int launch_conv(int v, nm_dtype_t xdt, nm_dtype_t ydt, const ConvParams& p, hipS
         return NM_ERR_UNSUPPORTED;
     }
     const Entry& e = kEntries[table().base[v]];
-    if (xdt == NM_F32 && ydt == NM_F32 && e.ff) return e.ff(p, s);
-    if (xdt == NM_BF16 && ydt == NM_BF16 && e.bb) return e.bb(p, s);
-    set_error("unsupported dtype pair: input and output must both be fp32 or both bf16");
+    const bool f8 = e.d.kind == 6;
+    if (xdt == NM_F32 && ydt == NM_F32 && e.ff && !f8) return e.ff(p, s);
+    if (xdt == NM_BF16 && ydt == NM_BF16 && e.bb && !f8) return e.bb(p, s);
+    if (xdt == NM_F8E4M3 && ydt == NM_BF16 && e.bb && f8) return e.bb(p, s);
+    set_error("unsupported dtype pair: fp32 -> fp32, bf16 -> bf16 or E4M3 -> bf16");
     return NM_ERR_UNSUPPORTED;
 }
 }  // namespace nm

@@ -62,7 +62,8 @@ inline ChunkGeom make_chunk_geom(int cin, int K, int CK, int vec)
 // unused slots carry weight 0 and row 0.
 struct Prepack {
     int kind = 0;                     // 0: fp32 MFMA kernel, 1: bf16 MFMA gather kernel, 2/3: gather-free bf16 kernel,
-                                      // 4: bf16 kernel-row runs, 5: fp32 MFMA kernel with per-chunk step counts
+                                      // 4: bf16 kernel-row runs, 5: fp32 MFMA kernel with per-chunk step counts,
+                                      // 6: fp8 kernel (dense instruction on zero-filled weights)
     ChunkGeom geom{};
     int SPC = 0;                      // k-steps per chunk (1, 2, 4 or 8)
     // kind 0: a k-step is 4 kept columns
@@ -80,6 +81,8 @@ struct Prepack {
     // kind 4 (contiguous kernel-row runs, layers with very few input channels): one chunk of SPC
     //   64-element k-steps; per pixel Kh runs of GR granules, each starting `par` elements early
     //   d_wfrag [n_rowblocks][SPC][2][64][8] bf16   A-operand lane values, zero in padding slots
+    // kind 6 (fp8 E4M3, dense instruction): a chunk is 64 channels of one tap
+    //   d_wfrag [n_rowblocks][nchunks][64][16] bytes   lane i + 16 q, byte e = channel 16 q + e of the chunk
     int par = 0;                      // kind 4: 0 or 1 elements of lead-in per run (alignment of the run start)
     uint32_t* d_rows = nullptr;
     float* d_wfrag = nullptr;
@@ -113,6 +116,7 @@ struct nm_packed {
     int n_rowblocks;  // n_tiles * rbpt
     nm_dtype_t value_dtype;
     int device;
+    float scale = 1.f;   // fp8 handles: the stored E4M3 value is weight * scale (a power of two)
     int sig = 0;      // hash of the operand tables built for this handle (part of the tuning-cache key)
     int32_t* d_idx = nullptr;   // [n_tiles][kprime]
     float* d_vals = nullptr;    // [n_tiles][kprime][tile]
@@ -154,6 +158,7 @@ struct ConvParams {
     // them up and applies bias, residual and activation.  ksplit <= 1: no split, partial unused.
     float* partial;
     int ksplit, cps;
+    float oscale;      // fp8: factor that takes the accumulator back to the weights' own scale (1 / handle scale)
 };
 
 struct VariantDesc {
@@ -169,6 +174,7 @@ struct VariantDesc {
                // 2 = bf16 sparse-matrix-instruction kernel, 3 = bf16 dense kernel on zero-filled weights,
                // 4 = bf16 dense kernel on contiguous kernel-row runs (very few input channels),
                // 5 = fp32 MFMA kernel that runs only the k-steps holding kept columns of each (tile, chunk)
+               // 6 = fp8 E4M3 kernel (fp8 activations, bf16 output): dense instruction on zero-filled weights
     int share; // kind 1: row blocks fed from one gathered operand
     int ksplit; // kinds 0, 5: workgroups that share the K axis of one output tile (1 = no split)
     int areg;  // kinds 2, 3: 1 = weights and index words go straight to registers, the LDS stages hold the strip alone
@@ -187,6 +193,7 @@ int launch_conv(int v, nm_dtype_t xdt, nm_dtype_t ydt, const ConvParams& p, hipS
 int run_prune(const float* d_w, nm_packed* wp, hipStream_t s);
 int run_build_prepack(nm_packed* wp, Prepack& pp, hipStream_t s);   // any kind
 int run_build_mask(const nm_packed* wp, uint8_t* d_mask, hipStream_t s);
+int run_quantize_e4m3(nm_packed* wp, hipStream_t s);   // d_vals -> the E4M3 values they are stored as (needs wp->scale)
 int run_fill_random(void* d, size_t n_elems, nm_dtype_t dt, uint32_t seed, hipStream_t s);
 
 // pooling kernels (nm_pool_kernels.hip)

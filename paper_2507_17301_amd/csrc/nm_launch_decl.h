@@ -14,4 +14,6 @@ template <int NBLK, int WP, int NJ, int CK, bool SPARSE, bool SPEC, bool AREG = 
 int launch_sp16_t(const ConvParams& p, hipStream_t s);
 template <int NBLK, int WP, int NJ, int KS>
 int launch_run16_t(const ConvParams& p, hipStream_t s);
+template <int NBLK, int WP, int NJ>
+int launch_f8_t(const ConvParams& p, hipStream_t s);
 }  // namespace nm

@@ -70,6 +70,38 @@ __device__ inline float round_bf16_rne(float v)
     return __uint_as_float(u & 0xffff0000u);
 }
 
+// fp32 -> fp8 E4M3 code (the OCP "e4m3fn" format: bias 7, 3 mantissa bits, subnormals,
+// largest value 448), round to nearest, ties to even, in integer arithmetic on the fp32
+// bit pattern.  |v| <= 448 here by construction of the weight scale.
+__device__ inline unsigned e4m3_code(float v)
+{
+    const unsigned u = __float_as_uint(v), sign = (u >> 24) & 0x80u;
+    const unsigned a = u & 0x7fffffffu;
+    const int e = (int)(a >> 23) - 127;            // leading bit at 2^e
+    if (a == 0u || e < -10) return sign;           // below half of the smallest step 2^-9
+    const unsigned man = (a & 0x7fffffu) | 0x800000u;   // |v| = man * 2^(e - 23)
+    const int E = e < -6 ? -6 : e;                 // binade whose spacing 2^(E - 3) applies
+    const int shift = 20 + (E - e);                // |v| / 2^(E - 3) = man / 2^shift
+    const unsigned q0 = man >> shift, rem = man & ((1u << shift) - 1u), half = 1u << (shift - 1);
+    const unsigned q = q0 + ((rem > half || (rem == half && (q0 & 1u))) ? 1u : 0u);
+    // normal numbers: q in 8 .. 16, and q = 16 carries into the exponent field by itself;
+    // below 2^-6: q in 0 .. 8 is the subnormal's mantissa (8 = the smallest normal)
+    return e >= -6 ? sign | (unsigned)(((E + 7) << 3) + (int)q - 8) : sign | q;
+}
+__device__ inline float e4m3_value(unsigned code)
+{
+    const int ex = (int)((code >> 3) & 15u), m = (int)(code & 7u);
+    const float a = ex == 0 ? ldexpf((float)m, -9) : ldexpf((float)(8 + m), ex - 10);
+    return (code & 0x80u) ? -a : a;
+}
+
+// kept values -> the E4M3 value they are stored as under the layer's power-of-two scale, in place
+__global__ void quantize_e4m3_kernel(float* __restrict__ vals, size_t n, float scale, float inv_scale)
+{
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x)
+        vals[i] = e4m3_value(e4m3_code(vals[i] * scale)) * inv_scale;
+}
+
 // vals[j][kk][t] = w[j*T + t][idx[j][kk]] (zero beyond Cout), optionally
 // rounded to bf16.
 __global__ void pack_values_kernel(const float* __restrict__ w, const int32_t* __restrict__ idx,
@@ -358,11 +390,44 @@ __global__ void fill_random_kernel(void* dst, size_t n, int bf16, unsigned seed)
          i += (size_t)gridDim.x * blockDim.x) {
         const unsigned h = hash32((unsigned)i * 2654435761u + seed);
         const float v = (float)(h >> 8) * (1.0f / 16777216.0f);   // [0,1)
-        if (bf16)
+        if (bf16 == 2)
+            reinterpret_cast<unsigned char*>(dst)[i] = (unsigned char)e4m3_code(v);
+        else if (bf16)
             reinterpret_cast<unsigned short*>(dst)[i] =
                 (unsigned short)(__float_as_uint(round_bf16_rne(v)) >> 16);
         else
             reinterpret_cast<float*>(dst)[i] = v;
+    }
+}
+
+// Operand table of the fp8 kernel (dense instruction on zero-filled weights): one thread per
+// (row block, 64-channel chunk, lane) writes that lane's 16 A-operand bytes: byte e of lane
+// i + 16 q is channel 16 q + e of the chunk (bytes 0-7 feed the first 16x16x32 instruction of
+// the k-step, bytes 8-15 the second), the weight's E4M3 code under the layer's scale, or 0.
+__global__ __launch_bounds__(256) void build_prepack_f8_kernel(
+    const int32_t* __restrict__ idx, const float* __restrict__ vals, int kprime, int T, int rbpt,
+    int n_rowblocks, int cin, int ncpt, int nchunks, float scale, unsigned char* __restrict__ wfrag)
+{
+    const size_t total = (size_t)n_rowblocks * nchunks * 64;
+    for (size_t id = (size_t)blockIdx.x * blockDim.x + threadIdx.x; id < total;
+         id += (size_t)gridDim.x * blockDim.x) {
+        const int lane = (int)(id % 64);
+        const size_t r = id / 64;
+        const int c = (int)(r % nchunks), rb = (int)(r / nchunks);
+        const int i = lane & 15, q = lane >> 4;
+        const int j = rb / rbpt, t = (rb - j * rbpt) * 16 + i;
+        const int32_t* idxj = idx + (size_t)j * kprime;
+        const int tap = c / ncpt, k0 = tap * cin + (c - tap * ncpt) * 64 + 16 * q;
+        unsigned w4[4] = {0u, 0u, 0u, 0u};
+        for (int e = 0; e < 16; ++e) {
+            const int k = k0 + e;
+            const int lb = lower_bound_idx(idxj, kprime, k);
+            float v = 0.f;
+            if (lb < kprime && idxj[lb] == k && t < T) v = vals[((size_t)j * kprime + lb) * T + t];
+            w4[e >> 2] |= e4m3_code(v * scale) << (8 * (e & 3));
+        }
+        unsigned* dst = reinterpret_cast<unsigned*>(wfrag + id * 16);
+        dst[0] = w4[0]; dst[1] = w4[1]; dst[2] = w4[2]; dst[3] = w4[3];
     }
 }
 
@@ -404,7 +469,12 @@ int run_build_prepack(nm_packed* wp, Prepack& pp, hipStream_t s)
     NM_HIP_CHECK(hipMalloc(&d_err, sizeof(int)));
     NM_HIP_CHECK(hipMemsetAsync(d_err, 0, sizeof(int), s));
     const size_t lds = (size_t)2 * g.nchunks * sizeof(int);
-    if (pp.kind == 0 || pp.kind == 5)
+    if (pp.kind == 6) {
+        const size_t total = (size_t)wp->n_rowblocks * g.nchunks * 64;
+        hipLaunchKernelGGL(build_prepack_f8_kernel, dim3(grid_for(total, 256)), dim3(256), 0, s, wp->d_idx,
+                           wp->d_vals, wp->kprime, wp->tile, wp->rbpt, wp->n_rowblocks, wp->cin, g.ncpt,
+                           g.nchunks, wp->scale, reinterpret_cast<unsigned char*>(pp.d_wfrag));
+    } else if (pp.kind == 0 || pp.kind == 5)
         hipLaunchKernelGGL(build_prepack_kernel, dim3(wp->n_tiles), dim3(256), lds, s, wp->d_idx,
                            wp->d_vals, wp->kprime, wp->tile, wp->rbpt, wp->cin, g.CK, g.vec, g.ncpt,
                            g.nchunks, pp.SPC, pp.kind == 5 ? 1 : 0, pp.d_rows, pp.d_wfrag, d_err);
@@ -440,6 +510,15 @@ int run_build_prepack(nm_packed* wp, Prepack& pp, hipStream_t s)
     return NM_OK;
 }
 
+int run_quantize_e4m3(nm_packed* wp, hipStream_t s)
+{
+    const size_t n = (size_t)wp->n_tiles * wp->kprime * wp->tile;
+    hipLaunchKernelGGL(quantize_e4m3_kernel, dim3(grid_for(n, 256)), dim3(256), 0, s, wp->d_vals, n, wp->scale,
+                       1.0f / wp->scale);
+    NM_HIP_CHECK(hipGetLastError());
+    return NM_OK;
+}
+
 int run_build_mask(const nm_packed* wp, unsigned char* d_mask, hipStream_t s)
 {
     NM_HIP_CHECK(hipMemsetAsync(d_mask, 0, (size_t)wp->cout * wp->K, s));
@@ -453,7 +532,7 @@ int run_build_mask(const nm_packed* wp, unsigned char* d_mask, hipStream_t s)
 int run_fill_random(void* d, size_t n_elems, nm_dtype_t dt, uint32_t seed, hipStream_t s)
 {
     hipLaunchKernelGGL(fill_random_kernel, dim3(grid_for(n_elems, 256)), dim3(256), 0, s, d,
-                       n_elems, dt == NM_BF16 ? 1 : 0, seed);
+                       n_elems, dt == NM_BF16 ? 1 : (dt == NM_F8E4M3 ? 2 : 0), seed);
     NM_HIP_CHECK(hipGetLastError());
     return NM_OK;
 }

@@ -83,3 +83,9 @@
     X(4, 1, 1) X(8, 1, 1) X(2, 1, 1) X(2, 2, 2) X(4, 2, 2) X(2, 4, 4) X(4, 4, 4) X(1, 4, 4) X(3, 4, 4) X(7, 1, 1)
 // Y(NBLK, WP, NJ, KS)
 #define NMRUN_CHUNKS(Y, NB, WP, NJ) Y(NB, WP, NJ, 1) Y(NB, WP, NJ, 2) Y(NB, WP, NJ, 3) Y(NB, WP, NJ, 4)
+
+// fp8 (E4M3 activations and weights, bf16 output): both operands streamed from global memory
+// into registers, 64-channel k-steps.
+// X(NBLK, WP, NJ)
+#define NMF8_SHAPES(X) \
+    X(4, 1, 4) X(4, 2, 4) X(4, 4, 4) X(2, 1, 4) X(2, 2, 4) X(2, 4, 4) X(4, 1, 2) X(4, 2, 2) X(8, 1, 2) X(8, 2, 2)

@@ -114,6 +114,7 @@ static const VariantDesc kFake[] = {
     {"F_SPR1_NB4_NJ2_CK64", 64, 4, 1, 2, 64, 1, 1, 2, 1, 1, 1},
     {"F_RUN_NB4_KS3", 64, 4, 1, 1, 192, 3, 1, 4, 1, 1, 0},
     {"F_RUN_NB4_KS1", 64, 4, 1, 1, 64, 1, 1, 4, 1, 1, 0},
+    {"F_F8_NB4_WP1_NJ4", 64, 4, 1, 4, 64, 1, 1, 6, 1, 1, 0},
     // K-split forms of the fp32 kernel
     {"F_NB4_WP1_NJ1_CK32_SPC4_S2", 64, 4, 1, 1, 32, 4, 1, 0, 1, 2, 0},
     {"F_NB4_WP1_NJ1_CK32_SPC4_S4", 64, 4, 1, 1, 32, 4, 1, 0, 1, 4, 0},
@@ -129,8 +130,10 @@ int launch_conv(int v, nm_dtype_t xdt, nm_dtype_t ydt, const ConvParams& p, hipS
     const VariantDesc& d = kFake[v];
     g_timer_variant = v;
     ++g_launches;
-    const size_t es = xdt == NM_F32 ? 4 : 2;
-    CHECK(xdt == ydt);
+    const size_t es = xdt == NM_F32 ? 4 : (xdt == NM_BF16 ? 2 : 1), yes = ydt == NM_F32 ? 4 : 2;
+    CHECK(xdt == ydt || (xdt == NM_F8E4M3 && ydt == NM_BF16));
+    CHECK((d.kind == 6) == (xdt == NM_F8E4M3));
+    CHECK(p.oscale > 0.f && (d.kind == 6 || p.oscale == 1.f));
     // the geometry the kernels rely on
     const long eh = (long)p.H + 2L * p.ph - (long)p.dh * (p.Kh - 1) - 1, ew = (long)p.W + 2L * p.pw - (long)p.dw * (p.Kw - 1) - 1;
     CHECK(eh >= 0 && ew >= 0 && p.Ho == eh / p.sh + 1 && p.Wo == ew / p.sw + 1);
@@ -153,9 +156,9 @@ int launch_conv(int v, nm_dtype_t xdt, nm_dtype_t ydt, const ConvParams& p, hipS
         CHECK(q2 == x / (unsigned)p.Wo);
     }
     // every pointer is an allocation of the right size
-    CHECK(inside(p.x, p.x_bytes) && inside(p.y, (size_t)p.P * p.Cout * es));
+    CHECK(inside(p.x, p.x_bytes) && inside(p.y, (size_t)p.P * p.Cout * yes));
     CHECK(!p.bias || inside(p.bias, (size_t)p.Cout * 4));
-    CHECK(!p.res || inside(p.res, (size_t)p.P * p.Cout * es));
+    CHECK(!p.res || inside(p.res, (size_t)p.P * p.Cout * yes));
     CHECK(inside(p.wfrag, p.wfrag_bytes));
     CHECK(p.rows_bytes == 0 || inside(p.rows, p.rows_bytes));
     if (!d.vec) CHECK(p.ktab && inside(p.ktab, (size_t)p.nchunks * d.CK * 4));
@@ -183,6 +186,13 @@ int run_build_prepack(nm_packed* wp, Prepack& pp, hipStream_t)
     (void)wp;
     return NM_OK;
 }
+int run_quantize_e4m3(nm_packed* wp, hipStream_t)
+{
+    CHECK(wp->scale > 0.f && inside(wp->d_vals, (size_t)wp->n_tiles * wp->kprime * wp->tile * 4));
+    int e = 0;
+    CHECK(frexpf(wp->scale, &e) == 0.5f);   // a power of two
+    return NM_OK;
+}
 int run_build_mask(const nm_packed* wp, uint8_t* d_mask, hipStream_t)
 {
     CHECK(inside(d_mask, (size_t)wp->cout * wp->K));
@@ -191,7 +201,7 @@ int run_build_mask(const nm_packed* wp, uint8_t* d_mask, hipStream_t)
 }
 int run_fill_random(void* d, size_t n, nm_dtype_t dt, uint32_t, hipStream_t)
 {
-    CHECK(inside(d, n * (dt == NM_F32 ? 4 : 2)));
+    CHECK(inside(d, n * (dt == NM_F32 ? 4 : (dt == NM_BF16 ? 2 : 1))));
     return NM_OK;
 }
 int run_maxpool(const void*, nm_dtype_t, int, int, int, int, int, int, int, int, int, void*, hipStream_t) { return NM_OK; }
@@ -242,53 +252,54 @@ static void conv_case(int b, int h, int w, int cin, int cout, int kh, int kw, in
     CHECK(nm_packed_indices(wp, idx.data()) == NM_OK);
     CHECK(nm_packed_values(wp, vals.data()) == NM_OK);
     CHECK(nm_packed_mask(wp, mask.data()) == NM_OK);
-    const size_t es = dt == NM_F32 ? 4 : 2;
+    const nm_dtype_t ydt = dt == NM_F8E4M3 ? NM_BF16 : dt;
+    const size_t es = dt == NM_F32 ? 4 : (dt == NM_BF16 ? 2 : 1), yes = ydt == NM_F32 ? 4 : 2;
     const long eh = (long)h + 2L * ph - (long)dh * (kh - 1) - 1, ew = (long)w + 2L * pw - (long)dw * (kw - 1) - 1;
     const int ho = (int)(eh / sh) + 1, wo = (int)(ew / sw) + 1;
     void* x = dev_alloc((size_t)b * h * w * cin * es);
-    void* y = dev_alloc((size_t)b * ho * wo * cout * es);
-    void* r = dev_alloc((size_t)b * ho * wo * cout * es);
+    void* y = dev_alloc((size_t)b * ho * wo * cout * yes);
+    void* r = dev_alloc((size_t)b * ho * wo * cout * yes);
     float* bias = (float*)dev_alloc((size_t)cout * 4);
     const int before = g_launches;
-    CHECK(nm_conv2d(x, dt, b, h, w, cin, wp, bias, sh, sw, ph, pw, dh, dw, 1, y, dt, nullptr) == NM_OK);
+    CHECK(nm_conv2d(x, dt, b, h, w, cin, wp, bias, sh, sw, ph, pw, dh, dw, 1, y, ydt, nullptr) == NM_OK);
     CHECK(g_launches == before + 1 && nm_last_variant() >= 0);
-    CHECK(nm_conv2d_res(x, dt, b, h, w, cin, wp, nullptr, r, sh, sw, ph, pw, dh, dw, 0, y, dt, nullptr) == NM_OK);
-    CHECK(nm_conv2d_res(x, dt, b, h, w, cin, wp, nullptr, y, sh, sw, ph, pw, dh, dw, 0, y, dt, nullptr) == NM_ERR_ARG);
+    CHECK(nm_conv2d_res(x, dt, b, h, w, cin, wp, nullptr, r, sh, sw, ph, pw, dh, dw, 0, y, ydt, nullptr) == NM_OK);
+    CHECK(nm_conv2d_res(x, dt, b, h, w, cin, wp, nullptr, y, sh, sw, ph, pw, dh, dw, 0, y, ydt, nullptr) == NM_ERR_ARG);
     int v = -1;
     float ms = 0.f;
-    CHECK(nm_autotune(dt, b, h, w, cin, wp, 1, sh, sw, ph, pw, dh, dw, 1, dt, nullptr, &v, &ms) == NM_OK);
-    CHECK(v >= 0 && ms > 0.f && nm_variant_legal(v, wp, dt, dt) == 1);
-    CHECK(nm_conv2d(x, dt, b, h, w, cin, wp, bias, sh, sw, ph, pw, dh, dw, 1, y, dt, nullptr) == NM_OK);
+    CHECK(nm_autotune(dt, b, h, w, cin, wp, 1, sh, sw, ph, pw, dh, dw, 1, ydt, nullptr, &v, &ms) == NM_OK);
+    CHECK(v >= 0 && ms > 0.f && nm_variant_legal(v, wp, dt, ydt) == 1);
+    CHECK(nm_conv2d(x, dt, b, h, w, cin, wp, bias, sh, sw, ph, pw, dh, dw, 1, y, ydt, nullptr) == NM_OK);
     CHECK(nm_last_variant() == v);
     // every legal variant forced in turn, an illegal one refused
     for (int u = 0; u < nm_variant_count(); ++u) {
         CHECK(nm_force_variant(u) == NM_OK);
-        const int legal = nm_variant_legal(u, wp, dt, dt);
-        const int rc = nm_conv2d(x, dt, b, h, w, cin, wp, bias, sh, sw, ph, pw, dh, dw, 1, y, dt, nullptr);
+        const int legal = nm_variant_legal(u, wp, dt, ydt);
+        const int rc = nm_conv2d(x, dt, b, h, w, cin, wp, bias, sh, sw, ph, pw, dh, dw, 1, y, ydt, nullptr);
         CHECK(legal ? (rc == NM_OK || rc == NM_ERR_UNSUPPORTED) : rc == NM_ERR_UNSUPPORTED);
     }
     CHECK(nm_force_variant(-1) == NM_OK);
     // K-split variants: through the growable workspace, through the static scratch, and under capture
     for (int u = 0; u < nm_variant_count(); ++u) {
         const char* nme = nm_variant_name(u);
-        if (!strstr(nme, "_S") || nm_variant_legal(u, wp, dt, dt) != 1) continue;
+        if (!strstr(nme, "_S") || nm_variant_legal(u, wp, dt, ydt) != 1) continue;
         CHECK(nm_force_variant(u) == NM_OK);
-        CHECK(nm_conv2d_static(x, dt, b, h, w, cin, wp, bias, r, sh, sw, ph, pw, dh, dw, 1, y, dt, nullptr) == NM_OK);
-        CHECK(nm_conv2d(x, dt, b, h, w, cin, wp, bias, sh, sw, ph, pw, dh, dw, 1, y, dt, nullptr) == NM_OK);
+        CHECK(nm_conv2d_static(x, dt, b, h, w, cin, wp, bias, r, sh, sw, ph, pw, dh, dw, 1, y, ydt, nullptr) == NM_OK);
+        CHECK(nm_conv2d(x, dt, b, h, w, cin, wp, bias, sh, sw, ph, pw, dh, dw, 1, y, ydt, nullptr) == NM_OK);
         g_capturing = true;   // large enough already: no allocation, so capture is fine
-        CHECK(nm_conv2d(x, dt, b, h, w, cin, wp, bias, sh, sw, ph, pw, dh, dw, 1, y, dt, nullptr) == NM_OK);
+        CHECK(nm_conv2d(x, dt, b, h, w, cin, wp, bias, sh, sw, ph, pw, dh, dw, 1, y, ydt, nullptr) == NM_OK);
         g_capturing = false;
     }
     CHECK(nm_force_variant(-1) == NM_OK);
     // argument and shape errors
-    CHECK(nm_conv2d(x, dt, b, h, w, cin + 1, wp, bias, sh, sw, ph, pw, dh, dw, 1, y, dt, nullptr) == NM_ERR_ARG);
-    CHECK(nm_conv2d((char*)x + 2, dt, b, h, w, cin, wp, bias, sh, sw, ph, pw, dh, dw, 1, y, dt, nullptr) == NM_ERR_ARG);
-    CHECK(nm_conv2d(x, dt, b, h, w, cin, wp, bias, 0, sw, ph, pw, dh, dw, 1, y, dt, nullptr) == NM_ERR_ARG);
-    CHECK(nm_conv2d(x, dt, b, h, w, cin, wp, bias, sh, sw, ph, pw, h + 2 * ph + 1, dw, 1, y, dt, nullptr) ==
+    CHECK(nm_conv2d(x, dt, b, h, w, cin + 1, wp, bias, sh, sw, ph, pw, dh, dw, 1, y, ydt, nullptr) == NM_ERR_ARG);
+    CHECK(nm_conv2d((char*)x + 2, dt, b, h, w, cin, wp, bias, sh, sw, ph, pw, dh, dw, 1, y, ydt, nullptr) == NM_ERR_ARG);
+    CHECK(nm_conv2d(x, dt, b, h, w, cin, wp, bias, 0, sw, ph, pw, dh, dw, 1, y, ydt, nullptr) == NM_ERR_ARG);
+    CHECK(nm_conv2d(x, dt, b, h, w, cin, wp, bias, sh, sw, ph, pw, h + 2 * ph + 1, dw, 1, y, ydt, nullptr) ==
           (kh > 1 ? NM_ERR_SHAPE : NM_OK));
-    CHECK(nm_conv2d(x, dt, b, h, w, cin, wp, bias, sh, sw, ph, pw, dh, dw, 1, y, dt == NM_F32 ? NM_BF16 : NM_F32, nullptr) ==
+    CHECK(nm_conv2d(x, dt, b, h, w, cin, wp, bias, sh, sw, ph, pw, dh, dw, 1, y, ydt == NM_F32 ? NM_BF16 : NM_F32, nullptr) ==
           NM_ERR_UNSUPPORTED);
-    CHECK(nm_conv2d(x, dt, 1 << 20, 4096, 4096, cin, wp, bias, sh, sw, ph, pw, dh, dw, 1, y, dt, nullptr) == NM_ERR_SHAPE);
+    CHECK(nm_conv2d(x, dt, 1 << 20, 4096, 4096, cin, wp, bias, sh, sw, ph, pw, dh, dw, 1, y, ydt, nullptr) == NM_ERR_SHAPE);
     CHECK(hipFree(x) == hipSuccess && hipFree(y) == hipSuccess && hipFree(r) == hipSuccess && hipFree(bias) == hipSuccess);
     CHECK(nm_packed_free(wp) == NM_OK);
 }
@@ -367,11 +378,25 @@ int main(int argc, char** argv)
     conv_case(1, 6, 10, 64, 64, 3, 3, 32, 64, 32, NM_F32, 1, 2, 2, 1, 2, 1);   // one group per tap
     conv_case(1, 5, 5, 128, 16, 1, 1, 4, 8, 16, NM_BF16, 1, 1, 0, 0, 1, 1);    // dense instruction only
     conv_case(1, 1, 1, 8, 5, 1, 1, 1, 2, 5, NM_F32, 1, 1, 0, 0, 1, 1);
+    conv_case(2, 7, 6, 128, 40, 3, 3, 2, 4, 16, NM_F8E4M3, 2, 1, 1, 1, 1, 1);    // fp8 in, bf16 out
+    {   // E4M3 weights that the fp8 kernel cannot take, and fp8 tensors on weights of another type
+        std::vector<float> wt(16 * 48, 0.25f);
+        nm_packed_t* h8 = nullptr;
+        CHECK(nm_prune(wt.data(), 16, 1, 1, 48, 2, 4, 16, NM_F8E4M3, &h8) == NM_ERR_UNSUPPORTED && !h8);
+        CHECK(nm_prune(wt.data(), 12, 1, 1, 64, 2, 4, 16, NM_F8E4M3, &h8) == NM_ERR_UNSUPPORTED && !h8);
+        std::vector<float> w64(16 * 64, 0.25f);
+        CHECK(nm_prune(w64.data(), 16, 1, 1, 64, 2, 4, 16, NM_F32, &h8) == NM_OK);
+        void* xb = dev_alloc(64), *yb = dev_alloc(64);
+        CHECK(nm_conv2d(xb, NM_F8E4M3, 1, 1, 1, 64, h8, nullptr, 1, 1, 0, 0, 1, 1, 0, yb, NM_BF16, nullptr) == NM_ERR_UNSUPPORTED);
+        float sc = 0.f;
+        CHECK(nm_packed_scale(h8, &sc) == NM_OK && sc == 1.f && nm_packed_scale(nullptr, &sc) == NM_ERR_ARG);
+        CHECK(hipFree(xb) == hipSuccess && hipFree(yb) == hipSuccess && nm_packed_free(h8) == NM_OK);
+    }
     split_limits();
     // nothing leaked on the "device": what is left is the K-split workspace and the static scratch
     CHECK(g_allocs.size() <= 2);
     const int n_entries = nm_cache_size();
-    CHECK(n_entries == 7);
+    CHECK(n_entries == 8);
 
     // ---- cache file round trip and hostile files
     const std::string path = tmp + "/nm_cache_san.txt";
