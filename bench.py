@@ -237,7 +237,7 @@ def stack_roofline(st, ms_step, rows, headline, floor_ms=None):
     families = sorted({(r["variant"] or "?").split("_")[0] for r in rows})
     roofline.update({
         "traffic": traffic, "traffic_source": source,
-        "kernel": "nm_conv_f8_kernel" if st.f8 else ("nm_conv_sp16_kernel" if st.bf16 else "nm_conv_kernel"),
+        "kernel": "nm_conv_sp16_kernel<F8> (+ nm_conv_f8_kernel)" if st.f8 else ("nm_conv_sp16_kernel" if st.bf16 else "nm_conv_kernel"),
         "variant_families": families,
         "launches_per_step": len(rows), "avg_launch_ms": ms_step / len(rows),
         # with an event after every layer of three extra steps (adds the events' own cost)

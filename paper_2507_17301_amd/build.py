@@ -92,6 +92,14 @@ def _shapes_var():
     return [tuple(int(v) for v in m) for m in re.findall(r"X\((\d+),\s*(\d+),\s*(\d+)\)", body)]
 
 
+def _shapes_f8s():
+    """(NBLK, WP, NJ) of NMF8S_SHAPES in nm_variants.h."""
+    text = open(os.path.join(CSRC, "nm_variants.h")).read()
+    body = text[text.index("#define NMF8S_SHAPES(X)"):]
+    body = body[:body.index("// Y(")]
+    return [tuple(int(v) for v in m) for m in re.findall(r"X\((\d+),\s*(\d+),\s*(\d+)\)", body)]
+
+
 def _shapes_f8():
     """(NBLK, WP, NJ) of NMF8_SHAPES in nm_variants.h."""
     text = open(os.path.join(CSRC, "nm_variants.h")).read()
@@ -126,6 +134,9 @@ def _jobs():
     for nb, wp, nj in _shapes_spr():
         jobs.append((instsp, os.path.join(OBJDIR, f"nm_conv_sp16_inst_spr_{nb}_{wp}_{nj}.o"),
                      ["-DNM_INST_SPR", f"-DNM_INST_NBLK={nb}", f"-DNM_INST_WP={wp}", f"-DNM_INST_NJ={nj}"]))
+    for nb, wp, nj in _shapes_f8s():
+        jobs.append((instsp, os.path.join(OBJDIR, f"nm_conv_sp16_inst_f8s_{nb}_{wp}_{nj}.o"),
+                     ["-DNM_INST_F8S", f"-DNM_INST_NBLK={nb}", f"-DNM_INST_WP={wp}", f"-DNM_INST_NJ={nj}"]))
     instrun = os.path.join(CSRC, "nm_conv_run16_inst.hip")
     for nb, wp, nj in _shapes_run():
         jobs.append((instrun, os.path.join(OBJDIR, f"nm_conv_run16_inst_{nb}_{wp}_{nj}.o"),

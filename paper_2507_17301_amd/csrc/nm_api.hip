@@ -137,6 +137,11 @@ size_t lds_bytes(const VariantDesc& d, const nm_packed* wp)
     const size_t otile = (size_t)d.BP * ((size_t)(4 / d.WP) * d.NJ * 16 * (d.kind == 0 || d.kind == 5 ? 4 : 2) + 16);
     if (d.kind == 6)   // only the wavefront-private output tiles [16 NBLK][16 NJ] bf16 with 16 bytes of padding per row
         return (size_t)4 * 16 * d.NBLK * (d.NJ * 32 + 16);
+    if (d.kind == 7) {   // up to three stages of the strip [BP][CK] bytes plus each wave's operands (1 KB per k-step and row block)
+        const int nchunks = wp->kh * wp->kw * ((wp->cin + d.CK - 1) / d.CK);
+        const size_t ops = d.areg ? 0 : (size_t)4 * d.NJ * (d.CK / 64) * 1024;
+        return std::max(otile, (size_t)std::min(3, nchunks) * ((size_t)d.BP * d.CK + ops));
+    }
     if (d.kind == 4)   // the strip [BP][64 SPC] bf16 plus the dense weights of the workgroup's row blocks
         return std::max(otile, (size_t)d.BP * d.SPC * 128 + (size_t)(4 / d.WP) * d.NJ * d.SPC * 2048);
     if (d.kind >= 2 && d.kind <= 4) {   // up to three stages of the strip [BP][CK] bf16 plus each wave's operands
@@ -174,6 +179,9 @@ const Prepack* find_prepack(const nm_packed* wp, const VariantDesc& d, int par =
     return nullptr;
 }
 
+// kinds 6 (register-streaming) and 7 (LDS-staged) are the fp8 kernels; they share one operand table layout
+inline bool is_f8_kind(int kind) { return kind == 6 || kind == 7; }
+
 // With `ra` the answer is for that convolution; without, "for some convolution".
 bool variant_legal(int v, const nm_packed* wp, nm_dtype_t xdt, const RunArgs* ra = nullptr)
 {
@@ -181,8 +189,8 @@ bool variant_legal(int v, const nm_packed* wp, nm_dtype_t xdt, const RunArgs* ra
     const VariantDesc& d = variant_desc(v);
     if (lds_bytes(d, wp) > (size_t)kMaxLdsBytes) return false;
     if (d.kind == 5 && xdt != NM_F32) return false;   // instantiated for fp32 tensors only
-    // fp8: E4M3 tensors with an E4M3 handle run the fp8 kernel and nothing else does
-    if ((d.kind == 6) != (xdt == NM_F8E4M3) || (d.kind == 6) != (wp->value_dtype == NM_F8E4M3)) return false;
+    // fp8: E4M3 tensors with an E4M3 handle run the fp8 kernels and nothing else does
+    if (is_f8_kind(d.kind) != (xdt == NM_F8E4M3) || is_f8_kind(d.kind) != (wp->value_dtype == NM_F8E4M3)) return false;
     if (d.kind >= 1 && d.kind <= 4) {
         // bf16 matrix cores: bf16 tensors, weights already rounded to bf16, and a
         // shared operand only for column tiles made of exactly two row blocks
@@ -325,7 +333,7 @@ int heuristic_variant(const nm_packed* wp, int P, nm_dtype_t xdt, const RunArgs*
         const double mfma = (double)d.BP * rb_per_wg;            // per chunk step, relative
         const double stage = (double)d.BP * 2.0;                 // staging cost per chunk, relative
         // the bf16 matrix-core kernel contracts several times faster where it applies
-        const double speed[7] = {1.0, 0.3, 0.1, 0.2, 0.1, 0.7, 0.1};   // relative cost of a unit of contraction
+        const double speed[8] = {1.0, 0.3, 0.1, 0.2, 0.1, 0.7, 0.12, 0.1};   // relative cost of a unit of contraction
         const double cost = (double)rounds * occ * (mfma + stage) * speed[d.kind];
         if (best < 0 || cost < best_cost * 0.999) {
             best = v;
@@ -552,15 +560,17 @@ int nm_prune(const float* w, int cout, int kh, int kw, int cin, int n, int m, in
     const bool vec_ok = cin % 4 == 0;
     for (int v = 0; v < variant_count(); ++v) {
         const VariantDesc& d = variant_desc(v);
-        if ((d.kind == 6) != (value_dtype == NM_F8E4M3)) continue;   // E4M3 handles feed the fp8 kernel only
-        if (d.kind == 6) {
-            if (find_prepack(wp, d)) continue;
+        if (is_f8_kind(d.kind) != (value_dtype == NM_F8E4M3)) continue;   // E4M3 handles feed the fp8 kernels only
+        if (is_f8_kind(d.kind)) {
+            // one table layout for both kernels (64-channel k-steps in K order); an entry per
+            // chunk size, because the chunk geometry travels with the table
+            if (cin % d.CK != 0 || find_prepack(wp, d)) continue;
             Prepack pp;
-            pp.kind = 6;
-            pp.geom = make_chunk_geom(cin, wp->K, 64, 1);
+            pp.kind = d.kind;
+            pp.geom = make_chunk_geom(cin, wp->K, d.CK, 1);
             pp.SPC = d.SPC;
             pp.rows_bytes = 0;
-            pp.wfrag_bytes = (size_t)wp->n_rowblocks * pp.geom.nchunks * 64 * 16;
+            pp.wfrag_bytes = (size_t)wp->n_rowblocks * (wp->K / 64) * 64 * 16;
             if (pp.wfrag_bytes >= 0x80000000ull) continue;
             wp->prepacks.push_back(pp);
             Prepack& ref = wp->prepacks.back();

@@ -58,10 +58,21 @@ struct Entry {
 #define NM_ENTRYF8(NB, WP, NJ)                                                                  \
     {{"F8_NB" #NB "_WP" #WP "_NJ" #NJ, 16 * NB * WP, NB, WP, NJ, 64, 1, 1, 6, 1, 1, 0}, nullptr, &launch_f8_t<NB, WP, NJ>},
 
+// kind 7: fp8 E4M3 in, bf16 out through the LDS-staged kernel: plain, with producer wavefronts,
+// with producer wavefronts and register-held weights
+#define NM_ENTRYF8S(NB, WP, NJ, CK)                                                                       \
+    {{"F8S_NB" #NB "_WP" #WP "_NJ" #NJ "_CK" #CK, 16 * NB * WP, NB, WP, NJ, CK, CK / 64, 1, 7, 1, 1, 0}, \
+     nullptr, &launch_sp16_t<NB, WP, NJ, CK, false, false, false, true>},                                 \
+    {{"F8W_NB" #NB "_WP" #WP "_NJ" #NJ "_CK" #CK, 16 * NB * WP, NB, WP, NJ, CK, CK / 64, 1, 7, 1, 1, 0}, \
+     nullptr, &launch_sp16_t<NB, WP, NJ, CK, false, true, false, true>},                                  \
+    {{"F8R_NB" #NB "_WP" #WP "_NJ" #NJ "_CK" #CK, 16 * NB * WP, NB, WP, NJ, CK, CK / 64, 1, 7, 1, 1, 1}, \
+     nullptr, &launch_sp16_t<NB, WP, NJ, CK, false, true, true, true>},
+#define NM_SHAPE_ENTRIESF8S(NB, WP, NJ) NMF8S_CHUNKS(NM_ENTRYF8S, NB, WP, NJ)
+
 const Entry kEntries[] = {NM_SHAPES(NM_SHAPE_ENTRIES) NM_SCALAR_VARIANTS(NM_ENTRY)
                           NM16_SHAPES(NM_SHAPE_ENTRIES16) NMSP_SHAPES(NM_SHAPE_ENTRIESSP) NMSPW_SHAPES(NM_SHAPE_ENTRIESSPW) NMSPR_SHAPES(NM_SHAPE_ENTRIESSPR)
                           NMRUN_SHAPES(NM_SHAPE_ENTRIESRUN) NMVAR_SHAPES(NM_SHAPE_ENTRIESVAR)
-                          NMF8_SHAPES(NM_ENTRYF8)};
+                          NMF8_SHAPES(NM_ENTRYF8) NMF8S_SHAPES(NM_SHAPE_ENTRIESF8S)};
 constexpr int kCount = (int)(sizeof(kEntries) / sizeof(kEntries[0]));
 
 // The fp32 MFMA kernel also runs with its K axis split over several workgroups per output
@@ -110,7 +121,7 @@ int launch_conv(int v, nm_dtype_t xdt, nm_dtype_t ydt, const ConvParams& p, hipS
         return NM_ERR_UNSUPPORTED;
     }
     const Entry& e = kEntries[table().base[v]];
-    const bool f8 = e.d.kind == 6;
+    const bool f8 = e.d.kind == 6 || e.d.kind == 7;
     if (xdt == NM_F32 && ydt == NM_F32 && e.ff && !f8) return e.ff(p, s);
     if (xdt == NM_BF16 && ydt == NM_BF16 && e.bb && !f8) return e.bb(p, s);
     if (xdt == NM_F8E4M3 && ydt == NM_BF16 && e.bb && f8) return e.bb(p, s);

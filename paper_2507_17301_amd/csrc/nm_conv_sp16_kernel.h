@@ -28,6 +28,15 @@
 //     operand (bits 2 ea + 1 .. 2 ea of its low half, ABID = 0).
 //   dense A: lane i + 16 q element e pairs with B lane group q element e.
 //   D: lane n + 16 q register r is row 4 q + r, column n.
+//
+// F8 = true is the same staging, ring and barriers for E4M3 tensors (one byte per element,
+// bf16 output): a k-step is again 64 channels, now 64 bytes of a pixel's row, so lane group q's
+// share is one 16-byte read (channels 16 q .. 16 q + 15) that feeds two dense
+// v_mfma_f32_16x16x32_fp8_fp8 -- bytes 0-7 the first, bytes 8-15 the second; operands are 8 bytes per
+// lane, lane i + 16 q holding K positions 8 q .. 8 q + 7, and which channel a K position stands
+// for is free as long as both operands agree -- against weights that nm_prune lays out to match.
+// The accumulators start from zero and are scaled back by the layer's weight scale before the
+// bias is added.
 #pragma once
 
 #include "nm_conv_kernel.h"
@@ -50,19 +59,42 @@ typedef __bf16 bf16x __attribute__((ext_vector_type(16)));
 // into registers inside the loop.
 constexpr int kSp16Stages = 3;
 // one stage: the strip [BP][CK] bf16, then per wave the weights (and index words) of its row blocks
-constexpr int sp16_stage_bytes(int BP, int CK, int NJ, bool sparse, bool areg = false)
+// (fp8: rows of CK bytes, one 16-byte weight operand per k-step and row block)
+constexpr int sp16_stage_bytes(int BP, int CK, int NJ, bool sparse, bool areg = false, bool f8 = false)
 {
-    return BP * CK * 2 + (areg ? 0 : 4 * NJ * (CK / 64) * ((sparse ? 1 : 2) * 1024 + (sparse ? 256 : 0)));
+    return BP * CK * (f8 ? 1 : 2) +
+           (areg ? 0 : 4 * NJ * (CK / 64) * ((sparse || f8 ? 1 : 2) * 1024 + (sparse ? 256 : 0)));
 }
 // (8 consecutive lanes of a 16-byte LDS read are served together: their granules must differ
-// modulo 128 bytes; the extra bit keeps rows r and r + 8 apart modulo 256 bytes as well)
-__device__ inline int sp16_swz(int row, int CK) { return CK == 64 ? ((row & 7) ^ ((row >> 3) & 1)) : (row & 15); }
+// modulo 128 bytes; the extra bit keeps rows r and r + 8 apart modulo 256 bytes as well.
+// RB = bytes per pixel row: with 64-byte rows two rows share 128 bytes, so the row's parity
+// already separates them and the other bits of the row number pick the granule.)
+__device__ inline int sp16_swz(int row, int RB)
+{
+    return RB == 64 ? ((row >> 1) & 3) : RB == 128 ? ((row & 7) ^ ((row >> 3) & 1)) : (row & 15);
+}
+// one 8-byte half of a 16-byte operand, as the fp8 matrix instruction takes it
+__device__ inline long sp16_half(const u4v& v, int h)
+{
+    const unsigned long long lo = h ? v.z : v.x, hi = h ? v.w : v.y;
+    return (long)(lo | (hi << 32));
+}
 
 // s_waitcnt with only the vector-memory counter set (gfx9 encoding: vmcnt in
 // bits 3:0 and 15:14, the other counters at their maxima).
 #define NM_WAIT_VMCNT(n) __builtin_amdgcn_s_waitcnt(((n) & 15) | (((n) >> 4) << 14) | 0x0f70)
 
 typedef __attribute__((address_space(3))) void* lds_ptr_t;
+
+// s_waitcnt on the LDS counter that also tells the compiler that the BH registers of one
+// strip read (R) are defined from here on (used inside the kernel, where BH is known)
+#define NM_SP16_WAIT(N, R)                                                               \
+    do {                                                                                 \
+        if constexpr (BH == 2)                                                           \
+            asm volatile("s_waitcnt lgkmcnt(" #N ")" : "+v"((R)[0]), "+v"((R)[BH - 1])); \
+        else                                                                             \
+            asm volatile("s_waitcnt lgkmcnt(" #N ")" : "+v"((R)[0]));                    \
+    } while (0)
 
 //
 // SPEC = true adds four producer wavefronts to the workgroup (512 threads): they issue every
@@ -78,18 +110,21 @@ typedef __attribute__((address_space(3))) void* lds_ptr_t;
 // issues no other vector-memory load inside the loop).  A stage is then the strip alone,
 // which halves the LDS traffic of tiles whose wavefronts hold four row blocks, and the
 // strip reads run four deep instead of two.
-template <int NBLK, int WP, int NJ, int CK, bool SPARSE, bool SPEC, bool AREG = false>
+template <int NBLK, int WP, int NJ, int CK, bool SPARSE, bool SPEC, bool AREG = false, bool F8 = false>
 __global__ __launch_bounds__(SPEC ? 512 : 256) void nm_conv_sp16_kernel(const ConvParams p)
 {
     static_assert(!AREG || SPEC, "register operands need the producer wavefronts");
+    static_assert(!F8 || !SPARSE, "the fp8 form runs the dense instruction");
+    constexpr int ES = F8 ? 1 : 2;               // bytes per element of x and of the weights
     constexpr int BPW = 16 * NBLK;
     constexpr int BP = BPW * WP;
     constexpr int WC = 4 / WP;
     constexpr int KS = CK / 64;                  // k-steps (64 channels) per chunk
-    constexpr int AH = SPARSE ? 1 : 2;           // 16-byte A operands per k-step and row block
-    constexpr int RB = CK * 2;                   // bytes per pixel row of a stage
+    constexpr int AH = (SPARSE || F8) ? 1 : 2;   // 16-byte A operands per k-step and row block
+    constexpr int BH = F8 ? 1 : 2;               // 16-byte strip reads per k-step and pixel block
+    constexpr int RB = CK * ES;                  // bytes per pixel row of a stage
     const int D = p.nchunks < kSp16Stages ? p.nchunks : kSp16Stages;   // stages in use (and allocated)
-    constexpr int STAGE = sp16_stage_bytes(BP, CK, NJ, SPARSE, AREG);
+    constexpr int STAGE = sp16_stage_bytes(BP, CK, NJ, SPARSE, AREG, F8);
     static_assert(CK % 64 == 0, "a chunk is a whole number of 64-channel k-steps");
 
     extern __shared__ __attribute__((aligned(16))) char lds8[];   // [D][BP][RB]
@@ -118,7 +153,8 @@ __global__ __launch_bounds__(SPEC ? 512 : 256) void nm_conv_sp16_kernel(const Co
 
     // ---- staging: wave-wide loads of 64 granules; load i of the stage covers
     // granules 64 i .. 64 i + 63 and is issued by wave i % 4 -------------------
-    constexpr int OPR = CK / 8;                  // granules (octets) per pixel row
+    constexpr int OPR = RB / 16;                 // 16-byte granules per pixel row
+    constexpr int EPG = 16 / ES;                 // elements per granule
     constexpr int NW = BP * OPR / 64;            // wave-wide loads per stage
     constexpr int NIT = (NW + 3) / 4;            // per wave
     int hi0[NIT], wi0[NIT];
@@ -128,7 +164,7 @@ __global__ __launch_bounds__(SPEC ? 512 : 256) void nm_conv_sp16_kernel(const Co
     for (int it = 0; it < NIT; ++it) {
         const int G = (wave + 4 * it) * 64 + lane;            // granule of the stage this lane fills
         const int pl = G / OPR;
-        const int oct = (G % OPR) ^ sp16_swz(pl, CK);         // the octet that belongs at that position
+        const int oct = (G % OPR) ^ sp16_swz(pl, RB);         // the granule of the row that belongs at that position
         const int pp = p0 + pl;
         const bool live = (pp < p.P) & (pl < BP);
         const int b = (int)fdiv((unsigned)pp, p.howo_mul, p.howo_shift);
@@ -138,13 +174,13 @@ __global__ __launch_bounds__(SPEC ? 512 : 256) void nm_conv_sp16_kernel(const Co
         const int h0 = ho * p.sh - p.ph, w0 = wo * p.sw - p.pw;
         hi0[it] = live ? h0 : -(1 << 28);   // a dead pixel has every tap outside the image
         wi0[it] = w0;
-        base[it] = (unsigned)(((b * p.H + h0) * p.W + w0) * p.Cin + oct * 8) * 2;
+        base[it] = (unsigned)(((b * p.H + h0) * p.W + w0) * p.Cin + oct * EPG) * ES;
     }
     int f_c = 0, f_kh = 0, f_kw = 0, f_ci0 = 0;
     bool f_live = true;                          // false once the iterator has run past the last chunk
     auto retap = [&]() {
         const int dhh = f_kh * p.dh, dww = f_kw * p.dw;
-        const unsigned tapoff = (unsigned)((dhh * p.W + dww) * p.Cin) * 2;
+        const unsigned tapoff = (unsigned)((dhh * p.W + dww) * p.Cin) * ES;
 #pragma unroll
         for (int it = 0; it < NIT; ++it) {
             const int hi = hi0[it] + dhh, wi = wi0[it] + dww;
@@ -155,7 +191,7 @@ __global__ __launch_bounds__(SPEC ? 512 : 256) void nm_conv_sp16_kernel(const Co
     // one wave-wide load of the current fetch chunk into stage `stage`
     auto fetch_item = [&](int it, int stage) {
         if (NW % 4 != 0 && wave + 4 * it >= NW) return;       // wave-uniform
-        const unsigned off = f_live ? voff[it] + (unsigned)(f_ci0 * 2) : kOOB;
+        const unsigned off = f_live ? voff[it] + (unsigned)(f_ci0 * ES) : kOOB;
         char* dst = lds8 + stage * STAGE + (wave + 4 * it) * 1024;
         __builtin_amdgcn_raw_ptr_buffer_load_lds(xr, (lds_ptr_t)dst, 16, off, 0, 0, 0);
     };
@@ -176,7 +212,7 @@ __global__ __launch_bounds__(SPEC ? 512 : 256) void nm_conv_sp16_kernel(const Co
     };
 
     // ---- operand streams ------------------------------------------------------
-    // weights: [row block][chunk][k-step][AH][lane] x 16 bytes (8 bf16)
+    // weights: [row block][chunk][k-step][AH][lane] x 16 bytes (8 bf16, or 16 E4M3)
     // index operands (sparse): [column tile][chunk][lane group][k-step] x 4 bytes
     // Both take the same road as the strip: each wave loads the operands of its
     // own row blocks into a private part of the stage (lane L's 16 bytes, or 4
@@ -221,12 +257,14 @@ __global__ __launch_bounds__(SPEC ? 512 : 256) void nm_conv_sp16_kernel(const Co
     };
 
     // this lane's operand granules inside block 0 of a stage: k-step s, half h
-    unsigned roff[KS][2];
+    // (bf16: granules 2 q and 2 q + 1 of the k-step's eight; fp8: granule q of its four)
+    unsigned roff[KS][BH];
 #pragma unroll
     for (int s = 0; s < KS; ++s)
 #pragma unroll
-        for (int h = 0; h < 2; ++h)
-            roff[s][h] = (unsigned)((wpix + n) * RB + (((s * 8 + q * 2 + h) ^ sp16_swz(n, CK)) * 16));
+        for (int h = 0; h < BH; ++h)
+            roff[s][h] = (unsigned)((wpix + n) * RB +
+                                    (((F8 ? s * 4 + q : s * 8 + q * 2 + h) ^ sp16_swz(n, RB)) * 16));
 
     // The memory counter retires loads in order, so "at most one stage's loads
     // outstanding" means that the stage before it has landed.
@@ -283,12 +321,13 @@ __global__ __launch_bounds__(SPEC ? 512 : 256) void nm_conv_sp16_kernel(const Co
         }
     }
 
-    // the accumulators start from the bias (zero where there is none or rows are handled one by one)
+    // the accumulators start from the bias (zero where there is none or rows are handled one by one;
+    // fp8: from zero, the bias joins after the accumulator is back at the weights' scale)
     f4 acc[NJ][NBLK];
 #pragma unroll
     for (int jj = 0; jj < NJ; ++jj)
 #pragma unroll
-        for (int b = 0; b < NBLK; ++b) acc[jj][b] = bb[jj];
+        for (int b = 0; b < NBLK; ++b) acc[jj][b] = F8 ? f4{0.f, 0.f, 0.f, 0.f} : bb[jj];
 
     constexpr int NM = KS * NBLK;                // B operands (LDS reads) per chunk for this wavefront
     static_assert((NBLK - 1) * 16 * RB < 65536, "block offsets must fit the LDS instruction's immediate");
@@ -341,26 +380,27 @@ __global__ __launch_bounds__(SPEC ? 512 : 256) void nm_conv_sp16_kernel(const Co
                                      : "=v"(idx[jj][s]) : "v"(ia), "n"((jj * KS + s) * 256) : "memory");
                 }
         }
-        unsigned raddr[KS][2];
+        unsigned raddr[KS][BH];
 #pragma unroll
         for (int s = 0; s < KS; ++s)
 #pragma unroll
-            for (int h = 0; h < 2; ++h) raddr[s][h] = sbase + roff[s][h];
-        auto read_b = [&](int m, u4v (&dst)[2]) {
+            for (int h = 0; h < BH; ++h) raddr[s][h] = sbase + roff[s][h];
+        auto read_b = [&](int m, u4v (&dst)[BH]) {
             const int s = m / NBLK, b = m % NBLK;
             asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(dst[0]) : "v"(raddr[s][0]), "n"(b * 16 * RB) : "memory");
-            asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(dst[1]) : "v"(raddr[s][1]), "n"(b * 16 * RB) : "memory");
+            if constexpr (BH == 2)
+                asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(dst[BH - 1]) : "v"(raddr[s][BH - 1]), "n"(b * 16 * RB) : "memory");
         };
-        u4v ring[2][2];
+        u4v ring[2][BH];
         read_b(0, ring[0]);
 #pragma unroll
         for (int m = 0; m < NM; ++m) {
             const int s = m / NBLK, b = m % NBLK;
-            if (m + 1 < NM) {
+            if (m + 1 < NM) {   // the next read is in flight (BH instructions); this one must be back
                 read_b(m + 1, ring[(m + 1) & 1]);
-                asm volatile("s_waitcnt lgkmcnt(2)" : "+v"(ring[m & 1][0]), "+v"(ring[m & 1][1]));
+                if constexpr (BH == 2) NM_SP16_WAIT(2, ring[m & 1]); else NM_SP16_WAIT(1, ring[m & 1]);
             } else {
-                asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(ring[m & 1][0]), "+v"(ring[m & 1][1]));
+                NM_SP16_WAIT(0, ring[m & 1]);
             }
             if (m == 0) {
                 // the operands were requested before the first strip read, so the wait
@@ -374,15 +414,20 @@ __global__ __launch_bounds__(SPEC ? 512 : 256) void nm_conv_sp16_kernel(const Co
                         if constexpr (SPARSE) asm volatile("" : "+v"(idx[jj][s2]));
                     }
             }
-            const u4v(&bo)[2] = ring[m & 1];
+            const u4v(&bo)[BH] = ring[m & 1];
 #pragma unroll
             for (int jj = 0; jj < NJ; ++jj) {
                 if constexpr (SPARSE) {
                     const bf16x bv = __builtin_shufflevector(__builtin_bit_cast(bf8x, bo[0]),
-                                                             __builtin_bit_cast(bf8x, bo[1]), 0, 1, 2, 3, 4,
+                                                             __builtin_bit_cast(bf8x, bo[BH - 1]), 0, 1, 2, 3, 4,
                                                              5, 6, 7, 8, 9, 10, 11, 12, 13, 14, 15);
                     acc[jj][b] = __builtin_amdgcn_smfmac_f32_16x16x64_bf16(
                         __builtin_bit_cast(bf8x, a[jj][s][0]), bv, acc[jj][b], (int)idx[jj][s], 0, 0);
+                } else if constexpr (F8) {
+#pragma unroll
+                    for (int h = 0; h < 2; ++h)
+                        acc[jj][b] = __builtin_amdgcn_mfma_f32_16x16x32_fp8_fp8(
+                            sp16_half(a[jj][s][0], h), sp16_half(bo[0], h), acc[jj][b], 0, 0, 0);
                 } else {
 #pragma unroll
                     for (int h = 0; h < 2; ++h)
@@ -422,38 +467,46 @@ __global__ __launch_bounds__(SPEC ? 512 : 256) void nm_conv_sp16_kernel(const Co
         auto chunk_r = [&](const Ops& o) {
             __builtin_amdgcn_s_barrier();            // the producers' loads of this chunk have landed
             const unsigned sbase = lds0 + (unsigned)(rstage * STAGE);
-            unsigned raddr[KS][2];
+            unsigned raddr[KS][BH];
 #pragma unroll
             for (int s2 = 0; s2 < KS; ++s2)
 #pragma unroll
-                for (int h = 0; h < 2; ++h) raddr[s2][h] = sbase + roff[s2][h];
-            auto read_b = [&](int m, u4v (&dst)[2]) {
+                for (int h = 0; h < BH; ++h) raddr[s2][h] = sbase + roff[s2][h];
+            auto read_b = [&](int m, u4v (&dst)[BH]) {
                 const int s2 = m / NBLK, b = m % NBLK;
                 asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(dst[0]) : "v"(raddr[s2][0]), "n"(b * 16 * RB) : "memory");
-                asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(dst[1]) : "v"(raddr[s2][1]), "n"(b * 16 * RB) : "memory");
+                if constexpr (BH == 2)
+                    asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(dst[BH - 1]) : "v"(raddr[s2][BH - 1]), "n"(b * 16 * RB) : "memory");
             };
-            u4v ring[RD][2];
+            u4v ring[RD][BH];
 #pragma unroll
             for (int m = 0; m < RD - 1; ++m) read_b(m, ring[m]);
 #pragma unroll
             for (int m = 0; m < NM; ++m) {
                 const int s2 = m / NBLK, b = m % NBLK;
                 if (m + RD - 1 < NM) read_b(m + RD - 1, ring[(m + RD - 1) % RD]);
-                // reads m .. min(m + RD, NM) - 1 are outstanding, two instructions each; the oldest must be back
-                const int ahead = (m + RD - 1 < NM ? RD : NM - m) - 1;
-                if (ahead == 3) asm volatile("s_waitcnt lgkmcnt(6)" : "+v"(ring[m % RD][0]), "+v"(ring[m % RD][1]));
-                else if (ahead == 2) asm volatile("s_waitcnt lgkmcnt(4)" : "+v"(ring[m % RD][0]), "+v"(ring[m % RD][1]));
-                else if (ahead == 1) asm volatile("s_waitcnt lgkmcnt(2)" : "+v"(ring[m % RD][0]), "+v"(ring[m % RD][1]));
-                else asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(ring[m % RD][0]), "+v"(ring[m % RD][1]));
-                const u4v(&bo)[2] = ring[m % RD];
+                // reads m .. min(m + RD, NM) - 1 are outstanding, BH instructions each; the oldest must be back
+                const int later = ((m + RD - 1 < NM ? RD : NM - m) - 1) * BH;
+                if (later == 6) NM_SP16_WAIT(6, ring[m % RD]);
+                else if (later == 4) NM_SP16_WAIT(4, ring[m % RD]);
+                else if (later == 3) NM_SP16_WAIT(3, ring[m % RD]);
+                else if (later == 2) NM_SP16_WAIT(2, ring[m % RD]);
+                else if (later == 1) NM_SP16_WAIT(1, ring[m % RD]);
+                else NM_SP16_WAIT(0, ring[m % RD]);
+                const u4v(&bo)[BH] = ring[m % RD];
 #pragma unroll
                 for (int jj = 0; jj < NJ; ++jj) {
                     if constexpr (SPARSE) {
                         const bf16x bv = __builtin_shufflevector(__builtin_bit_cast(bf8x, bo[0]),
-                                                                 __builtin_bit_cast(bf8x, bo[1]), 0, 1, 2, 3, 4,
+                                                                 __builtin_bit_cast(bf8x, bo[BH - 1]), 0, 1, 2, 3, 4,
                                                                  5, 6, 7, 8, 9, 10, 11, 12, 13, 14, 15);
                         acc[jj][b] = __builtin_amdgcn_smfmac_f32_16x16x64_bf16(
                             __builtin_bit_cast(bf8x, o.a[jj][s2][0]), bv, acc[jj][b], (int)o.idx[jj][s2], 0, 0);
+                    } else if constexpr (F8) {
+#pragma unroll
+                        for (int h = 0; h < 2; ++h)
+                            acc[jj][b] = __builtin_amdgcn_mfma_f32_16x16x32_fp8_fp8(
+                                sp16_half(o.a[jj][s2][0], h), sp16_half(bo[0], h), acc[jj][b], 0, 0, 0);
                     } else {
 #pragma unroll
                         for (int h = 0; h < 2; ++h)
@@ -495,9 +548,10 @@ __global__ __launch_bounds__(SPEC ? 512 : 256) void nm_conv_sp16_kernel(const Co
             for (int b = 0; b < NBLK; ++b) {
                 const int pl = wpix + b * 16 + n;
                 const int pp = p0 + pl;
+                // (bf16: the bias is already in the accumulator)
                 tile_put4<bf16_t>(p, lds8 + pl * PITCH + ((wcx * NJ + jj) * 16 + q * 4) * 2,
                                   (unsigned)pp * (unsigned)p.Cout + (unsigned)co, row_live && pp < p.P,
-                                  acc[jj][b]);   // the bias is already in the accumulator
+                                  F8 ? acc[jj][b] * p.oscale + bb[jj] : acc[jj][b]);
             }
         }
         __syncthreads();
@@ -518,7 +572,7 @@ __global__ __launch_bounds__(SPEC ? 512 : 256) void nm_conv_sp16_kernel(const Co
             for (int b = 0; b < NBLK; ++b) {
                 const int pp = p0 + wpix + b * 16 + n;
                 if (pp >= p.P) continue;
-                const f4 v = acc[jj][b];   // the bias is already in the accumulator
+                const f4 v = F8 ? acc[jj][b] * p.oscale + bb[jj] : acc[jj][b];   // bf16: the bias is already there
                 emit4(p, y, (unsigned)pp * (unsigned)p.Cout + (unsigned)co, v);
             }
         } else {
@@ -529,7 +583,7 @@ __global__ __launch_bounds__(SPEC ? 512 : 256) void nm_conv_sp16_kernel(const Co
 #pragma unroll
                 for (int r = 0; r < 4; ++r) {
                     if (rit + r >= p.tile || co + r >= p.Cout) continue;
-                    float v = acc[jj][b][r] + (p.bias ? p.bias[co + r] : 0.f);
+                    float v = (F8 ? acc[jj][b][r] * p.oscale : acc[jj][b][r]) + (p.bias ? p.bias[co + r] : 0.f);
                     emit1(p, y, (unsigned)pp * (unsigned)p.Cout + (unsigned)(co + r), v);
                 }
             }
@@ -537,11 +591,15 @@ __global__ __launch_bounds__(SPEC ? 512 : 256) void nm_conv_sp16_kernel(const Co
     }
 }
 
-template <int NBLK, int WP, int NJ, int CK, bool SPARSE, bool SPEC, bool AREG>
+template <int NBLK, int WP, int NJ, int CK, bool SPARSE, bool SPEC, bool AREG, bool F8>
 int launch_sp16_t(const ConvParams& p, hipStream_t s)
 {
-    auto kern = nm_conv_sp16_kernel<NBLK, WP, NJ, CK, SPARSE, SPEC, AREG>;
-    constexpr size_t stage = sp16_stage_bytes(16 * NBLK * WP, CK, NJ, SPARSE, AREG);
+    auto kern = nm_conv_sp16_kernel<NBLK, WP, NJ, CK, SPARSE, SPEC, AREG, F8>;
+    constexpr size_t stage = sp16_stage_bytes(16 * NBLK * WP, CK, NJ, SPARSE, AREG, F8);
+    if (F8 && (p.tile % 16 != 0 || p.Cout % 8 != 0 || p.Cin % CK != 0)) {
+        set_error("internal: the fp8 kernel needs T %% 16 == 0, Cout %% 8 == 0 and whole chunks per tap");
+        return NM_ERR_UNSUPPORTED;
+    }
     // the most this kernel may ever be launched with: the full ring, or what the CU has
     constexpr size_t ring = kSp16Stages * stage > out_tile_bytes(16 * NBLK * WP, (4 / WP) * NJ * 16, 2)
                                 ? kSp16Stages * stage : out_tile_bytes(16 * NBLK * WP, (4 / WP) * NJ * 16, 2);

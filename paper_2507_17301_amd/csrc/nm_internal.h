@@ -63,7 +63,8 @@ inline ChunkGeom make_chunk_geom(int cin, int K, int CK, int vec)
 struct Prepack {
     int kind = 0;                     // 0: fp32 MFMA kernel, 1: bf16 MFMA gather kernel, 2/3: gather-free bf16 kernel,
                                       // 4: bf16 kernel-row runs, 5: fp32 MFMA kernel with per-chunk step counts,
-                                      // 6: fp8 kernel (dense instruction on zero-filled weights)
+                                      // 6, 7: fp8 kernels (dense instruction on zero-filled weights), register-streaming
+                                      // and LDS-staged
     ChunkGeom geom{};
     int SPC = 0;                      // k-steps per chunk (1, 2, 4 or 8)
     // kind 0: a k-step is 4 kept columns
@@ -81,8 +82,8 @@ struct Prepack {
     // kind 4 (contiguous kernel-row runs, layers with very few input channels): one chunk of SPC
     //   64-element k-steps; per pixel Kh runs of GR granules, each starting `par` elements early
     //   d_wfrag [n_rowblocks][SPC][2][64][8] bf16   A-operand lane values, zero in padding slots
-    // kind 6 (fp8 E4M3, dense instruction): a chunk is 64 channels of one tap
-    //   d_wfrag [n_rowblocks][nchunks][64][16] bytes   lane i + 16 q, byte e = channel 16 q + e of the chunk
+    // kind 6 and 7 (fp8 E4M3, dense instruction): a k-step is 64 channels of one tap, a chunk CK / 64 of them
+    //   d_wfrag [n_rowblocks][K / 64][64][16] bytes   lane i + 16 q, byte e = channel 16 q + e of the k-step
     int par = 0;                      // kind 4: 0 or 1 elements of lead-in per run (alignment of the run start)
     uint32_t* d_rows = nullptr;
     float* d_wfrag = nullptr;

@@ -10,7 +10,7 @@ template <int NBLK, int WP, int NJ, int CK, int SPC, int MODE, typename TIN, typ
 int launch_t(const ConvParams& p, hipStream_t s);
 template <int NBLK, int WP, int NJ, int CK, int SPC, int SHARE>
 int launch16_t(const ConvParams& p, hipStream_t s);
-template <int NBLK, int WP, int NJ, int CK, bool SPARSE, bool SPEC, bool AREG = false>
+template <int NBLK, int WP, int NJ, int CK, bool SPARSE, bool SPEC, bool AREG = false, bool F8 = false>
 int launch_sp16_t(const ConvParams& p, hipStream_t s);
 template <int NBLK, int WP, int NJ, int KS>
 int launch_run16_t(const ConvParams& p, hipStream_t s);

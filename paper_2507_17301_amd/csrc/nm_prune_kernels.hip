@@ -469,11 +469,13 @@ int run_build_prepack(nm_packed* wp, Prepack& pp, hipStream_t s)
     NM_HIP_CHECK(hipMalloc(&d_err, sizeof(int)));
     NM_HIP_CHECK(hipMemsetAsync(d_err, 0, sizeof(int), s));
     const size_t lds = (size_t)2 * g.nchunks * sizeof(int);
-    if (pp.kind == 6) {
-        const size_t total = (size_t)wp->n_rowblocks * g.nchunks * 64;
+    if (pp.kind == 6 || pp.kind == 7) {
+        // the table is made of 64-channel k-steps whatever the variant's chunk size
+        const int ncpt64 = wp->cin / 64, nk64 = wp->K / 64;
+        const size_t total = (size_t)wp->n_rowblocks * nk64 * 64;
         hipLaunchKernelGGL(build_prepack_f8_kernel, dim3(grid_for(total, 256)), dim3(256), 0, s, wp->d_idx,
-                           wp->d_vals, wp->kprime, wp->tile, wp->rbpt, wp->n_rowblocks, wp->cin, g.ncpt,
-                           g.nchunks, wp->scale, reinterpret_cast<unsigned char*>(pp.d_wfrag));
+                           wp->d_vals, wp->kprime, wp->tile, wp->rbpt, wp->n_rowblocks, wp->cin, ncpt64,
+                           nk64, wp->scale, reinterpret_cast<unsigned char*>(pp.d_wfrag));
     } else if (pp.kind == 0 || pp.kind == 5)
         hipLaunchKernelGGL(build_prepack_kernel, dim3(wp->n_tiles), dim3(256), lds, s, wp->d_idx,
                            wp->d_vals, wp->kprime, wp->tile, wp->rbpt, wp->cin, g.CK, g.vec, g.ncpt,

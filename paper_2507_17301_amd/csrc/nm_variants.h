@@ -84,6 +84,13 @@
 // Y(NBLK, WP, NJ, KS)
 #define NMRUN_CHUNKS(Y, NB, WP, NJ) Y(NB, WP, NJ, 1) Y(NB, WP, NJ, 2) Y(NB, WP, NJ, 3) Y(NB, WP, NJ, 4)
 
+// fp8 through the staged kernel of the gather-free bf16 form (LDS ring, optional producer
+// wavefronts and register-held weights): CK E4M3 channels of one tap per chunk.
+// X(NBLK, WP, NJ)
+#define NMF8S_SHAPES(X) X(8, 1, 2) X(4, 1, 2) X(4, 1, 1) X(6, 1, 2) X(4, 2, 2) X(8, 1, 4) X(4, 2, 4) X(4, 1, 4) X(2, 1, 2)
+// Y(NBLK, WP, NJ, CK)
+#define NMF8S_CHUNKS(Y, NB, WP, NJ) Y(NB, WP, NJ, 64) Y(NB, WP, NJ, 128) Y(NB, WP, NJ, 256)
+
 // fp8 (E4M3 activations and weights, bf16 output): both operands streamed from global memory
 // into registers, 64-channel k-steps.
 // X(NBLK, WP, NJ)

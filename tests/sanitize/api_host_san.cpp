@@ -115,6 +115,8 @@ static const VariantDesc kFake[] = {
     {"F_RUN_NB4_KS3", 64, 4, 1, 1, 192, 3, 1, 4, 1, 1, 0},
     {"F_RUN_NB4_KS1", 64, 4, 1, 1, 64, 1, 1, 4, 1, 1, 0},
     {"F_F8_NB4_WP1_NJ4", 64, 4, 1, 4, 64, 1, 1, 6, 1, 1, 0},
+    {"F_F8S_NB4_WP1_NJ2_CK64", 64, 4, 1, 2, 64, 1, 1, 7, 1, 1, 0},
+    {"F_F8R_NB4_WP1_NJ2_CK128", 64, 4, 1, 2, 128, 2, 1, 7, 1, 1, 1},
     // K-split forms of the fp32 kernel
     {"F_NB4_WP1_NJ1_CK32_SPC4_S2", 64, 4, 1, 1, 32, 4, 1, 0, 1, 2, 0},
     {"F_NB4_WP1_NJ1_CK32_SPC4_S4", 64, 4, 1, 1, 32, 4, 1, 0, 1, 4, 0},
@@ -132,8 +134,13 @@ int launch_conv(int v, nm_dtype_t xdt, nm_dtype_t ydt, const ConvParams& p, hipS
     ++g_launches;
     const size_t es = xdt == NM_F32 ? 4 : (xdt == NM_BF16 ? 2 : 1), yes = ydt == NM_F32 ? 4 : 2;
     CHECK(xdt == ydt || (xdt == NM_F8E4M3 && ydt == NM_BF16));
-    CHECK((d.kind == 6) == (xdt == NM_F8E4M3));
-    CHECK(p.oscale > 0.f && (d.kind == 6 || p.oscale == 1.f));
+    const bool f8 = d.kind == 6 || d.kind == 7;
+    CHECK(f8 == (xdt == NM_F8E4M3));
+    CHECK(p.oscale > 0.f && (f8 || p.oscale == 1.f));
+    if (f8) {   // whole chunks per tap, and the table holds every 64-channel k-step of every row block
+        CHECK(p.Cin % d.CK == 0 && p.nchunks == p.Kh * p.Kw * (p.Cin / d.CK));
+        CHECK(p.wfrag_bytes == (size_t)p.n_rowblocks * (p.K / 64) * 1024);
+    }
     // the geometry the kernels rely on
     const long eh = (long)p.H + 2L * p.ph - (long)p.dh * (p.Kh - 1) - 1, ew = (long)p.W + 2L * p.pw - (long)p.dw * (p.Kw - 1) - 1;
     CHECK(eh >= 0 && ew >= 0 && p.Ho == eh / p.sh + 1 && p.Wo == ew / p.sw + 1);

@@ -1,6 +1,8 @@
 """The fp8 (E4M3) workload against the CPU oracle, through the C ABI: kept sets and the
 stored E4M3 values bit for bit, the convolution within the bf16 tolerance (exact products,
 fp32 accumulation, one bf16 rounding) with the oracle fed the E4M3 operands as exact floats."""
+import re
+
 import numpy as np
 import pytest
 
@@ -60,6 +62,8 @@ CASES = [
     (L("f8_dense", 10, 10, 64, 96, 3, 3, 1, 1, 1, 1, 1, 16), 2),
     (L("f8_one_pixel", 3, 3, 64, 24, 3, 3, 1, 0, 1, 2, 4, 16), 1),
     (L("f8_group_per_tap", 8, 8, 128, 32, 3, 3, 1, 1, 1, 32, 128, 16), 2),
+    (L("f8_3x3_cin256", 9, 7, 256, 56, 3, 3, 1, 1, 1, 2, 4, 16), 3),           # 256-channel chunks, ring of stages wraps
+    (L("f8_1x1_cin512_s2", 15, 15, 512, 144, 1, 1, 2, 0, 1, 1, 4, 16), 2),     # 1, 2 or 4 ... 8 chunks by chunk size
 ]
 
 
@@ -81,13 +85,16 @@ def test_fp8_conv_every_variant(layer, batch, with_res):
     wp = nm.nm_prune(w, layer.n, layer.m, layer.tile, nm.NM_F8E4M3)
     rd = torch.from_numpy(res).cuda().to(torch.bfloat16) if with_res else None
     bd = torch.from_numpy(bias).cuda() if use_bias else None
-    ran = 0
+    ran, families = 0, set()
     try:
         for v in range(nm.nm_variant_count()):
             if not nm.nm_variant_legal(v, wp, nm.NM_F8E4M3, nm.NM_BF16):
                 continue
             name = nm.nm_variant_name(v)
-            assert name.startswith("F8_")
+            # F8: register-streaming kernel; F8S / F8W / F8R: the LDS-staged one, plain, with producer
+            # wavefronts, with producer wavefronts and register-held weights
+            assert re.match(r"F8[SWR]?_NB", name)
+            families.add(name.split("_")[0])
             say(f"forced {name} on {layer.name} residual={with_res}")
             nm.nm_force_variant(v)
             y = nm.nm_conv2d_res(xd, wp, rd, bd, layer.stride, layer.pad, layer.dil, relu)
@@ -97,7 +104,7 @@ def test_fp8_conv_every_variant(layer, batch, with_res):
             ran += 1
     finally:
         nm.nm_force_variant(-1)
-    assert ran >= 10
+    assert ran >= 10 and families == {"F8", "F8S", "F8W", "F8R"}
     y = nm.nm_conv2d_res(xd, wp, rd, bd, layer.stride, layer.pad, layer.dil, relu)    # the untuned default
     torch.cuda.synchronize()
     assert norm_err(y.float().cpu().numpy(), ref) <= BF16_TOL
