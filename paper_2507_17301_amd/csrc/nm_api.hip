@@ -1050,7 +1050,7 @@ int nm_autotune(nm_dtype_t xdt, int b, int h, int w, int cin, const nm_packed_t*
         return ms / reps;
     };
     // First pass: every legal variant, one warm-up launch (code object, attributes) and the
-    // median of three groups.  Second pass: the five fastest again, interleaved so that clock
+    // median of three groups.  Second pass: the five fastest (up to ten if that close) again, interleaved so that clock
     // and cache drift hit them alike, median of seven groups -- single passes were seen to
     // pick variants a few percent off the best from run to run.
     std::vector<std::pair<float, int>> first;
@@ -1075,7 +1075,10 @@ int nm_autotune(nm_dtype_t xdt, int b, int h, int w, int cin, const nm_packed_t*
                 wp->kh, wp->kw, b, wp->n, wp->m, wp->tile, first.size());
         for (const auto& c : first) fprintf(stderr, "  %9.2f us  %s\n", c.first * 1e3f, variant_desc(c.second).name);
     }
-    const int finalists = (int)std::min<size_t>(5, first.size());
+    // finalists: the five fastest, and whatever else came within 5 % of the fastest (at most ten)
+    int finalists = (int)std::min<size_t>(5, first.size());
+    while (finalists < (int)std::min<size_t>(10, first.size()) && first[finalists].first <= first[0].first * 1.05f)
+        ++finalists;
     std::vector<std::vector<float>> again(finalists);
     for (int r = 0; r < 7 && finalists > 1; ++r)
         for (int c = 0; c < finalists; ++c) {
