@@ -35,6 +35,10 @@
 // v_mfma_f32_16x16x32_fp8_fp8 -- bytes 0-7 the first, bytes 8-15 the second; operands are 8 bytes per
 // lane, lane i + 16 q holding K positions 8 q .. 8 q + 7, and which channel a K position stands
 // for is free as long as both operands agree -- against weights that nm_prune lays out to match.
+// With chunks of 128 channels or more, two k-steps go into one v_mfma_f32_16x16x128_f8f6f4 (both
+// operands 32 bytes per lane: the two k-steps' 16 bytes, same pairing of lane group and byte on
+// both sides; checked on the device against a plain product): twice the rate of the 32-deep
+// instruction, which is what the late layers' K loops are bound by.
 // The accumulators start from zero and are scaled back by the layer's weight scale before the
 // bias is added.
 #pragma once
@@ -72,6 +76,12 @@ constexpr int sp16_stage_bytes(int BP, int CK, int NJ, bool sparse, bool areg = 
 __device__ inline int sp16_swz(int row, int RB)
 {
     return RB == 64 ? ((row >> 1) & 3) : RB == 128 ? ((row & 7) ^ ((row >> 3) & 1)) : (row & 15);
+}
+// two 16-byte operands side by side, as the 128-deep fp8 matrix instruction takes them
+typedef int i8v __attribute__((ext_vector_type(8)));
+__device__ inline i8v sp16_pair(const u4v& lo, const u4v& hi)
+{
+    return i8v{(int)lo.x, (int)lo.y, (int)lo.z, (int)lo.w, (int)hi.x, (int)hi.y, (int)hi.z, (int)hi.w};
 }
 // one 8-byte half of a 16-byte operand, as the fp8 matrix instruction takes it
 __device__ inline long sp16_half(const u4v& v, int h)
@@ -119,9 +129,10 @@ __global__ __launch_bounds__(SPEC ? 512 : 256) void nm_conv_sp16_kernel(const Co
     constexpr int BPW = 16 * NBLK;
     constexpr int BP = BPW * WP;
     constexpr int WC = 4 / WP;
-    constexpr int KS = CK / 64;                  // k-steps (64 channels) per chunk
-    constexpr int AH = (SPARSE || F8) ? 1 : 2;   // 16-byte A operands per k-step and row block
-    constexpr int BH = F8 ? 1 : 2;               // 16-byte strip reads per k-step and pixel block
+    constexpr bool F8X = F8 && CK % 128 == 0;    // fp8 with 128-channel k-steps (one 128-deep instruction each)
+    constexpr int KS = F8X ? CK / 128 : CK / 64; // k-steps (64 channels; 128 for F8X) per chunk
+    constexpr int AH = (SPARSE || (F8 && !F8X)) ? 1 : 2;   // 16-byte A operands per k-step and row block
+    constexpr int BH = (F8 && !F8X) ? 1 : 2;     // 16-byte strip reads per k-step and pixel block
     constexpr int RB = CK * ES;                  // bytes per pixel row of a stage
     const int D = p.nchunks < kSp16Stages ? p.nchunks : kSp16Stages;   // stages in use (and allocated)
     constexpr int STAGE = sp16_stage_bytes(BP, CK, NJ, SPARSE, AREG, F8);
@@ -257,14 +268,15 @@ __global__ __launch_bounds__(SPEC ? 512 : 256) void nm_conv_sp16_kernel(const Co
     };
 
     // this lane's operand granules inside block 0 of a stage: k-step s, half h
-    // (bf16: granules 2 q and 2 q + 1 of the k-step's eight; fp8: granule q of its four)
+    // (bf16: granules 2 q and 2 q + 1 of the k-step's eight; fp8: granule q of its four, and for
+    // 128-channel k-steps granule q of either half)
     unsigned roff[KS][BH];
 #pragma unroll
     for (int s = 0; s < KS; ++s)
 #pragma unroll
         for (int h = 0; h < BH; ++h)
             roff[s][h] = (unsigned)((wpix + n) * RB +
-                                    (((F8 ? s * 4 + q : s * 8 + q * 2 + h) ^ sp16_swz(n, RB)) * 16));
+                                    (((F8X ? (2 * s + h) * 4 + q : F8 ? s * 4 + q : s * 8 + q * 2 + h) ^ sp16_swz(n, RB)) * 16));
 
     // The memory counter retires loads in order, so "at most one stage's loads
     // outstanding" means that the stage before it has landed.
@@ -423,6 +435,9 @@ __global__ __launch_bounds__(SPEC ? 512 : 256) void nm_conv_sp16_kernel(const Co
                                                              5, 6, 7, 8, 9, 10, 11, 12, 13, 14, 15);
                     acc[jj][b] = __builtin_amdgcn_smfmac_f32_16x16x64_bf16(
                         __builtin_bit_cast(bf8x, a[jj][s][0]), bv, acc[jj][b], (int)idx[jj][s], 0, 0);
+                } else if constexpr (F8X) {
+                    acc[jj][b] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(
+                        sp16_pair(a[jj][s][0], a[jj][s][AH - 1]), sp16_pair(bo[0], bo[BH - 1]), acc[jj][b], 0, 0, 0, 0, 0, 0);
                 } else if constexpr (F8) {
 #pragma unroll
                     for (int h = 0; h < 2; ++h)
@@ -502,6 +517,9 @@ __global__ __launch_bounds__(SPEC ? 512 : 256) void nm_conv_sp16_kernel(const Co
                                                                  5, 6, 7, 8, 9, 10, 11, 12, 13, 14, 15);
                         acc[jj][b] = __builtin_amdgcn_smfmac_f32_16x16x64_bf16(
                             __builtin_bit_cast(bf8x, o.a[jj][s2][0]), bv, acc[jj][b], (int)o.idx[jj][s2], 0, 0);
+                    } else if constexpr (F8X) {
+                        acc[jj][b] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(
+                            sp16_pair(o.a[jj][s2][0], o.a[jj][s2][AH - 1]), sp16_pair(bo[0], bo[BH - 1]), acc[jj][b], 0, 0, 0, 0, 0, 0);
                     } else if constexpr (F8) {
 #pragma unroll
                         for (int h = 0; h < 2; ++h)
