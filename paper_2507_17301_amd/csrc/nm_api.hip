@@ -315,8 +315,40 @@ void fill_params(ConvParams& p, const VariantDesc& d, const Prepack& pp, const n
 // Deterministic default when the shape has not been tuned: a small model of
 // "rounds of workgroups x work per workgroup", preferring tiles that fill the
 // 256 CUs and reuse the staged strip across many row blocks.
+//
+// For the gather-free bf16 and the staged fp8 kernels the model is replaced by a rule read off
+// tuned ResNet stacks (the model's picks ran x1.46 behind the tuned ones there): a tile of 128
+// pixels x 128 channels (64 pixels where that leaves under half the CUs a workgroup, 64 channels
+// where the layer has no more), all four wavefronts along the channels; producer wavefronts and
+// register-held weights unless the launch is many rounds of workgroups on a 1x1 layer; 128-channel
+// chunks on deep, small layers, 64 otherwise.  Variants are ranked by their distance from that.
 int heuristic_variant(const nm_packed* wp, int P, nm_dtype_t xdt, const RunArgs* ra)
 {
+    {
+        const long wg128 = (long)((P + 127) / 128) * ((wp->n_rowblocks + 7) / 8);
+        const int bp_t = wg128 >= kNumCU / 2 ? 128 : 64;
+        const int wgc_t = wp->n_rowblocks >= 8 ? 128 : 64;
+        const long n_wg_t = (long)((P + bp_t - 1) / bp_t) * ((wp->n_rowblocks * 16 + wgc_t - 1) / wgc_t);
+        const bool plain_t = wp->kh * wp->kw == 1 && n_wg_t >= 4L * kNumCU;
+        const int ck_t = (wp->cin >= 256 && n_wg_t <= 2L * kNumCU) ? 128 : 64;
+        auto lg = [](double a, double b) { return fabs(log2(a / b)); };
+        int pick = -1;
+        double pick_score = 0;
+        for (int v = 0; v < variant_count(); ++v) {
+            const VariantDesc& d = variant_desc(v);
+            if (d.kind != 2 && d.kind != 3 && d.kind != 7) continue;
+            if (!variant_legal(v, wp, xdt, ra)) continue;
+            const int wgc = (4 / d.WP) * d.NJ * 16;
+            double score = 4.0 * lg(d.BP, bp_t) + 4.0 * lg(wgc, wgc_t) + 1.0 * lg(d.CK, ck_t) + (d.WP != 1 ? 1.5 : 0.0);
+            score += d.kind == 3 ? 6.0 : 0.0;                       // the sparse instruction where its operand exists
+            score += plain_t ? (d.spec ? 2.0 : 0.0) : (d.areg ? 0.0 : d.spec ? 1.0 : 3.0);
+            if (pick < 0 || score < pick_score - 1e-9) {
+                pick = v;
+                pick_score = score;
+            }
+        }
+        if (pick >= 0) return pick;
+    }
     int best = -1;
     double best_cost = 0;
     for (int v = 0; v < variant_count(); ++v) {

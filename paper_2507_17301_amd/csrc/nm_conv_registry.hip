@@ -32,13 +32,13 @@ struct Entry {
 #define NM_SHAPE_ENTRIESSP(NB, WP, NJ) NMSP_CHUNKS(NM_ENTRYSP, NB, WP, NJ)
 // the same with producer wavefronts (same operand tables, same LDS footprint)
 #define NM_ENTRYSPW(NB, WP, NJ, CK, SP)                                                         \
-    {{"SPW" #SP "_NB" #NB "_WP" #WP "_NJ" #NJ "_CK" #CK, 16 * NB * WP, NB, WP, NJ, CK, CK / 64, 1, (SP) ? 2 : 3, 1, 1, 0}, \
+    {{"SPW" #SP "_NB" #NB "_WP" #WP "_NJ" #NJ "_CK" #CK, 16 * NB * WP, NB, WP, NJ, CK, CK / 64, 1, (SP) ? 2 : 3, 1, 1, 0, 1}, \
      nullptr, &launch_sp16_t<NB, WP, NJ, CK, (SP) != 0, true>},
 #define NM_SHAPE_ENTRIESSPW(NB, WP, NJ) NMSPW_CHUNKS(NM_ENTRYSPW, NB, WP, NJ)
 
 // producer wavefronts and register operands
 #define NM_ENTRYSPR(NB, WP, NJ, CK, SP)                                                         \
-    {{"SPR" #SP "_NB" #NB "_WP" #WP "_NJ" #NJ "_CK" #CK, 16 * NB * WP, NB, WP, NJ, CK, CK / 64, 1, (SP) ? 2 : 3, 1, 1, 1}, \
+    {{"SPR" #SP "_NB" #NB "_WP" #WP "_NJ" #NJ "_CK" #CK, 16 * NB * WP, NB, WP, NJ, CK, CK / 64, 1, (SP) ? 2 : 3, 1, 1, 1, 1}, \
      nullptr, &launch_sp16_t<NB, WP, NJ, CK, (SP) != 0, true, true>},
 #define NM_SHAPE_ENTRIESSPR(NB, WP, NJ) NMSPR_CHUNKS(NM_ENTRYSPR, NB, WP, NJ)
 
@@ -63,9 +63,9 @@ struct Entry {
 #define NM_ENTRYF8S(NB, WP, NJ, CK)                                                                       \
     {{"F8S_NB" #NB "_WP" #WP "_NJ" #NJ "_CK" #CK, 16 * NB * WP, NB, WP, NJ, CK, CK / 64, 1, 7, 1, 1, 0}, \
      nullptr, &launch_sp16_t<NB, WP, NJ, CK, false, false, false, true>},                                 \
-    {{"F8W_NB" #NB "_WP" #WP "_NJ" #NJ "_CK" #CK, 16 * NB * WP, NB, WP, NJ, CK, CK / 64, 1, 7, 1, 1, 0}, \
+    {{"F8W_NB" #NB "_WP" #WP "_NJ" #NJ "_CK" #CK, 16 * NB * WP, NB, WP, NJ, CK, CK / 64, 1, 7, 1, 1, 0, 1}, \
      nullptr, &launch_sp16_t<NB, WP, NJ, CK, false, true, false, true>},                                  \
-    {{"F8R_NB" #NB "_WP" #WP "_NJ" #NJ "_CK" #CK, 16 * NB * WP, NB, WP, NJ, CK, CK / 64, 1, 7, 1, 1, 1}, \
+    {{"F8R_NB" #NB "_WP" #WP "_NJ" #NJ "_CK" #CK, 16 * NB * WP, NB, WP, NJ, CK, CK / 64, 1, 7, 1, 1, 1, 1}, \
      nullptr, &launch_sp16_t<NB, WP, NJ, CK, false, true, true, true>},
 #define NM_SHAPE_ENTRIESF8S(NB, WP, NJ) NMF8S_CHUNKS(NM_ENTRYF8S, NB, WP, NJ)
 

@@ -178,7 +178,8 @@ struct VariantDesc {
                // 6 = fp8 E4M3 kernel (fp8 activations, bf16 output): dense instruction on zero-filled weights
     int share; // kind 1: row blocks fed from one gathered operand
     int ksplit; // kinds 0, 5: workgroups that share the K axis of one output tile (1 = no split)
-    int areg;  // kinds 2, 3: 1 = weights and index words go straight to registers, the LDS stages hold the strip alone
+    int areg;  // kinds 2, 3, 7: 1 = weights and index words go straight to registers, the LDS stages hold the strip alone
+    int spec;  // kinds 2, 3, 7: 1 = four producer wavefronts issue the loads (512 threads)
 };
 
 // Allows kernel `fn` more than 64 KB of dynamic LDS on the current device; done once per
