@@ -1088,11 +1088,11 @@ int nm_autotune(nm_dtype_t xdt, int b, int h, int w, int cin, const nm_packed_t*
     std::vector<std::pair<float, int>> first;
     for (int v = 0; v < variant_count(); ++v) {
         if (!variant_legal(v, wp, xdt, &ra)) continue;
-        {   // a K split is worth its second kernel only where the output tiles alone leave most CUs idle
+        {   // a K split is worth its second kernel only where the output tiles are one short, ragged round (at most two per CU)
             const VariantDesc& d = variant_desc(v);
             const long tiles = (long)((g.P + d.BP - 1) / d.BP) *
                                ((wp->n_rowblocks + (4 / d.WP) * d.NJ - 1) / ((4 / d.WP) * d.NJ));
-            if (d.ksplit > 1 && (tiles > kNumCU / 2 || tiles * d.ksplit > 4 * kNumCU)) continue;
+            if (d.ksplit > 1 && (tiles > 2 * kNumCU || tiles * d.ksplit > 8 * kNumCU)) continue;
         }
         if (time_group(v, 1) < 0.f) { cleanup(); return rc_t; }
         float t[3];
