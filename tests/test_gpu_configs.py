@@ -8,6 +8,7 @@ images {0, 1, B/2, B-1} -- images are independent, but pixel tiles cross image
 boundaries, hence the first, the last and the middle of the batch.
 """
 import dataclasses
+import re
 
 import numpy as np
 import pytest
@@ -103,6 +104,36 @@ def test_config4_resnet50_batch64_bf16_whole_batch(layer):
     i = R50.index(layer)
     say(f"config 4 bf16 batch 64 layer {i} {layer.name}, every output")
     _check_images(layer, 64, 4000 + i, True)
+
+
+@pytest.mark.parametrize("bf16", [False, True], ids=["fp32", "bf16"])
+def test_config4_resnet50_batch64_untuned_default(bf16):
+    """What a caller gets without tuning: with the cache empty, every unique shape of the stack runs
+    the library's default variant at the full batch; every output of images 0 and 63."""
+    import torch
+    nm.nm_cache_clear()
+    tol = BF16_TOL if bf16 else FP32_TOL
+    ndt = nm.NM_BF16 if bf16 else nm.NM_F32
+    picks = set()
+    for layer in wl.unique_shapes(R50):
+        i = R50.index(layer)
+        x, w, bias = wl.make_tensors(layer, 64, 4000 + i)
+        wp = nm.nm_prune(w, layer.n, layer.m, layer.tile, ndt)
+        xd = torch.from_numpy(x).cuda()
+        if bf16:
+            xd = xd.to(torch.bfloat16)
+        say(f"config 4 {'bf16' if bf16 else 'fp32'} batch 64 layer {i} {layer.name}, untuned default")
+        y = nm.nm_conv2d(xd, wp, torch.from_numpy(bias).cuda(), layer.stride, layer.pad, layer.dil, True)
+        torch.cuda.synchronize()
+        vname = nm.nm_variant_name(nm.nm_last_variant())
+        assert not re.search(r"_S\d+$", vname)   # the default never needs the K-split workspace
+        picks.add(vname.split("_")[0])
+        ref = oracle_conv(layer, x[[0, 63]], w, bias, relu=True, bf16=bf16)
+        got = y[torch.tensor([0, 63], device=y.device)].float().cpu().numpy()
+        for n_, b in enumerate((0, 63)):
+            assert norm_err(got[n_], ref[n_]) <= tol, f"{layer.name} {vname} image {b}"
+    if bf16:   # the gather-free kernels (and the kernel-row-run kernel for the first layer), not the fp32 path on bf16 data
+        assert picks <= {"SP1", "SPW1", "SPR1", "RUN"}, picks
 
 
 def test_config4_resnet50_batch64_large_groups():
